@@ -1,0 +1,240 @@
+"""ctypes binding of the C ABI in include/kfac.h: argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used as device memory; every arithmetic
+step runs in the HIP library.  There is no fallback: if the library is missing
+or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+KFAC_OK = 0
+KFAC_F32 = 0
+KFAC_BF16 = 1
+
+_i64 = ctypes.c_int64
+_f32 = ctypes.c_float
+_vp = ctypes.c_void_p
+_sz = ctypes.c_size_t
+
+
+class CurvatureItem(ctypes.Structure):
+    _fields_ = [("x", _vp), ("n_tokens", _i64), ("d", _i64), ("ldx", _i64), ("factor", _vp), ("ldf", _i64)]
+
+
+class InvertItem(ctypes.Structure):
+    _fields_ = [("factor", _vp), ("d", _i64), ("ldf", _i64), ("inv", _vp), ("ldi", _i64), ("info_dev", _vp)]
+
+
+class PreconditionItem(ctypes.Structure):
+    _fields_ = [("b_inv", _vp), ("d_out", _i64), ("ldb", _i64), ("a_inv", _vp), ("d_in", _i64), ("lda", _i64),
+                ("grad", _vp), ("ldg", _i64), ("out", _vp), ("ldo", _i64)]
+
+
+#: every symbol include/kfac.h declares, with its ctypes signature
+SIGNATURES = {
+    "kfac_curvature": (ctypes.c_int, [_vp, ctypes.c_int, _i64, _i64, _i64, _f32, _f32, _vp, _i64, _vp, _sz, _vp]),
+    "kfac_curvature_workspace": (_sz, [_i64, _i64, ctypes.c_int]),
+    "kfac_curvature_grouped": (ctypes.c_int, [ctypes.POINTER(CurvatureItem), _i64, ctypes.c_int, _f32, _f32, _vp, _sz, _vp]),
+    "kfac_curvature_grouped_workspace": (_sz, [ctypes.POINTER(CurvatureItem), _i64, ctypes.c_int]),
+    "kfac_invert": (ctypes.c_int, [_vp, _i64, _i64, _f32, _vp, _i64, _vp, _vp, _sz, _vp]),
+    "kfac_invert_workspace": (_sz, [_i64]),
+    "kfac_invert_batched": (ctypes.c_int, [ctypes.POINTER(InvertItem), _i64, _f32, _vp, _sz, _vp]),
+    "kfac_invert_batched_workspace": (_sz, [ctypes.POINTER(InvertItem), _i64]),
+    "kfac_precondition": (ctypes.c_int, [_vp, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
+    "kfac_precondition_workspace": (_sz, [_i64, _i64]),
+    "kfac_precondition_grouped": (ctypes.c_int, [ctypes.POINTER(PreconditionItem), _i64, _vp, _sz, _vp]),
+    "kfac_precondition_grouped_workspace": (_sz, [ctypes.POINTER(PreconditionItem), _i64]),
+    "kfac_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "kfac_version": (ctypes.c_int, []),
+}
+
+_lib = None
+
+
+class KfacError(RuntimeError):
+    pass
+
+
+def library_path():
+    return _build.LIB
+
+
+def load():
+    """Load the HIP library (built in-tree).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise KfacError("HIP library %s is missing: run paper_2211_14133_amd/build.py (there is no CPU fallback)" % path)
+        lib = ctypes.CDLL(path)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(status):
+    if status != KFAC_OK:
+        raise KfacError("kfac call failed: %s" % load().kfac_status_string(status).decode())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return KFAC_F32
+    if t.dtype == torch.bfloat16:
+        return KFAC_BF16
+    raise KfacError("unsupported activation dtype %s" % t.dtype)
+
+
+def _need_f32_matrix(t, name):
+    if not (t.is_cuda and t.dtype == torch.float32 and t.dim() == 2 and t.stride(1) == 1):
+        raise KfacError("%s must be a 2-D float32 device tensor with unit column stride" % name)
+
+
+def _workspace(nbytes, like, workspace):
+    if nbytes == 0:
+        return None, 0, None
+    if workspace is None:
+        workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=like.device)
+    ptr = (workspace.data_ptr() + 255) // 256 * 256
+    avail = workspace.numel() - (ptr - workspace.data_ptr())
+    return ctypes.c_void_p(ptr), avail, workspace
+
+
+def _curv_items(xs, factors):
+    arr = (CurvatureItem * len(xs))()
+    for i, (x, f) in enumerate(zip(xs, factors)):
+        if not (x.is_cuda and x.dim() == 2 and x.stride(1) == 1):
+            raise KfacError("x must be a 2-D device tensor [tokens, d] with unit column stride")
+        _need_f32_matrix(f, "factor")
+        if f.shape[0] != x.shape[1] or f.shape[1] != x.shape[1]:
+            raise KfacError("factor must be [d, d] for x [tokens, d]")
+        arr[i] = CurvatureItem(x.data_ptr(), x.shape[0], x.shape[1], x.stride(0), f.data_ptr(), f.stride(0))
+    return arr
+
+
+def kfac_curvature(x, factor, alpha, beta, workspace=None, stream=None):
+    """factor = beta * factor + alpha * x^T x  (one factor, one micro-batch)."""
+    lib = load()
+    _curv_items([x], [factor])
+    dt = _dtype_code(x)
+    need = lib.kfac_curvature_workspace(x.shape[0], x.shape[1], dt)
+    ws, nbytes, keep = _workspace(need, x, workspace)
+    _check(lib.kfac_curvature(ctypes.c_void_p(x.data_ptr()), dt, x.shape[0], x.shape[1], x.stride(0),
+                              alpha, beta, ctypes.c_void_p(factor.data_ptr()), factor.stride(0),
+                              ws, nbytes, _stream(stream)))
+    return factor
+
+
+def kfac_curvature_grouped_workspace(xs, factors):
+    arr = _curv_items(xs, factors)
+    return int(load().kfac_curvature_grouped_workspace(arr, len(xs), _dtype_code(xs[0])))
+
+
+def kfac_curvature_grouped(xs, factors, alpha, beta, workspace=None, stream=None):
+    """Many independent curvature items with a common alpha / beta."""
+    lib = load()
+    arr = _curv_items(xs, factors)
+    dt = _dtype_code(xs[0])
+    need = lib.kfac_curvature_grouped_workspace(arr, len(xs), dt)
+    ws, nbytes, keep = _workspace(need, xs[0], workspace)
+    _check(lib.kfac_curvature_grouped(arr, len(xs), dt, alpha, beta, ws, nbytes, _stream(stream)))
+    return factors
+
+
+def _inv_items(factors, invs, infos):
+    arr = (InvertItem * len(factors))()
+    for i, (f, v) in enumerate(zip(factors, invs)):
+        _need_f32_matrix(f, "factor")
+        _need_f32_matrix(v, "inv")
+        if f.shape[0] != f.shape[1] or v.shape != f.shape:
+            raise KfacError("factor and inv must be square and of equal shape")
+        arr[i] = InvertItem(f.data_ptr(), f.shape[0], f.stride(0), v.data_ptr(), v.stride(0),
+                            infos.data_ptr() + 4 * i)
+    return arr
+
+
+def kfac_invert(factor, damping, inv, info=None, workspace=None, stream=None):
+    """inv = (factor + damping I)^-1; returns the device int32 status tensor."""
+    lib = load()
+    if info is None:
+        info = torch.zeros(1, dtype=torch.int32, device=factor.device)
+    _inv_items([factor], [inv], info)
+    need = lib.kfac_invert_workspace(factor.shape[0])
+    ws, nbytes, keep = _workspace(need, factor, workspace)
+    _check(lib.kfac_invert(ctypes.c_void_p(factor.data_ptr()), factor.shape[0], factor.stride(0), damping,
+                           ctypes.c_void_p(inv.data_ptr()), inv.stride(0), ctypes.c_void_p(info.data_ptr()),
+                           ws, nbytes, _stream(stream)))
+    return info
+
+
+def kfac_invert_batched_workspace(factors, invs):
+    infos = torch.zeros(len(factors), dtype=torch.int32, device=factors[0].device)
+    arr = _inv_items(factors, invs, infos)
+    return int(load().kfac_invert_batched_workspace(arr, len(factors)))
+
+
+def kfac_invert_batched(factors, damping, invs, infos=None, workspace=None, stream=None):
+    """All inversions of a stage advanced together; returns the int32 status tensor [count]."""
+    lib = load()
+    if infos is None:
+        infos = torch.zeros(len(factors), dtype=torch.int32, device=factors[0].device)
+    arr = _inv_items(factors, invs, infos)
+    need = lib.kfac_invert_batched_workspace(arr, len(factors))
+    ws, nbytes, keep = _workspace(need, factors[0], workspace)
+    _check(lib.kfac_invert_batched(arr, len(factors), damping, ws, nbytes, _stream(stream)))
+    return infos
+
+
+def _prec_items(b_invs, a_invs, grads, outs):
+    arr = (PreconditionItem * len(grads))()
+    for i, (b, a, g, o) in enumerate(zip(b_invs, a_invs, grads, outs)):
+        for t, nm in ((b, "b_inv"), (a, "a_inv"), (g, "grad"), (o, "out")):
+            _need_f32_matrix(t, nm)
+        d_out, d_in = g.shape
+        if b.shape != (d_out, d_out) or a.shape != (d_in, d_in) or o.shape != g.shape:
+            raise KfacError("shape mismatch: grad [d_out, d_in], b_inv [d_out, d_out], a_inv [d_in, d_in]")
+        arr[i] = PreconditionItem(b.data_ptr(), d_out, b.stride(0), a.data_ptr(), d_in, a.stride(0),
+                                  g.data_ptr(), g.stride(0), o.data_ptr(), o.stride(0))
+    return arr
+
+
+def kfac_precondition(b_inv, a_inv, grad, out, workspace=None, stream=None):
+    """out = b_inv @ grad @ a_inv for one layer."""
+    lib = load()
+    _prec_items([b_inv], [a_inv], [grad], [out])
+    d_out, d_in = grad.shape
+    need = lib.kfac_precondition_workspace(d_out, d_in)
+    ws, nbytes, keep = _workspace(need, grad, workspace)
+    _check(lib.kfac_precondition(ctypes.c_void_p(b_inv.data_ptr()), d_out, b_inv.stride(0),
+                                 ctypes.c_void_p(a_inv.data_ptr()), d_in, a_inv.stride(0),
+                                 ctypes.c_void_p(grad.data_ptr()), grad.stride(0),
+                                 ctypes.c_void_p(out.data_ptr()), out.stride(0), ws, nbytes, _stream(stream)))
+    return out
+
+
+def kfac_precondition_grouped_workspace(b_invs, a_invs, grads, outs):
+    arr = _prec_items(b_invs, a_invs, grads, outs)
+    return int(load().kfac_precondition_grouped_workspace(arr, len(grads)))
+
+
+def kfac_precondition_grouped(b_invs, a_invs, grads, outs, workspace=None, stream=None):
+    """All layers of a stage in two launches."""
+    lib = load()
+    arr = _prec_items(b_invs, a_invs, grads, outs)
+    need = lib.kfac_precondition_grouped_workspace(arr, len(grads))
+    ws, nbytes, keep = _workspace(need, grads[0], workspace)
+    _check(lib.kfac_precondition_grouped(arr, len(grads), ws, nbytes, _stream(stream)))
+    return outs

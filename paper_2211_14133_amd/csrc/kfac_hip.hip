@@ -1,0 +1,550 @@
+// C ABI of the K-FAC work-item library (see include/kfac.h) and the host-side
+// drivers that turn each work item into launches of the TN contraction engine
+// and of the diagonal-block kernel.  Everything runs on the caller's stream;
+// nothing here allocates, frees or synchronises.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+#include "../../include/kfac.h"
+#include "diag_block.h"
+#include "tn_gemm.h"
+
+using namespace kfac;
+
+namespace {
+
+constexpr size_t WS_ALIGN = 256;
+constexpr int TARGET_TILES = 512;  // 256 CUs x 2 resident workgroups
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline bool fits_int(int64_t v) { return v > 0 && v < (int64_t(1) << 30); }
+
+inline bool ws_ok(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return true;
+    return ws != nullptr && have >= need && (reinterpret_cast<uintptr_t>(ws) % WS_ALIGN) == 0;
+}
+
+// Collects problems that share the launch parameters and sends them to the
+// engine in chunks of at most TN_MAX_PROBLEMS.
+struct TnBatch {
+    std::vector<TnProblem> probs;
+    int tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE, splits = 1;
+    float alpha = 1.f, beta = 0.f;
+    float *partial = nullptr;
+
+    void add(const float *A, int lda, const float *B, int ldb, float *C, int ldc, int M, int N, int K,
+             float *Ct = nullptr, int ldct = 0, const int *guard = nullptr)
+    {
+        if (M <= 0 || N <= 0) return;
+        TnProblem p;
+        p.A = A; p.B = B; p.C = C; p.Ct = Ct; p.guard = guard;
+        p.M = M; p.N = N; p.K = K;
+        p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.ldct = ldct;
+        p.tile_begin = 0;
+        probs.push_back(p);
+    }
+
+    hipError_t launch(hipStream_t stream)
+    {
+        size_t i = 0;
+        while (i < probs.size()) {
+            TnLaunch lp;
+            std::memset(&lp, 0, sizeof(lp));
+            int tiles = 0, cnt = 0;
+            while (i < probs.size() && cnt < TN_MAX_PROBLEMS) {
+                lp.p[cnt] = probs[i];
+                lp.p[cnt].tile_begin = tiles;
+                tiles += tn_tiles(probs[i].M, probs[i].N, tile_mode) * splits;
+                ++cnt;
+                ++i;
+            }
+            lp.count = cnt;
+            lp.tile_mode = tile_mode;
+            lp.mask_a = mask_a;
+            lp.mask_b = mask_b;
+            lp.splits = splits;
+            lp.alpha = alpha;
+            lp.beta = beta;
+            lp.partial = partial;
+            hipLaunchKernelGGL(tn_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, stream, lp);
+            if (splits > 1)
+                hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / splits), dim3(TN_THREADS), 0, stream, lp);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        probs.clear();
+        return hipSuccess;
+    }
+};
+
+// Split-K factor for a launch with `tiles` output tiles and K rows: enough
+// splits to give every CU two workgroups, each split at least 256 rows long.
+inline int choose_splits(int64_t tiles, int64_t K)
+{
+    if (tiles >= TARGET_TILES) return 1;
+    const int64_t by_tiles = (TARGET_TILES + tiles - 1) / tiles;
+    const int64_t by_k = std::max<int64_t>(1, K / 256);
+    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(by_tiles, by_k), 32));
+}
+
+// ------------------------------------------------------------------ curvature
+
+struct CurvPlan {
+    int splits;
+    int64_t tiles;  // output tiles of all items
+    size_t ws;
+};
+
+bool curvature_plan(const kfac_curvature_item *items, int64_t count, CurvPlan &pl)
+{
+    int64_t tiles = 0, kmin = INT64_MAX;
+    for (int64_t i = 0; i < count; ++i) {
+        if (!fits_int(items[i].d) || !fits_int(items[i].n_tokens)) return false;
+        tiles += tn_tiles((int)items[i].d, (int)items[i].d, TILE_LOWER);
+        kmin = std::min(kmin, items[i].n_tokens);
+    }
+    // a launch holds at most TN_MAX_PROBLEMS items; size the split for one launch
+    const int64_t launches = (count + TN_MAX_PROBLEMS - 1) / TN_MAX_PROBLEMS;
+    pl.splits = choose_splits(std::max<int64_t>(1, tiles / std::max<int64_t>(1, launches)), kmin);
+    pl.tiles = tiles;
+    pl.ws = pl.splits > 1 ? align_up((size_t)tiles * pl.splits * BM * BN * sizeof(float), WS_ALIGN) : 0;
+    return true;
+}
+
+// ------------------------------------------------------------------ inversion
+
+inline int work_ld(int64_t d) { return (int)align_up((size_t)d, 32); }
+
+inline size_t invert_item_bytes(int64_t d)
+{
+    return 2 * align_up((size_t)d * work_ld(d) * sizeof(float), WS_ALIGN);
+}
+
+struct InvMat {
+    float *F, *S;
+    int d, ld, nblk;
+    float *inv;
+    int ldi;
+    int *info;
+};
+
+struct TriNode {
+    int mat, r0, b1, b2;
+};
+
+// Balanced splitting of block range [lo, hi): returns the height of the node and
+// files it under that height.  Nodes of equal height are independent.
+int build_tree(int mat, int lo, int hi, int d, std::vector<std::vector<TriNode>> &levels)
+{
+    if (hi - lo <= 1) return 0;
+    const int mid = lo + (hi - lo + 1) / 2;
+    const int hl = build_tree(mat, lo, mid, d, levels);
+    const int hr = build_tree(mat, mid, hi, d, levels);
+    const int h = 1 + std::max(hl, hr);
+    if ((int)levels.size() <= h) levels.resize(h + 1);
+    TriNode nd;
+    nd.mat = mat;
+    nd.r0 = lo * NB;
+    nd.b1 = (mid - lo) * NB;
+    nd.b2 = std::min(hi * NB, d) - mid * NB;
+    levels[h].push_back(nd);
+    return h;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *kfac_status_string(kfac_status s)
+{
+    switch (s) {
+        case KFAC_OK: return "ok";
+        case KFAC_ERR_ARG: return "invalid argument";
+        case KFAC_ERR_UNSUPPORTED: return "unsupported dtype or option";
+        case KFAC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case KFAC_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+int kfac_version(void) { return 100; }
+
+// ------------------------------------------------------------------ curvature
+
+size_t kfac_curvature_grouped_workspace(const kfac_curvature_item *items, int64_t count, kfac_dtype dtype)
+{
+    (void)dtype;
+    if (items == nullptr || count <= 0) return 0;
+    CurvPlan pl;
+    if (!curvature_plan(items, count, pl)) return 0;
+    return pl.ws;
+}
+
+kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t count, kfac_dtype dtype,
+                                   float alpha, float beta, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count == 0) return KFAC_OK;
+    if (items == nullptr || count < 0) return KFAC_ERR_ARG;
+    if (dtype != KFAC_F32 && dtype != KFAC_BF16) return KFAC_ERR_ARG;
+    for (int64_t i = 0; i < count; ++i) {
+        const kfac_curvature_item &it = items[i];
+        if (it.x == nullptr || it.factor == nullptr) return KFAC_ERR_ARG;
+        if (!fits_int(it.d) || !fits_int(it.n_tokens)) return KFAC_ERR_ARG;
+        if (it.ldx < it.d || it.ldf < it.d || !fits_int(it.ldx) || !fits_int(it.ldf)) return KFAC_ERR_ARG;
+        if ((reinterpret_cast<uintptr_t>(it.x) & 3) || (reinterpret_cast<uintptr_t>(it.factor) & 3)) return KFAC_ERR_ARG;
+    }
+    if (dtype != KFAC_F32) return KFAC_ERR_UNSUPPORTED;
+    CurvPlan pl;
+    if (!curvature_plan(items, count, pl)) return KFAC_ERR_ARG;
+    if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;
+
+    TnBatch b;
+    b.tile_mode = TILE_LOWER;
+    b.splits = pl.splits;
+    b.alpha = alpha;
+    b.beta = beta;
+    b.partial = static_cast<float *>(workspace);
+    // one launch per TN_MAX_PROBLEMS items; the partial buffer is indexed per launch, so
+    // give each launch its own slice
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    size_t done = 0;
+    float *part = static_cast<float *>(workspace);
+    while (done < (size_t)count) {
+        const size_t n = std::min<size_t>(TN_MAX_PROBLEMS, (size_t)count - done);
+        int64_t tiles = 0;
+        for (size_t i = done; i < done + n; ++i) {
+            const kfac_curvature_item &it = items[i];
+            const float *x = static_cast<const float *>(it.x);
+            b.add(x, (int)it.ldx, x, (int)it.ldx, it.factor, (int)it.ldf, (int)it.d, (int)it.d, (int)it.n_tokens,
+                  it.factor, (int)it.ldf);
+            tiles += tn_tiles((int)it.d, (int)it.d, TILE_LOWER);
+        }
+        b.partial = part;
+        if (b.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+        if (pl.splits > 1) part += (size_t)tiles * pl.splits * BM * BN;
+        done += n;
+    }
+    return KFAC_OK;
+}
+
+size_t kfac_curvature_workspace(int64_t n_tokens, int64_t d, kfac_dtype dtype)
+{
+    kfac_curvature_item it;
+    std::memset(&it, 0, sizeof(it));
+    it.n_tokens = n_tokens;
+    it.d = d;
+    return kfac_curvature_grouped_workspace(&it, 1, dtype);
+}
+
+kfac_status kfac_curvature(const void *x, kfac_dtype dtype, int64_t n_tokens, int64_t d, int64_t ldx,
+                           float alpha, float beta, float *factor, int64_t ldf,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    kfac_curvature_item it;
+    it.x = x;
+    it.n_tokens = n_tokens;
+    it.d = d;
+    it.ldx = ldx;
+    it.factor = factor;
+    it.ldf = ldf;
+    return kfac_curvature_grouped(&it, 1, dtype, alpha, beta, workspace, workspace_bytes, stream);
+}
+
+// ------------------------------------------------------------------ inversion
+
+size_t kfac_invert_batched_workspace(const kfac_invert_item *items, int64_t count)
+{
+    if (items == nullptr || count <= 0) return 0;
+    size_t total = 0;
+    for (int64_t i = 0; i < count; ++i) {
+        if (!fits_int(items[i].d)) return 0;
+        total += invert_item_bytes(items[i].d);
+    }
+    return total;
+}
+
+size_t kfac_invert_workspace(int64_t d)
+{
+    return fits_int(d) ? invert_item_bytes(d) : 0;
+}
+
+kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, float damping,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count == 0) return KFAC_OK;
+    if (items == nullptr || count < 0) return KFAC_ERR_ARG;
+    if (!(damping >= 0.f)) return KFAC_ERR_ARG;
+    for (int64_t i = 0; i < count; ++i) {
+        const kfac_invert_item &it = items[i];
+        if (it.factor == nullptr || it.inv == nullptr || it.info_dev == nullptr) return KFAC_ERR_ARG;
+        if (!fits_int(it.d) || it.ldf < it.d || it.ldi < it.d || !fits_int(it.ldf) || !fits_int(it.ldi)) return KFAC_ERR_ARG;
+        if ((reinterpret_cast<uintptr_t>(it.factor) & 3) || (reinterpret_cast<uintptr_t>(it.inv) & 3) ||
+            (reinterpret_cast<uintptr_t>(it.info_dev) & 3))
+            return KFAC_ERR_ARG;
+        if (static_cast<const void *>(it.factor) == static_cast<const void *>(it.inv)) return KFAC_ERR_ARG;
+    }
+    const size_t need = kfac_invert_batched_workspace(items, count);
+    if (!ws_ok(workspace, workspace_bytes, need)) return KFAC_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    std::vector<InvMat> mats((size_t)count);
+    char *cur = static_cast<char *>(workspace);
+    int max_blk = 0;
+    for (int64_t i = 0; i < count; ++i) {
+        InvMat &m = mats[(size_t)i];
+        m.d = (int)items[i].d;
+        m.ld = work_ld(m.d);
+        const size_t one = align_up((size_t)m.d * m.ld * sizeof(float), WS_ALIGN);
+        m.F = reinterpret_cast<float *>(cur);
+        m.S = reinterpret_cast<float *>(cur + one);
+        cur += 2 * one;
+        m.nblk = (m.d + NB - 1) / NB;
+        m.inv = items[i].inv;
+        m.ldi = (int)items[i].ldi;
+        m.info = items[i].info_dev;
+        max_blk = std::max(max_blk, m.nblk);
+    }
+
+    // 1. info = 0; working copy F = factor + damping I.
+    for (size_t i0 = 0; i0 < mats.size(); i0 += PREP_MAX_ITEMS) {
+        const size_t n = std::min<size_t>(PREP_MAX_ITEMS, mats.size() - i0);
+        PrepLaunch pl;
+        std::memset(&pl, 0, sizeof(pl));
+        int dmax = 0;
+        for (size_t i = 0; i < n; ++i) {
+            const InvMat &m = mats[i0 + i];
+            pl.it[i].src = items[i0 + i].factor;
+            pl.it[i].dst = m.F;
+            pl.it[i].info = m.info;
+            pl.it[i].d = m.d;
+            pl.it[i].lds_ = (int)items[i0 + i].ldf;
+            pl.it[i].ldd = m.ld;
+            dmax = std::max(dmax, m.d);
+        }
+        pl.damping = damping;
+        hipLaunchKernelGGL(invert_clear_info_kernel, dim3(1), dim3(64), 0, st, pl, (int)n);
+        hipLaunchKernelGGL(invert_prepare_kernel, dim3(std::min(dmax, 512), (unsigned)n), dim3(256), 0, st, pl);
+    }
+    if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
+
+    // 2. Blocked upper Cholesky M = U^T U, right-looking, one panel of every matrix per step.
+    TnBatch trsm, syrk;
+    trsm.tile_mode = TILE_FULL;
+    trsm.mask_a = MASK_KEEP_K_LE;  // U_kk^-1 is upper triangular: rows k <= column
+    syrk.tile_mode = TILE_UPPER;
+    syrk.alpha = -1.f;
+    syrk.beta = 1.f;
+    for (int kb = 0; kb < max_blk; ++kb) {
+        std::vector<DiagItem> ditems;
+        for (const InvMat &m : mats) {
+            if (kb >= m.nblk) continue;
+            const int r0 = kb * NB;
+            const int n = std::min(NB, m.d - r0);
+            const int rest = m.d - r0 - n;
+            DiagItem di;
+            di.F = m.F + (size_t)r0 * m.ld + r0;
+            di.S = m.S + (size_t)r0 * m.ld + r0;
+            di.info = m.info;
+            di.n = n;
+            di.ldf = m.ld;
+            di.lds = m.ld;
+            di.pivot_base = r0;
+            ditems.push_back(di);
+            if (rest > 0) {
+                float *panel = m.F + (size_t)r0 * m.ld + r0 + n;                 // n x rest, becomes U12
+                float *below = m.F + (size_t)(r0 + n) * m.ld + r0;               // rest x n, mirror of U12
+                float *trail = m.F + (size_t)(r0 + n) * m.ld + r0 + n;           // rest x rest
+                trsm.add(di.S, m.ld, panel, m.ld, panel, m.ld, n, rest, n, below, m.ld);
+                syrk.add(panel, m.ld, panel, m.ld, trail, m.ld, rest, rest, n);
+            }
+        }
+        for (size_t i0 = 0; i0 < ditems.size(); i0 += DIAG_MAX_ITEMS) {
+            const size_t n = std::min<size_t>(DIAG_MAX_ITEMS, ditems.size() - i0);
+            DiagLaunch dl;
+            std::memset(&dl, 0, sizeof(dl));
+            for (size_t i = 0; i < n; ++i) dl.it[i] = ditems[i0 + i];
+            hipLaunchKernelGGL(diag_block_kernel, dim3((unsigned)n), dim3(DIAG_THREADS), 0, st, dl);
+        }
+        if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
+        if (trsm.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+        if (syrk.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+    }
+
+    // 3. W = U^-1 by pairwise merging of already inverted diagonal ranges:
+    //    [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
+    //    Y = U12 W22 goes where U12 was (the factor's upper blocks are no longer needed:
+    //    later merges read the mirrored copy below the diagonal).
+    std::vector<std::vector<TriNode>> levels;
+    for (size_t i = 0; i < mats.size(); ++i) build_tree((int)i, 0, mats[i].nblk, mats[i].d, levels);
+    TnBatch s1, s2;
+    s1.tile_mode = TILE_FULL;
+    s1.mask_b = MASK_KEEP_K_LE;  // W22 upper triangular
+    s2.tile_mode = TILE_FULL;
+    s2.mask_a = MASK_KEEP_K_GE;  // W11 read through its mirror below the diagonal
+    s2.alpha = -1.f;
+    for (size_t h = 1; h < levels.size(); ++h) {
+        for (const TriNode &nd : levels[h]) {
+            const InvMat &m = mats[(size_t)nd.mat];
+            const int c1 = nd.r0 + nd.b1;
+            const float *l21 = m.F + (size_t)c1 * m.ld + nd.r0;      // b2 x b1 = U12^T
+            const float *s22 = m.S + (size_t)c1 * m.ld + c1;         // b2 x b2
+            const float *s11 = m.S + (size_t)nd.r0 * m.ld + nd.r0;   // b1 x b1
+            float *y = m.F + (size_t)nd.r0 * m.ld + c1;              // b1 x b2
+            float *w12 = m.S + (size_t)nd.r0 * m.ld + c1;            // b1 x b2
+            float *w21 = m.S + (size_t)c1 * m.ld + nd.r0;            // b2 x b1 (mirror)
+            s1.add(l21, m.ld, s22, m.ld, y, m.ld, nd.b1, nd.b2, nd.b2);
+            s2.add(s11, m.ld, y, m.ld, w12, m.ld, nd.b1, nd.b2, nd.b1, w21, m.ld);
+        }
+        if (s1.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+        if (s2.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+    }
+
+    // 4. inv = W W^T, read through the mirror: inv[i][j] = sum_{k >= max(i,j)} S[k][i] S[k][j].
+    TnBatch lu;
+    lu.tile_mode = TILE_LOWER;
+    lu.mask_a = MASK_KEEP_K_GE;
+    lu.mask_b = MASK_KEEP_K_GE;
+    for (const InvMat &m : mats) lu.add(m.S, m.ld, m.S, m.ld, m.inv, m.ldi, m.d, m.d, m.d, m.inv, m.ldi, m.info);
+    if (lu.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+    return KFAC_OK;
+}
+
+kfac_status kfac_invert(const float *factor, int64_t d, int64_t ldf, float damping,
+                        float *inv, int64_t ldi, int32_t *info_dev,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    kfac_invert_item it;
+    it.factor = factor;
+    it.d = d;
+    it.ldf = ldf;
+    it.inv = inv;
+    it.ldi = ldi;
+    it.info_dev = info_dev;
+    return kfac_invert_batched(&it, 1, damping, workspace, workspace_bytes, stream);
+}
+
+// --------------------------------------------------------------- precondition
+
+namespace {
+struct PrecPlan {
+    int splits1, splits2;
+    size_t t_bytes, part_bytes, ws;
+};
+
+bool precondition_plan(const kfac_precondition_item *items, int64_t count, PrecPlan &pl)
+{
+    int64_t tiles1 = 0, tiles2 = 0, k1 = INT64_MAX, k2 = INT64_MAX;
+    size_t t_bytes = 0;
+    for (int64_t i = 0; i < count; ++i) {
+        if (!fits_int(items[i].d_out) || !fits_int(items[i].d_in)) return false;
+        const int dout = (int)items[i].d_out, din = (int)items[i].d_in;
+        tiles1 += tn_tiles(din, dout, TILE_FULL);
+        tiles2 += tn_tiles(dout, din, TILE_FULL);
+        k1 = std::min<int64_t>(k1, dout);
+        k2 = std::min<int64_t>(k2, din);
+        t_bytes += align_up((size_t)din * dout * sizeof(float), WS_ALIGN);
+    }
+    const int64_t launches = (count + TN_MAX_PROBLEMS - 1) / TN_MAX_PROBLEMS;
+    pl.splits1 = choose_splits(std::max<int64_t>(1, tiles1 / launches), k1);
+    pl.splits2 = choose_splits(std::max<int64_t>(1, tiles2 / launches), k2);
+    pl.t_bytes = t_bytes;
+    const size_t p1 = pl.splits1 > 1 ? (size_t)tiles1 * pl.splits1 * BM * BN * sizeof(float) : 0;
+    const size_t p2 = pl.splits2 > 1 ? (size_t)tiles2 * pl.splits2 * BM * BN * sizeof(float) : 0;
+    pl.part_bytes = align_up(std::max(p1, p2), WS_ALIGN);
+    pl.ws = pl.t_bytes + pl.part_bytes;
+    return true;
+}
+}  // namespace
+
+size_t kfac_precondition_grouped_workspace(const kfac_precondition_item *items, int64_t count)
+{
+    if (items == nullptr || count <= 0) return 0;
+    PrecPlan pl;
+    if (!precondition_plan(items, count, pl)) return 0;
+    return pl.ws;
+}
+
+size_t kfac_precondition_workspace(int64_t d_out, int64_t d_in)
+{
+    kfac_precondition_item it;
+    std::memset(&it, 0, sizeof(it));
+    it.d_out = d_out;
+    it.d_in = d_in;
+    return kfac_precondition_grouped_workspace(&it, 1);
+}
+
+kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64_t count,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count == 0) return KFAC_OK;
+    if (items == nullptr || count < 0) return KFAC_ERR_ARG;
+    for (int64_t i = 0; i < count; ++i) {
+        const kfac_precondition_item &it = items[i];
+        if (!it.b_inv || !it.a_inv || !it.grad || !it.out) return KFAC_ERR_ARG;
+        if (!fits_int(it.d_out) || !fits_int(it.d_in)) return KFAC_ERR_ARG;
+        if (it.ldb < it.d_out || it.lda < it.d_in || it.ldg < it.d_in || it.ldo < it.d_in) return KFAC_ERR_ARG;
+        if (!fits_int(it.ldb) || !fits_int(it.lda) || !fits_int(it.ldg) || !fits_int(it.ldo)) return KFAC_ERR_ARG;
+        if ((reinterpret_cast<uintptr_t>(it.b_inv) & 3) || (reinterpret_cast<uintptr_t>(it.a_inv) & 3) ||
+            (reinterpret_cast<uintptr_t>(it.grad) & 3) || (reinterpret_cast<uintptr_t>(it.out) & 3))
+            return KFAC_ERR_ARG;
+    }
+    PrecPlan pl;
+    if (!precondition_plan(items, count, pl)) return KFAC_ERR_ARG;
+    if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *tbase = static_cast<char *>(workspace);
+    float *partial = reinterpret_cast<float *>(tbase + pl.t_bytes);
+
+    // T^T = G^T B^-1   (d_in x d_out), then  out = (T^T)^T A^-1.
+    for (int pass = 0; pass < 2; ++pass) {
+        size_t done = 0;
+        char *tcur = tbase;
+        while (done < (size_t)count) {
+            const size_t n = std::min<size_t>(TN_MAX_PROBLEMS, (size_t)count - done);
+            TnBatch b;
+            b.tile_mode = TILE_FULL;
+            b.splits = pass == 0 ? pl.splits1 : pl.splits2;
+            b.partial = partial;
+            for (size_t i = done; i < done + n; ++i) {
+                const kfac_precondition_item &it = items[i];
+                const int dout = (int)it.d_out, din = (int)it.d_in;
+                float *tt = reinterpret_cast<float *>(tcur);
+                tcur += align_up((size_t)din * dout * sizeof(float), WS_ALIGN);
+                if (pass == 0)
+                    b.add(it.grad, (int)it.ldg, it.b_inv, (int)it.ldb, tt, dout, din, dout, dout);
+                else
+                    b.add(tt, dout, it.a_inv, (int)it.lda, it.out, (int)it.ldo, dout, din, din);
+            }
+            if (b.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+            done += n;
+        }
+    }
+    return KFAC_OK;
+}
+
+kfac_status kfac_precondition(const float *b_inv, int64_t d_out, int64_t ldb,
+                              const float *a_inv, int64_t d_in, int64_t lda,
+                              const float *grad, int64_t ldg, float *out, int64_t ldo,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    kfac_precondition_item it;
+    it.b_inv = b_inv;
+    it.d_out = d_out;
+    it.ldb = ldb;
+    it.a_inv = a_inv;
+    it.d_in = d_in;
+    it.lda = lda;
+    it.grad = grad;
+    it.ldg = ldg;
+    it.out = out;
+    it.ldo = ldo;
+    return kfac_precondition_grouped(&it, 1, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,421 @@
+// Grouped fp32 "TN" contraction engine for gfx950:  C = alpha * A^T B + beta * C.
+//
+// Both operands are row-major with the contraction index as the ROW index
+// (A is K x M, B is K x N).  Every contraction of the K-FAC work items has that
+// shape once the symmetry of the factors and of their inverses is used:
+//   curvature    X^T X                     (tokens are rows of X)
+//   precondition G^T B^-1, then T^T A^-1   (B^-1, A^-1 symmetric)
+//   inversion    the updates of an upper Cholesky factorisation M = U^T U,
+//                the triangular inverse and the product W W^T, with mirrored
+//                copies kept so that each left operand can be read row-wise.
+// so one main loop serves all of them: rows of both operands are contiguous,
+// loads are 512-byte coalesced and go to LDS without a transpose.
+//
+// Tiling: a 256-thread workgroup (4 wave64) owns a 128 x 128 tile of C; each
+// wave owns 64 x 64 as 2 x 2 MFMA 32x32x2 blocks (64 accumulator registers).
+// K advances in slabs of 16 through double-buffered LDS with register prefetch.
+// The token sum is folded into a second accumulator every CHUNK slabs, so the
+// fp32 rounding error grows with the chunk length, not with K.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kfac {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128;
+constexpr int BN = 128;
+constexpr int BK = 16;
+constexpr int TN_THREADS = 256;
+constexpr int TN_MAX_PROBLEMS = 48;
+constexpr int TN_CHUNK_SLABS = 8;  // fold the running sum every 8 * 16 = 128 rows of K
+constexpr int SUPER_ROWS = 8;      // tiles of 8 consecutive tile-rows are scheduled together
+
+enum TileMode : int { TILE_FULL = 0, TILE_LOWER = 1, TILE_UPPER = 2 };
+// Element (k, m) of an operand is kept if ...
+enum OperandMask : int { MASK_NONE = 0, MASK_KEEP_K_GE = 1, MASK_KEEP_K_LE = 2 };
+
+struct TnProblem {
+    const float *A;    // K x M, lda
+    const float *B;    // K x N, ldb
+    float *C;          // M x N, ldc (read when beta != 0)
+    float *Ct;         // optional mirror: Ct[n * ldct + m] = C[m][n]
+    const int *guard;  // optional: stores are skipped when *guard != 0
+    int M, N, K;
+    int lda, ldb, ldc, ldct;
+    int tile_begin;    // first logical tile (tile * splits + split) of this problem
+};
+
+struct TnLaunch {
+    TnProblem p[TN_MAX_PROBLEMS];
+    int count;
+    int tile_mode;  // TILE_LOWER / TILE_UPPER need M == N
+    int mask_a;
+    int mask_b;
+    int splits;     // > 1: partial tiles go to `partial`, tn_reduce_kernel finishes
+    float alpha;
+    float beta;
+    float *partial;  // [total logical tiles][BM * BN]
+};
+
+__host__ __device__ inline int tn_tiles(int M, int N, int mode)
+{
+    const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+    return mode == TILE_FULL ? tm * tn : tm * (tm + 1) / 2;
+}
+
+// Order of the tiles of one problem: bands of SUPER_ROWS tile-rows, column by
+// column inside a band, so that tiles running at the same time share operand
+// columns (they hit in the XCD's L2).
+__device__ inline void tn_decode_full(int idx, int tm, int tn, int &ti, int &tj)
+{
+    const int band = idx / (SUPER_ROWS * tn);
+    const int r = idx - band * SUPER_ROWS * tn;
+    const int rows = min(SUPER_ROWS, tm - band * SUPER_ROWS);
+    tj = r / rows;
+    ti = band * SUPER_ROWS + r % rows;
+}
+
+__device__ inline void tn_decode_lower(int idx, int nt, int &ti, int &tj)
+{
+    int r0 = 0, r1 = 0;
+    for (;;) {
+        r1 = min(r0 + SUPER_ROWS, nt);
+        const int cnt = (r1 * (r1 + 1) - r0 * (r0 + 1)) / 2;
+        if (idx < cnt || r1 == nt) break;
+        idx -= cnt;
+        r0 = r1;
+    }
+    const int rows = r1 - r0;
+    const int rect = r0 * rows;
+    if (idx < rect) {
+        tj = idx / rows;
+        ti = r0 + idx % rows;
+        return;
+    }
+    idx -= rect;
+    ti = tj = r1 - 1;
+    for (int j = r0; j < r1; ++j) {
+        const int c = r1 - j;
+        if (idx < c) {
+            tj = j;
+            ti = j + idx;
+            return;
+        }
+        idx -= c;
+    }
+}
+
+// blockIdx -> logical tile, so that each XCD (blocks are dealt round-robin to
+// the 8 XCDs) works on one contiguous range of logical tiles.
+__device__ inline int tn_logical_tile(int bid, int nblocks)
+{
+    const int base = nblocks >> 3, rem = nblocks & 7;
+    const int xcd = bid & 7, q = bid >> 3;
+    return xcd * base + min(xcd, rem) + q;
+}
+
+struct TnTile {
+    int prob, ti, tj, split, m0, n0, kt0, kt1, kbase;
+    bool diag;
+};
+
+__device__ inline TnTile tn_locate(const TnLaunch &lp, int t)
+{
+    TnTile tl;
+    int pi = 0;
+    for (int i = 1; i < lp.count; ++i)
+        if (lp.p[i].tile_begin <= t) pi = i;
+    const TnProblem &pr = lp.p[pi];
+    const int local = t - pr.tile_begin;
+    const int tile = local / lp.splits;
+    tl.prob = pi;
+    tl.split = local - tile * lp.splits;
+    const int tm = (pr.M + BM - 1) / BM, tn = (pr.N + BN - 1) / BN;
+    if (lp.tile_mode == TILE_FULL) {
+        tn_decode_full(tile, tm, tn, tl.ti, tl.tj);
+    } else {
+        tn_decode_lower(tile, tm, tl.ti, tl.tj);
+        if (lp.tile_mode == TILE_UPPER) {
+            const int s = tl.ti;
+            tl.ti = tl.tj;
+            tl.tj = s;
+        }
+    }
+    tl.diag = (lp.tile_mode != TILE_FULL) && (tl.ti == tl.tj);
+    tl.m0 = tl.ti * BM;
+    tl.n0 = tl.tj * BN;
+    // K range that can hold non-zeros under the operand masks, in slabs of BK
+    int kb = 0, ke = pr.K;
+    if (lp.mask_a == MASK_KEEP_K_GE) kb = max(kb, tl.m0);
+    if (lp.mask_a == MASK_KEEP_K_LE) ke = min(ke, tl.m0 + BM);
+    if (lp.mask_b == MASK_KEEP_K_GE) kb = max(kb, tl.n0);
+    if (lp.mask_b == MASK_KEEP_K_LE) ke = min(ke, tl.n0 + BN);
+    kb = (kb / BK) * BK;
+    const int nslab = ke > kb ? (ke - kb + BK - 1) / BK : 0;
+    const int per = (nslab + lp.splits - 1) / lp.splits;
+    tl.kbase = kb;
+    tl.kt0 = min(nslab, tl.split * per);
+    tl.kt1 = min(nslab, tl.kt0 + per);
+    return tl;
+}
+
+__device__ inline float4 tn_load4(const float *P, int k, int c, int ld, int K, int W, bool fast, int mask)
+{
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k < K) {
+        const float *p = P + (size_t)k * (size_t)ld + c;
+        if (fast) {
+            v = *reinterpret_cast<const float4 *>(p);
+        } else {
+            if (c + 0 < W) v.x = p[0];
+            if (c + 1 < W) v.y = p[1];
+            if (c + 2 < W) v.z = p[2];
+            if (c + 3 < W) v.w = p[3];
+        }
+        if (mask == MASK_KEEP_K_GE) {
+            if (k < c + 0) v.x = 0.f;
+            if (k < c + 1) v.y = 0.f;
+            if (k < c + 2) v.z = 0.f;
+            if (k < c + 3) v.w = 0.f;
+        } else if (mask == MASK_KEEP_K_LE) {
+            if (k > c + 0) v.x = 0.f;
+            if (k > c + 1) v.y = 0.f;
+            if (k > c + 2) v.z = 0.f;
+            if (k > c + 3) v.w = 0.f;
+        }
+    }
+    return v;
+}
+
+// Which elements of a tile are stored directly / mirrored.  On a diagonal tile
+// of a triangular launch only one triangle is stored and the other one is its
+// mirror, which makes the result bitwise symmetric.
+__device__ inline bool tn_keep(bool diag, int mode, int m, int n)
+{
+    return !diag || (mode == TILE_LOWER ? n <= m : n >= m);
+}
+
+__global__ __launch_bounds__(TN_THREADS, 2) void tn_gemm_kernel(const TnLaunch lp)
+{
+    __shared__ float As[2][BK][BM];
+    __shared__ float Bs[2][BK][BN];
+
+    const int tid = threadIdx.x;
+    const TnTile tl = tn_locate(lp, tn_logical_tile(blockIdx.x, gridDim.x));
+    const TnProblem &pr = lp.p[tl.prob];
+    const int M = pr.M, N = pr.N, K = pr.K;
+    const float *__restrict__ A = pr.A;
+    const float *__restrict__ B = pr.B;
+    const int lda = pr.lda, ldb = pr.ldb;
+
+    const bool fast_a = (tl.m0 + BM <= M) && ((lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0);
+    const bool fast_b = (tl.n0 + BN <= N) && ((ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
+
+    const int lrow = tid >> 5;        // 0..7 (and +8)
+    const int lcol = (tid & 31) << 2; // 0..124
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int li = lane & 31, lh = lane >> 5;
+
+    floatx16 acc[2][2], sum[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc[i][j][r] = 0.f;
+                sum[i][j][r] = 0.f;
+            }
+
+    if (tl.kt1 > tl.kt0) {
+        float4 ra[2], rb[2];
+        {
+            const int k = tl.kbase + tl.kt0 * BK + lrow;
+            ra[0] = tn_load4(A, k, tl.m0 + lcol, lda, K, M, fast_a, lp.mask_a);
+            ra[1] = tn_load4(A, k + 8, tl.m0 + lcol, lda, K, M, fast_a, lp.mask_a);
+            rb[0] = tn_load4(B, k, tl.n0 + lcol, ldb, K, N, fast_b, lp.mask_b);
+            rb[1] = tn_load4(B, k + 8, tl.n0 + lcol, ldb, K, N, fast_b, lp.mask_b);
+        }
+        *reinterpret_cast<float4 *>(&As[0][lrow][lcol]) = ra[0];
+        *reinterpret_cast<float4 *>(&As[0][lrow + 8][lcol]) = ra[1];
+        *reinterpret_cast<float4 *>(&Bs[0][lrow][lcol]) = rb[0];
+        *reinterpret_cast<float4 *>(&Bs[0][lrow + 8][lcol]) = rb[1];
+        __syncthreads();
+
+        int folded = 0;
+        for (int kt = tl.kt0; kt < tl.kt1; ++kt) {
+            const int cur = (kt - tl.kt0) & 1;
+            const bool more = (kt + 1 < tl.kt1);
+            if (more) {
+                const int k = tl.kbase + (kt + 1) * BK + lrow;
+                ra[0] = tn_load4(A, k, tl.m0 + lcol, lda, K, M, fast_a, lp.mask_a);
+                ra[1] = tn_load4(A, k + 8, tl.m0 + lcol, lda, K, M, fast_a, lp.mask_a);
+                rb[0] = tn_load4(B, k, tl.n0 + lcol, ldb, K, N, fast_b, lp.mask_b);
+                rb[1] = tn_load4(B, k + 8, tl.n0 + lcol, ldb, K, N, fast_b, lp.mask_b);
+            }
+#pragma unroll
+            for (int s = 0; s < BK / 2; ++s) {
+                // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2s + lh
+                const float2 a = *reinterpret_cast<const float2 *>(&As[cur][2 * s + lh][wm + 2 * li]);
+                const float2 b = *reinterpret_cast<const float2 *>(&Bs[cur][2 * s + lh][wn + 2 * li]);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.y, acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.x, acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc[1][1], 0, 0, 0);
+            }
+            if (more) {
+                *reinterpret_cast<float4 *>(&As[cur ^ 1][lrow][lcol]) = ra[0];
+                *reinterpret_cast<float4 *>(&As[cur ^ 1][lrow + 8][lcol]) = ra[1];
+                *reinterpret_cast<float4 *>(&Bs[cur ^ 1][lrow][lcol]) = rb[0];
+                *reinterpret_cast<float4 *>(&Bs[cur ^ 1][lrow + 8][lcol]) = rb[1];
+            }
+            __syncthreads();
+            if (++folded == TN_CHUNK_SLABS) {
+                folded = 0;
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        sum[i][j] += acc[i][j];
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                    }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
+
+    // Accumulator layout of MFMA 32x32: register r of lane (li, lh) is row
+    // 8*(r/4) + 4*lh + r%4, column li of the block; block (bi, bj) interleaves
+    // rows/columns with stride 2 (see the operand feed above).
+    if (lp.splits > 1) {
+        const int t = tn_logical_tile(blockIdx.x, gridDim.x);
+        float *P = lp.partial + (size_t)t * (BM * BN);
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lm = wm + 2 * (8 * (r >> 2) + 4 * lh + (r & 3)) + bi;
+                const int ln = wn + 2 * li;
+                *reinterpret_cast<float2 *>(&P[lm * BN + ln]) = make_float2(sum[bi][0][r], sum[bi][1][r]);
+            }
+        return;
+    }
+
+    if (pr.guard != nullptr && *pr.guard != 0) return;
+
+    float *__restrict__ C = pr.C;
+    float *__restrict__ Ct = pr.Ct;
+    const int ldc = pr.ldc, ldct = pr.ldct;
+    const float alpha = lp.alpha, beta = lp.beta;
+    const bool interior = (tl.m0 + BM <= M) && (tl.n0 + BN <= N) && !tl.diag;
+    const bool fast_c = interior && ((ldc & 1) == 0) && ((reinterpret_cast<uintptr_t>(C) & 7) == 0);
+
+    if (fast_c) {
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = tl.m0 + wm + 2 * (8 * (r >> 2) + 4 * lh + (r & 3)) + bi;
+                const int n = tl.n0 + wn + 2 * li;
+                float2 *dst = reinterpret_cast<float2 *>(C + (size_t)m * ldc + n);
+                float2 v = make_float2(alpha * sum[bi][0][r], alpha * sum[bi][1][r]);
+                if (beta != 0.f) {
+                    const float2 old = *dst;
+                    v.x += beta * old.x;
+                    v.y += beta * old.y;
+                }
+                sum[bi][0][r] = v.x;
+                sum[bi][1][r] = v.y;
+                *dst = v;
+            }
+    } else {
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = tl.m0 + wm + 2 * (8 * (r >> 2) + 4 * lh + (r & 3)) + bi;
+                    const int n = tl.n0 + wn + 2 * li + bj;
+                    float v = alpha * sum[bi][bj][r];
+                    if (m < M && n < N && tn_keep(tl.diag, lp.tile_mode, m, n)) {
+                        float *dst = C + (size_t)m * ldc + n;
+                        if (beta != 0.f) v += beta * (*dst);
+                        *dst = v;
+                    }
+                    sum[bi][bj][r] = v;
+                }
+    }
+
+    if (Ct != nullptr) {
+        const bool fast_t = interior && ((ldct & 3) == 0) && ((reinterpret_cast<uintptr_t>(Ct) & 15) == 0);
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                // eight consecutive rows m of C held by this lane for column n
+                const int n = tl.n0 + wn + 2 * li + bj;
+                const int mq = tl.m0 + wm + 16 * q + 8 * lh;
+                if (fast_t) {
+                    float4 *dst = reinterpret_cast<float4 *>(Ct + (size_t)n * ldct + mq);
+                    dst[0] = make_float4(sum[0][bj][4 * q + 0], sum[1][bj][4 * q + 0], sum[0][bj][4 * q + 1], sum[1][bj][4 * q + 1]);
+                    dst[1] = make_float4(sum[0][bj][4 * q + 2], sum[1][bj][4 * q + 2], sum[0][bj][4 * q + 3], sum[1][bj][4 * q + 3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int m = mq + e;
+                        const bool strict = !tl.diag || (m != n && tn_keep(true, lp.tile_mode, m, n));
+                        if (m < M && n < N && strict) Ct[(size_t)n * ldct + m] = sum[e & 1][bj][4 * q + (e >> 1)];
+                    }
+                }
+            }
+    }
+}
+
+// Second pass of a split-K launch: adds the partial tiles of each output tile in
+// split order (fixed order: the result does not depend on scheduling) and
+// applies the same epilogue as the main kernel.  One workgroup per output tile.
+__global__ __launch_bounds__(TN_THREADS) void tn_reduce_kernel(const TnLaunch lp)
+{
+    const int t0 = blockIdx.x * lp.splits;  // logical index of split 0 of this output tile
+    const TnTile tl = tn_locate(lp, t0);
+    const TnProblem &pr = lp.p[tl.prob];
+    if (pr.guard != nullptr && *pr.guard != 0) return;
+    const float *P = lp.partial + (size_t)t0 * (BM * BN);
+    const int tid = threadIdx.x;
+    const int M = pr.M, N = pr.N;
+    for (int it = 0; it < BM / 8; ++it) {
+        const int lm = (tid >> 5) + 8 * it;
+        const int ln = (tid & 31) << 2;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int sp = 0; sp < lp.splits; ++sp) {
+            const float4 v = *reinterpret_cast<const float4 *>(&P[(size_t)sp * (BM * BN) + lm * BN + ln]);
+            s.x += v.x;
+            s.y += v.y;
+            s.z += v.z;
+            s.w += v.w;
+        }
+        const float vals[4] = {s.x, s.y, s.z, s.w};
+        const int m = tl.m0 + lm;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int n = tl.n0 + ln + e;
+            if (m < M && n < N && tn_keep(tl.diag, lp.tile_mode, m, n)) {
+                float v = lp.alpha * vals[e];
+                float *dst = pr.C + (size_t)m * pr.ldc + n;
+                if (lp.beta != 0.f) v += lp.beta * (*dst);
+                *dst = v;
+                if (pr.Ct != nullptr && (!tl.diag || m != n)) pr.Ct[(size_t)n * pr.ldct + m] = v;
+            }
+        }
+    }
+}
+
+}  // namespace kfac

@@ -1,0 +1,344 @@
+"""Parity of the HIP path against the fp64 oracle, element by element, through the C ABI.
+
+Tolerances (relative Frobenius error over the whole matrix, accumulated in fp64):
+factors <= 1e-4 for fp32 inputs, preconditioned gradient <= 5e-3 (the
+benchmark definition's gates); inverses are checked against the oracle with
+a bound scaled by the condition number, and by their residual.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2211_14133_amd import synth  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+FACTOR_TOL = 1e-4
+PRECOND_TOL = 5e-3
+
+
+@pytest.fixture(scope="module")
+def k():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2211_14133_amd as lib
+
+    lib.load()
+    return lib
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def gpu_factor(k, x, alpha=None, beta=0.0, factor=None, ld_pad=0):
+    n, d = x.shape
+    if alpha is None:
+        alpha = 1.0 / n
+    if factor is None:
+        buf = torch.full((d, d + ld_pad), 7.0, dtype=torch.float32, device="cuda")
+        factor = buf[:, :d]
+    k.kfac_curvature(x, factor, alpha, beta)
+    return factor
+
+
+# ------------------------------------------------------------------ curvature
+
+@pytest.mark.parametrize("n,d", [(256, 64), (300, 200), (1000, 129), (513, 767), (4096, 768), (2048, 1024), (16, 1), (1, 5)])
+def test_curvature_parity(k, oracle, n, d):
+    print("curvature n=%d d=%d" % (n, d), flush=True)
+    x = synth.activations(1, 0, 0, 0, n, d, gelu=(d % 2 == 1))
+    f = host(gpu_factor(k, dev(x)))
+    want = oracle.curvature(x)
+    err = oracle.rel_fro(f, want)
+    print("  rel_fro", err, flush=True)
+    assert err <= FACTOR_TOL
+    assert err <= 5e-7  # chunked fp32 accumulation: a few ulp
+    assert np.array_equal(f, f.T)
+
+
+def test_curvature_strided_input_and_output(k, oracle):
+    n, d = 700, 300
+    big = synth.activations(1, 0, 1, 0, n, d + 37)
+    xb = dev(big)
+    x = xb[:, 5:5 + d]  # ldx = d + 37, pointer offset by 5 floats: unaligned rows
+    f = gpu_factor(k, x, ld_pad=3)
+    want = oracle.curvature(big[:, 5:5 + d])
+    assert oracle.rel_fro(host(f), want) <= 5e-7
+    # the padding columns of the output buffer are untouched
+    assert torch.all(f.as_strided((d, 3), (d + 3, 1), d) == 7.0)
+
+
+def test_curvature_hadamard_exact(k):
+    for n, d in [(256, 256), (1024, 640), (4096, 1024)]:
+        x = synth.hadamard_columns(n, d)
+        f = host(gpu_factor(k, dev(x)))
+        assert np.array_equal(f, np.eye(d, dtype=np.float32)), (n, d)
+
+
+def test_curvature_small_integers_bitwise(k, oracle):
+    rng = np.random.default_rng(5)
+    for n, d in [(4096, 384), (1000, 130)]:
+        x = rng.integers(-8, 9, size=(n, d)).astype(np.float32)
+        f = host(gpu_factor(k, dev(x), alpha=1.0))
+        want = oracle.curvature_update(x, 1.0, 0.0)
+        assert np.array_equal(f.astype(np.float64), want)
+
+
+def test_curvature_ones_and_one_hot(k):
+    f = host(gpu_factor(k, torch.ones(64, 40, device="cuda")))
+    assert np.array_equal(f, np.ones((40, 40), dtype=np.float32))
+    idx = torch.arange(512, device="cuda") % 7
+    x = torch.zeros(512, 9, device="cuda")
+    x[torch.arange(512), idx] = 1.0
+    f = host(gpu_factor(k, x, alpha=1.0))
+    want = np.diag(np.bincount(host(idx), minlength=9)).astype(np.float32)
+    assert np.array_equal(f, want)
+
+
+def test_curvature_microbatch_accumulation(k, oracle):
+    d, n, nm = 320, 512, 4
+    xs = [synth.activations(1, 0, 2, m, n, d) for m in range(nm)]
+    alpha = 1.0 / (n * nm)
+    f = None
+    for m, x in enumerate(xs):
+        f = gpu_factor(k, dev(x), alpha=alpha, beta=0.0 if m == 0 else 1.0, factor=f)
+    want = oracle.curvature(xs)
+    assert oracle.rel_fro(host(f), want) <= 5e-7
+    assert np.array_equal(host(f), host(f).T)
+    # general beta
+    x = xs[0]
+    f0 = np.asarray(np.random.default_rng(3).standard_normal((d, d)), dtype=np.float32)
+    f0 = (f0 + f0.T) / 2
+    fd = dev(f0)
+    k.kfac_curvature(dev(x), fd, 0.5, 0.25)
+    want = oracle.curvature_update(x, 0.5, 0.25, f0)
+    assert oracle.rel_fro(host(fd), want) <= 5e-7
+
+
+def test_curvature_grouped_matches_single_and_oracle(k, oracle):
+    shapes = [(512, 64), (512, 300), (384, 1024), (512, 129), (256, 640)]
+    xs = [synth.activations(1, 0, 3 + i, 0, n, d) for i, (n, d) in enumerate(shapes)]
+    xd = [dev(x) for x in xs]
+    fg = [torch.empty(d, d, device="cuda") for _, d in shapes]
+    k.kfac_curvature_grouped(xd, fg, 1.0 / 512, 0.0)
+    for x, xdv, f in zip(xs, xd, fg):
+        want = oracle.curvature_update(x, 1.0 / 512, 0.0)
+        assert oracle.rel_fro(host(f), want) <= 5e-7
+        assert np.array_equal(host(f), host(f).T)
+    # 60 items: more than one launch
+    many = [dev(synth.activations(1, 1, i, 0, 128, 96)) for i in range(60)]
+    fm = [torch.empty(96, 96, device="cuda") for _ in many]
+    k.kfac_curvature_grouped(many, fm, 1.0 / 128, 0.0)
+    for x, f in zip(many, fm):
+        assert oracle.rel_fro(host(f), oracle.curvature(host(x))) <= 5e-7
+
+
+def test_curvature_is_deterministic(k):
+    x = dev(synth.activations(1, 0, 9, 0, 4096, 768))
+    a = host(gpu_factor(k, x)).copy()
+    for _ in range(2):
+        assert np.array_equal(a, host(gpu_factor(k, x)))
+
+
+# ------------------------------------------------------------------ inversion
+
+def gpu_invert(k, f, lam):
+    d = f.shape[0]
+    fd = dev(f.astype(np.float32))
+    inv = torch.full((d, d), 3.0, device="cuda")
+    info = k.kfac_invert(fd, lam, inv)
+    return host(inv), int(host(info)[0])
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 63, 64, 65, 127, 128, 129, 200, 256, 257, 384, 767, 768, 769, 1024])
+def test_invert_parity(k, oracle, d):
+    print("invert d=%d" % d, flush=True)
+    n = max(2 * d, 64)
+    x = synth.activations(2, 0, 0, 0, n, d, gelu=(d % 3 == 0))
+    a = oracle.curvature(x).astype(np.float32)
+    lam = 1e-3
+    inv, info = gpu_invert(k, a, lam)
+    assert info == 0
+    want, _ = oracle.invert(a.astype(np.float64), lam)
+    at = a.astype(np.float64) + lam * np.eye(d)
+    cond = np.linalg.cond(at)
+    err = oracle.rel_fro(inv, want)
+    res = np.linalg.norm(at @ inv.astype(np.float64) - np.eye(d)) / np.sqrt(d)
+    print("  cond %.3g rel_fro %.3g residual %.3g" % (cond, err, res), flush=True)
+    assert err <= 2e-6 * cond + 1e-6
+    assert res <= 2e-6 * cond + 1e-6
+    assert np.array_equal(inv, inv.T)
+
+
+def test_invert_closed_forms(k):
+    d = 300
+    inv, info = gpu_invert(k, np.zeros((d, d)), 4.0)
+    assert info == 0 and np.array_equal(inv, np.eye(d, dtype=np.float32) / 4.0)
+    al, be = 0.7, 0.3
+    inv, info = gpu_invert(k, be * np.ones((d, d)), al)
+    want = (np.eye(d) - be / (al + be * d) * np.ones((d, d))) / al
+    assert info == 0 and np.linalg.norm(inv - want) <= 1e-5 * np.linalg.norm(want)
+    i = np.arange(1, d + 1)
+    t = 2 * np.eye(d) - np.eye(d, k=1) - np.eye(d, k=-1)
+    inv, info = gpu_invert(k, t, 0.0)
+    want = np.minimum.outer(i, i) * (d + 1 - np.maximum.outer(i, i)) / (d + 1.0)
+    assert info == 0 and np.linalg.norm(inv - want) <= 1e-3 * np.linalg.norm(want)  # cond ~ 4e4
+
+
+def test_invert_only_reads_upper_triangle(k, oracle):
+    d = 200
+    a = oracle.curvature(synth.activations(2, 0, 1, 0, 400, d)).astype(np.float32)
+    junk = a.copy()
+    junk[np.tril_indices(d, -1)] = 123.0
+    i1, _ = gpu_invert(k, a, 1e-3)
+    i2, _ = gpu_invert(k, junk, 1e-3)
+    assert np.array_equal(i1, i2)
+
+
+def test_invert_failure_reports_pivot_and_keeps_inverse(k):
+    d = 300
+    m = np.eye(d)
+    m[170, 170] = -1.0
+    inv, info = gpu_invert(k, m, 0.0)
+    assert info == 171
+    assert np.all(inv == 3.0)  # untouched
+    m = np.eye(d)
+    m[5, 9] = np.nan
+    inv, info = gpu_invert(k, m, 0.0)
+    assert info == -1 and np.all(inv == 3.0)
+    # rank-deficient factor without damping fails, with damping succeeds
+    x = np.ones((4, 150), dtype=np.float32)
+    a = (x.T @ x / 4).astype(np.float32)
+    inv, info = gpu_invert(k, a, 0.0)
+    assert info > 0
+    inv, info = gpu_invert(k, a, 1e-3)
+    assert info == 0
+
+
+def test_invert_batched_mixed_sizes(k, oracle):
+    ds = [64, 300, 128, 513, 1, 256, 767]
+    fs = [oracle.curvature(synth.activations(2, 1, i, 0, 2 * d + 8, d)).astype(np.float32) for i, d in enumerate(ds)]
+    fd = [dev(f) for f in fs]
+    invs = [torch.empty(d, d, device="cuda") for d in ds]
+    infos = k.kfac_invert_batched(fd, 1e-3, invs)
+    assert np.all(host(infos) == 0)
+    for f, inv in zip(fs, invs):
+        want, _ = oracle.invert(f.astype(np.float64), 1e-3)
+        assert oracle.rel_fro(host(inv), want) <= 1e-4
+        single, _ = gpu_invert(k, f, 1e-3)
+        assert np.array_equal(single, host(inv))
+
+
+# --------------------------------------------------------------- precondition
+
+@pytest.mark.parametrize("d_out,d_in", [(64, 64), (2, 3), (5, 7), (130, 257), (768, 300), (256, 1024), (1024, 1024)])
+def test_precondition_parity(k, oracle, d_out, d_in):
+    print("precondition %dx%d" % (d_out, d_in), flush=True)
+    rng = np.random.default_rng(d_out * 7 + d_in)
+    b = rng.standard_normal((d_out, d_out)).astype(np.float32)
+    b = (b + b.T) / 2
+    a = rng.standard_normal((d_in, d_in)).astype(np.float32)
+    a = (a + a.T) / 2
+    g = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    out = torch.empty(d_out, d_in, device="cuda")
+    k.kfac_precondition(dev(b), dev(a), dev(g), out)
+    want = oracle.precondition(b, g, a)
+    err = oracle.rel_fro(host(out), want)
+    print("  rel_fro", err, flush=True)
+    assert err <= 2e-6
+
+
+def test_precondition_identity_diagonal_and_alias(k):
+    d_out, d_in = 150, 260
+    g = dev(np.random.default_rng(1).standard_normal((d_out, d_in)).astype(np.float32))
+    out = torch.empty_like(g)
+    k.kfac_precondition(torch.eye(d_out, device="cuda"), torch.eye(d_in, device="cuda"), g, out)
+    assert torch.equal(out, g)
+    bd = torch.rand(d_out, device="cuda") + 1
+    ad = torch.rand(d_in, device="cuda") + 1
+    k.kfac_precondition(torch.diag(bd), torch.diag(ad), g, out)
+    want = g * bd[:, None] * ad[None, :]
+    assert torch.allclose(out, want, rtol=1e-6, atol=0)
+    g2 = g.clone()
+    k.kfac_precondition(torch.diag(bd), torch.diag(ad), g2, g2)  # in place
+    assert torch.equal(g2, out)
+
+
+def test_precondition_grouped(k, oracle):
+    shapes = [(64, 64), (300, 128), (128, 300), (1, 9)]
+    rng = np.random.default_rng(2)
+    bs, as_, gs = [], [], []
+    for do, di in shapes:
+        b = rng.standard_normal((do, do)).astype(np.float32)
+        a = rng.standard_normal((di, di)).astype(np.float32)
+        bs.append((b + b.T) / 2)
+        as_.append((a + a.T) / 2)
+        gs.append(rng.standard_normal((do, di)).astype(np.float32))
+    outs = [torch.empty(do, di, device="cuda") for do, di in shapes]
+    k.kfac_precondition_grouped([dev(b) for b in bs], [dev(a) for a in as_], [dev(g) for g in gs], outs)
+    for b, a, g, o in zip(bs, as_, gs, outs):
+        assert oracle.rel_fro(host(o), oracle.precondition(b, g, a)) <= 2e-6
+
+
+# ---------------------------------------------------------------- whole chain
+
+def run_chain(k, oracle, cfg_id, layers=None):
+    c = synth.CONFIGS[cfg_id]
+    worst = 0.0
+    for li, (name, d_in, d_out, gelu) in enumerate(c["layers"]):
+        if layers is not None and name not in layers:
+            continue
+        n = c["tokens"]
+        x = synth.activations(cfg_id, 0, li, 0, n, d_in, gelu=gelu)
+        e = synth.errors(cfg_id, 0, li, 0, n, d_out)
+        g = synth.weight_gradient([e], [x])
+        xd, ed, gd = dev(x), dev(e), dev(g)
+        a = torch.empty(d_in, d_in, device="cuda")
+        b = torch.empty(d_out, d_out, device="cuda")
+        k.kfac_curvature(xd, a, 1.0 / n, 0.0)
+        k.kfac_curvature(ed, b, 1.0 / n, 0.0)
+        ai, bi = torch.empty_like(a), torch.empty_like(b)
+        info_a = k.kfac_invert(a, synth.DAMPING, ai)
+        info_b = k.kfac_invert(b, synth.DAMPING, bi)
+        p = torch.empty_like(gd)
+        k.kfac_precondition(bi, ai, gd, p)
+        assert int(info_a[0]) == 0 and int(info_b[0]) == 0
+        oa, ob, oai, obi, op = oracle.kfac_chain([x], [e], g, synth.DAMPING)
+        ea, eb = oracle.rel_fro(host(a), oa), oracle.rel_fro(host(b), ob)
+        eai, ebi = oracle.rel_fro(host(ai), oai), oracle.rel_fro(host(bi), obi)
+        ep = oracle.rel_fro(host(p), op)
+        print("cfg %d %-5s A %.2e B %.2e A^-1 %.2e B^-1 %.2e P %.2e" % (cfg_id, name, ea, eb, eai, ebi, ep), flush=True)
+        assert ea <= FACTOR_TOL and eb <= FACTOR_TOL
+        assert ep <= PRECOND_TOL
+        worst = max(worst, ep)
+    return worst
+
+
+def test_chain_config1_and_kronecker(k, oracle):
+    run_chain(k, oracle, 1)
+    # the GPU result against the explicit Kronecker solve
+    c = synth.CONFIGS[1]
+    x = synth.activations(1, 0, 0, 0, c["tokens"], 64)
+    e = synth.errors(1, 0, 0, 0, c["tokens"], 64)
+    g = synth.weight_gradient([e], [x])
+    a = torch.empty(64, 64, device="cuda")
+    b = torch.empty(64, 64, device="cuda")
+    k.kfac_curvature(dev(x), a, 1.0 / 256, 0.0)
+    k.kfac_curvature(dev(e), b, 1.0 / 256, 0.0)
+    ai, bi = torch.empty_like(a), torch.empty_like(b)
+    k.kfac_invert(a, synth.DAMPING, ai)
+    k.kfac_invert(b, synth.DAMPING, bi)
+    p = torch.empty(64, 64, device="cuda")
+    k.kfac_precondition(bi, ai, dev(g), p)
+    brute = oracle.kron_solve(oracle.curvature(x), oracle.curvature(e), g, synth.DAMPING)
+    assert oracle.rel_fro(host(p), brute) <= PRECOND_TOL
+
+
+def test_chain_config2_bert_base_block(k, oracle):
+    run_chain(k, oracle, 2)
