@@ -161,30 +161,45 @@ __device__ inline TnTile tn_locate(const TnLaunch &lp, int t)
     return tl;
 }
 
-__device__ inline float4 tn_load4(const float *P, int k, int c, int ld, int K, int W, bool fast, int mask)
+// Unconditional load of four consecutive elements of operand row k starting at
+// column c.  Out-of-range rows / columns are clamped to the last valid one, so
+// the load never depends on a branch; tn_fix4 zeroes what must not count after
+// the MFMA work of the current slab has been issued (the load latency is then
+// hidden behind it).
+template <bool FAST>
+__device__ inline float4 tn_load4(const float *P, int k, int c, int ld, int K, int W)
 {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (k < K) {
-        const float *p = P + (size_t)k * (size_t)ld + c;
-        if (fast) {
-            v = *reinterpret_cast<const float4 *>(p);
-        } else {
-            if (c + 0 < W) v.x = p[0];
-            if (c + 1 < W) v.y = p[1];
-            if (c + 2 < W) v.z = p[2];
-            if (c + 3 < W) v.w = p[3];
-        }
-        if (mask == MASK_KEEP_K_GE) {
-            if (k < c + 0) v.x = 0.f;
-            if (k < c + 1) v.y = 0.f;
-            if (k < c + 2) v.z = 0.f;
-            if (k < c + 3) v.w = 0.f;
-        } else if (mask == MASK_KEEP_K_LE) {
-            if (k > c + 0) v.x = 0.f;
-            if (k > c + 1) v.y = 0.f;
-            if (k > c + 2) v.z = 0.f;
-            if (k > c + 3) v.w = 0.f;
-        }
+    const int kc = min(k, K - 1);
+    const float *row = P + (size_t)kc * (size_t)ld;
+    if (FAST) return *reinterpret_cast<const float4 *>(row + c);
+    float4 v;
+    v.x = row[min(c + 0, W - 1)];
+    v.y = row[min(c + 1, W - 1)];
+    v.z = row[min(c + 2, W - 1)];
+    v.w = row[min(c + 3, W - 1)];
+    return v;
+}
+
+template <bool FAST>
+__device__ inline float4 tn_fix4(float4 v, int k, int c, int K, int W, int mask)
+{
+    if (k >= K) v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!FAST) {
+        if (c + 0 >= W) v.x = 0.f;
+        if (c + 1 >= W) v.y = 0.f;
+        if (c + 2 >= W) v.z = 0.f;
+        if (c + 3 >= W) v.w = 0.f;
+    }
+    if (mask == MASK_KEEP_K_GE) {
+        if (k < c + 0) v.x = 0.f;
+        if (k < c + 1) v.y = 0.f;
+        if (k < c + 2) v.z = 0.f;
+        if (k < c + 3) v.w = 0.f;
+    } else if (mask == MASK_KEEP_K_LE) {
+        if (k > c + 0) v.x = 0.f;
+        if (k > c + 1) v.y = 0.f;
+        if (k > c + 2) v.z = 0.f;
+        if (k > c + 3) v.w = 0.f;
     }
     return v;
 }
@@ -197,6 +212,101 @@ __device__ inline bool tn_keep(bool diag, int mode, int m, int n)
     return !diag || (mode == TILE_LOWER ? n <= m : n >= m);
 }
 
+// K loop of one tile.  FAST: both operands can be read with aligned 16-byte
+// loads over the whole tile width.
+template <bool FAST>
+__device__ inline void tn_mainloop(const TnLaunch &lp, const TnProblem &pr, const TnTile &tl,
+                                   float (&As)[2][BK][BM], float (&Bs)[2][BK][BN], floatx16 (&sum)[2][2])
+{
+    const int tid = threadIdx.x;
+    const int M = pr.M, N = pr.N, K = pr.K;
+    const float *__restrict__ A = pr.A;
+    const float *__restrict__ B = pr.B;
+    const int lda = pr.lda, ldb = pr.ldb;
+    const int mask_a = lp.mask_a, mask_b = lp.mask_b;
+
+    const int lrow = tid >> 5;         // 0..7 (and +8)
+    const int lcol = (tid & 31) << 2;  // 0..124
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int li = lane & 31, lh = lane >> 5;
+    const int ca = tl.m0 + lcol, cb = tl.n0 + lcol;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    if (tl.kt1 <= tl.kt0) return;
+
+    float4 ra[2], rb[2];
+    int k = tl.kbase + tl.kt0 * BK + lrow;
+    ra[0] = tn_load4<FAST>(A, k, ca, lda, K, M);
+    ra[1] = tn_load4<FAST>(A, k + 8, ca, lda, K, M);
+    rb[0] = tn_load4<FAST>(B, k, cb, ldb, K, N);
+    rb[1] = tn_load4<FAST>(B, k + 8, cb, ldb, K, N);
+    *reinterpret_cast<float4 *>(&As[0][lrow][lcol]) = tn_fix4<FAST>(ra[0], k, ca, K, M, mask_a);
+    *reinterpret_cast<float4 *>(&As[0][lrow + 8][lcol]) = tn_fix4<FAST>(ra[1], k + 8, ca, K, M, mask_a);
+    *reinterpret_cast<float4 *>(&Bs[0][lrow][lcol]) = tn_fix4<FAST>(rb[0], k, cb, K, N, mask_b);
+    *reinterpret_cast<float4 *>(&Bs[0][lrow + 8][lcol]) = tn_fix4<FAST>(rb[1], k + 8, cb, K, N, mask_b);
+    __syncthreads();
+
+    int folded = 0;
+    for (int kt = tl.kt0; kt < tl.kt1; ++kt) {
+        const int cur = (kt - tl.kt0) & 1;
+        const bool more = (kt + 1 < tl.kt1);
+        k += BK;
+        if (more) {
+            ra[0] = tn_load4<FAST>(A, k, ca, lda, K, M);
+            ra[1] = tn_load4<FAST>(A, k + 8, ca, lda, K, M);
+            rb[0] = tn_load4<FAST>(B, k, cb, ldb, K, N);
+            rb[1] = tn_load4<FAST>(B, k + 8, cb, ldb, K, N);
+        }
+        // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2s + lh
+        float2 af[BK / 2], bf[BK / 2];
+#pragma unroll
+        for (int s = 0; s < BK / 2; ++s) {
+            af[s] = *reinterpret_cast<const float2 *>(&As[cur][2 * s + lh][wm + 2 * li]);
+            bf[s] = *reinterpret_cast<const float2 *>(&Bs[cur][2 * s + lh][wn + 2 * li]);
+        }
+        // keep all LDS reads of the slab ahead of its MFMAs: the waits then count
+        // down read by read instead of draining before every group
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < BK / 2; ++s) {
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s].x, bf[s].x, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s].x, bf[s].y, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s].y, bf[s].x, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s].y, bf[s].y, acc[1][1], 0, 0, 0);
+        }
+        if (more) {
+            *reinterpret_cast<float4 *>(&As[cur ^ 1][lrow][lcol]) = tn_fix4<FAST>(ra[0], k, ca, K, M, mask_a);
+            *reinterpret_cast<float4 *>(&As[cur ^ 1][lrow + 8][lcol]) = tn_fix4<FAST>(ra[1], k + 8, ca, K, M, mask_a);
+            *reinterpret_cast<float4 *>(&Bs[cur ^ 1][lrow][lcol]) = tn_fix4<FAST>(rb[0], k, cb, K, N, mask_b);
+            *reinterpret_cast<float4 *>(&Bs[cur ^ 1][lrow + 8][lcol]) = tn_fix4<FAST>(rb[1], k + 8, cb, K, N, mask_b);
+        }
+        __syncthreads();
+        if (++folded == TN_CHUNK_SLABS) {
+            folded = 0;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    sum[i][j] += acc[i][j];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
+}
+
 __global__ __launch_bounds__(TN_THREADS, 2) void tn_gemm_kernel(const TnLaunch lp)
 {
     __shared__ float As[2][BK][BM];
@@ -205,91 +315,27 @@ __global__ __launch_bounds__(TN_THREADS, 2) void tn_gemm_kernel(const TnLaunch l
     const int tid = threadIdx.x;
     const TnTile tl = tn_locate(lp, tn_logical_tile(blockIdx.x, gridDim.x));
     const TnProblem &pr = lp.p[tl.prob];
-    const int M = pr.M, N = pr.N, K = pr.K;
-    const float *__restrict__ A = pr.A;
-    const float *__restrict__ B = pr.B;
-    const int lda = pr.lda, ldb = pr.ldb;
+    const int M = pr.M, N = pr.N;
 
-    const bool fast_a = (tl.m0 + BM <= M) && ((lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0);
-    const bool fast_b = (tl.n0 + BN <= N) && ((ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
+    const bool fast_a = (tl.m0 + BM <= M) && ((pr.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.A) & 15) == 0);
+    const bool fast_b = (tl.n0 + BN <= N) && ((pr.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.B) & 15) == 0);
 
-    const int lrow = tid >> 5;        // 0..7 (and +8)
-    const int lcol = (tid & 31) << 2; // 0..124
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int li = lane & 31, lh = lane >> 5;
 
-    floatx16 acc[2][2], sum[2][2];
+    floatx16 sum[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                acc[i][j][r] = 0.f;
-                sum[i][j][r] = 0.f;
-            }
+            for (int r = 0; r < 16; ++r) sum[i][j][r] = 0.f;
 
-    if (tl.kt1 > tl.kt0) {
-        float4 ra[2], rb[2];
-        {
-            const int k = tl.kbase + tl.kt0 * BK + lrow;
-            ra[0] = tn_load4(A, k, tl.m0 + lcol, lda, K, M, fast_a, lp.mask_a);
-            ra[1] = tn_load4(A, k + 8, tl.m0 + lcol, lda, K, M, fast_a, lp.mask_a);
-            rb[0] = tn_load4(B, k, tl.n0 + lcol, ldb, K, N, fast_b, lp.mask_b);
-            rb[1] = tn_load4(B, k + 8, tl.n0 + lcol, ldb, K, N, fast_b, lp.mask_b);
-        }
-        *reinterpret_cast<float4 *>(&As[0][lrow][lcol]) = ra[0];
-        *reinterpret_cast<float4 *>(&As[0][lrow + 8][lcol]) = ra[1];
-        *reinterpret_cast<float4 *>(&Bs[0][lrow][lcol]) = rb[0];
-        *reinterpret_cast<float4 *>(&Bs[0][lrow + 8][lcol]) = rb[1];
-        __syncthreads();
-
-        int folded = 0;
-        for (int kt = tl.kt0; kt < tl.kt1; ++kt) {
-            const int cur = (kt - tl.kt0) & 1;
-            const bool more = (kt + 1 < tl.kt1);
-            if (more) {
-                const int k = tl.kbase + (kt + 1) * BK + lrow;
-                ra[0] = tn_load4(A, k, tl.m0 + lcol, lda, K, M, fast_a, lp.mask_a);
-                ra[1] = tn_load4(A, k + 8, tl.m0 + lcol, lda, K, M, fast_a, lp.mask_a);
-                rb[0] = tn_load4(B, k, tl.n0 + lcol, ldb, K, N, fast_b, lp.mask_b);
-                rb[1] = tn_load4(B, k + 8, tl.n0 + lcol, ldb, K, N, fast_b, lp.mask_b);
-            }
-#pragma unroll
-            for (int s = 0; s < BK / 2; ++s) {
-                // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2s + lh
-                const float2 a = *reinterpret_cast<const float2 *>(&As[cur][2 * s + lh][wm + 2 * li]);
-                const float2 b = *reinterpret_cast<const float2 *>(&Bs[cur][2 * s + lh][wn + 2 * li]);
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc[0][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.y, acc[0][1], 0, 0, 0);
-                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.x, acc[1][0], 0, 0, 0);
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc[1][1], 0, 0, 0);
-            }
-            if (more) {
-                *reinterpret_cast<float4 *>(&As[cur ^ 1][lrow][lcol]) = ra[0];
-                *reinterpret_cast<float4 *>(&As[cur ^ 1][lrow + 8][lcol]) = ra[1];
-                *reinterpret_cast<float4 *>(&Bs[cur ^ 1][lrow][lcol]) = rb[0];
-                *reinterpret_cast<float4 *>(&Bs[cur ^ 1][lrow + 8][lcol]) = rb[1];
-            }
-            __syncthreads();
-            if (++folded == TN_CHUNK_SLABS) {
-                folded = 0;
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        sum[i][j] += acc[i][j];
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-                    }
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
+    if (fast_a && fast_b)
+        tn_mainloop<true>(lp, pr, tl, As, Bs, sum);
+    else
+        tn_mainloop<false>(lp, pr, tl, As, Bs, sum);
 
     // Accumulator layout of MFMA 32x32: register r of lane (li, lh) is row
     // 8*(r/4) + 4*lh + r%4, column li of the block; block (bi, bj) interleaves
