@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark: one K-FAC step (curvature + inversion + precondition) of a BERT-Large pipeline stage.
+
+A step is what one GPU of the paper's Chimera BERT-Large run has to do for
+K-FAC (figure "chimera_timeline": 2 stages x 3 encoder blocks per GPU,
+8 micro-batches of 32 x 128 tokens): for each of the 8 micro-batches one
+curvature work item per factor (72 factors: A and B of 36 linears), then one
+inversion per factor and one precondition per layer.  Inputs are synthetic
+(seeded torch.randn on the device; GELU of it for the second feed-forward
+linear's input; errors scaled by 1e-3) and are resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_F32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
+# HBM traffic of one curvature launch of the default workload, from the
+# FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (None = not measured).
+CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="workload id (4 = BERT-Large stage, the headline)")
+    ap.add_argument("--seed", type=int, default=221114133)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the K-FAC work; run it with --gpus 1 "
+              "(this build has no multi-GPU path)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2211_14133_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU: there is no CPU fallback")
+    lib = binding.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = synth.CONFIGS[args.config]
+    if cfg["bf16"]:
+        raise SystemExit("the bf16-input workload is not a benchmark configuration")
+    tokens, n_micro, blocks = cfg["tokens"], cfg["n_micro"], cfg["blocks"]
+    damping = synth.DAMPING
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+
+    # ------------------------------------------------------------------ inputs
+    layers = []  # (d_in, d_out)
+    xs = [[] for _ in range(n_micro)]  # per micro-batch: list of [tokens, d] inputs, A then B per layer
+    facs, invs, grads, outs = [], [], [], []
+    for b in range(blocks):
+        for (name, d_in, d_out, gelu) in cfg["layers"]:
+            layers.append((d_in, d_out))
+            g = torch.zeros(d_out, d_in, device=dev)
+            for m in range(n_micro):
+                x = torch.randn(tokens, d_in, device=dev, generator=gen)
+                if gelu:
+                    x = torch.nn.functional.gelu(x)
+                e = torch.randn(tokens, d_out, device=dev, generator=gen) * 1e-3
+                xs[m].append(x)
+                xs[m].append(e)
+                g.addmm_(e.t(), x, alpha=1.0 / (tokens * n_micro))
+            grads.append(g)
+            outs.append(torch.empty_like(g))
+            facs.append(torch.empty(d_in, d_in, device=dev))
+            facs.append(torch.empty(d_out, d_out, device=dev))
+            invs.append(torch.empty(d_in, d_in, device=dev))
+            invs.append(torch.empty(d_out, d_out, device=dev))
+    a_invs, b_invs = invs[0::2], invs[1::2]
+    infos = torch.zeros(len(facs), dtype=torch.int32, device=dev)
+
+    # ---------------------------------------------- marshal once, outside the loop
+    curv_items = [binding._curv_items(xs[m], facs) for m in range(n_micro)]
+    inv_items = binding._inv_items(facs, invs, infos)
+    prec_items = binding._prec_items(b_invs, a_invs, grads, outs)
+    nfac, nlay = len(facs), len(grads)
+    ws_bytes = max(lib.kfac_curvature_grouped_workspace(curv_items[0], nfac, binding.KFAC_F32),
+                   lib.kfac_invert_batched_workspace(inv_items, nfac),
+                   lib.kfac_precondition_grouped_workspace(prec_items, nlay))
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
+    ws_ptr = (ws.data_ptr() + 255) // 256 * 256
+    import ctypes
+
+    wsp = ctypes.c_void_p(ws_ptr)
+    stream = torch.cuda.current_stream()
+    sp = ctypes.c_void_p(stream.cuda_stream)
+    alpha = 1.0 / (tokens * n_micro)
+
+    def check(st):
+        if st != 0:
+            raise RuntimeError("kfac call failed: %s" % lib.kfac_status_string(st).decode())
+
+    def step(events=None):
+        if events is not None:
+            events["t0"].record(stream)
+        for m in range(n_micro):
+            if events is not None:
+                events["c0"][m].record(stream)
+            check(lib.kfac_curvature_grouped(curv_items[m], nfac, binding.KFAC_F32, alpha,
+                                             0.0 if m == 0 else 1.0, wsp, ws_bytes, sp))
+            if events is not None:
+                events["c1"][m].record(stream)
+        check(lib.kfac_invert_batched(inv_items, nfac, damping, wsp, ws_bytes, sp))
+        if events is not None:
+            events["t2"].record(stream)
+        check(lib.kfac_precondition_grouped(prec_items, nlay, wsp, ws_bytes, sp))
+        if events is not None:
+            events["t3"].record(stream)
+
+    def new_events():
+        ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+        return {"t0": ev(), "t2": ev(), "t3": ev(), "c0": [ev() for _ in range(n_micro)],
+                "c1": [ev() for _ in range(n_micro)]}
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    all_events = [new_events() for _ in range(args.steps)]
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(all_events[i])
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    ms_per_step = (t_end - t_start) * 1e3 / args.steps
+    if int(infos.abs().max().item()) != 0:
+        raise RuntimeError("an inversion reported failure: %s" % infos.tolist())
+
+    curv_launch_ms, curv_ms, inv_ms, prec_ms = [], 0.0, 0.0, 0.0
+    for ev in all_events:
+        for m in range(n_micro):
+            curv_launch_ms.append(ev["c0"][m].elapsed_time(ev["c1"][m]))
+        curv_ms += ev["t0"].elapsed_time(ev["c1"][n_micro - 1])
+        inv_ms += ev["c1"][n_micro - 1].elapsed_time(ev["t2"])
+        prec_ms += ev["t2"].elapsed_time(ev["t3"])
+    curv_ms /= args.steps
+    inv_ms /= args.steps
+    prec_ms /= args.steps
+    launch_ms = sum(curv_launch_ms) / len(curv_launch_ms)
+
+    # ------------------------------------------------- algorithmic work (useful flops)
+    f_curv_launch = sum(tokens * d * (d + 1) for (di, do) in layers for d in (di, do))
+    f_curv = f_curv_launch * n_micro
+    f_inv = sum(d ** 3 for (di, do) in layers for d in (di, do))
+    f_prec = sum(2 * do * di * (di + do) for (di, do) in layers)
+    f_total = f_curv + f_inv + f_prec
+    achieved = f_curv_launch / (launch_ms * 1e-3) / 1e12
+
+    result = {
+        "metric": "kfac_step_ms_bert_large_stage (curvature + inversion + precondition)",
+        "value": round(ms_per_step, 3),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: %d blocks x %d linears, %d micro-batches x %d tokens, fp32, damping %g"
+                        % (cfg["name"], blocks, len(cfg["layers"]), n_micro, tokens, damping),
+            "factors": nfac,
+            "layers": nlay,
+        },
+        "useful_tflops": round(f_total / (ms_per_step * 1e-3) / 1e12, 2),
+        "phases_ms": {"curvature": round(curv_ms, 3), "inversion": round(inv_ms, 3), "precondition": round(prec_ms, 3)},
+        "phases_useful_tflops": {
+            "curvature": round(f_curv / (curv_ms * 1e-3) / 1e12, 2),
+            "inversion": round(f_inv / (inv_ms * 1e-3) / 1e12, 2),
+            "precondition": round(f_prec / (prec_ms * 1e-3) / 1e12, 2),
+        },
+        "roofline": {
+            "kernel": "curvature_syrk_kernel (one launch = all %d factors of the stage for one micro-batch)" % nfac,
+            "bound": "mfma",
+            "achieved": round(achieved, 2),
+            "peak": PEAK_F32_MFMA_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(achieved / PEAK_F32_MFMA_TFLOPS, 4),
+            "traffic": CURVATURE_TRAFFIC_BYTES_PER_LAUNCH,
+            "launch_ms": round(launch_ms, 4),
+            "flops_per_launch": f_curv_launch,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping,
+                                              f_curv, f_inv, f_prec)
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping, f_curv, f_inv, f_prec):
+    """Time the fp64 oracle, as it stands, on one layer of the workload and scale to a step."""
+    from oracle import kfac_oracle as oracle
+
+    # sample: every linear of the first encoder block, micro-batch 0
+    nl = len(cfg["layers"])
+    hx = [xs[0][2 * i].cpu().numpy() for i in range(nl)]
+    he = [xs[0][2 * i + 1].cpu().numpy() for i in range(nl)]
+    hg = [grads[i].cpu().numpy() for i in range(nl)]
+    t0 = time.perf_counter()
+    fa = [oracle.curvature_update(x, 1.0 / tokens, 0.0) for x in hx]
+    fb = [oracle.curvature_update(e, 1.0 / tokens, 0.0) for e in he]
+    t1 = time.perf_counter()
+    ia = [oracle.invert(a, damping)[0] for a in fa]
+    ib = [oracle.invert(b, damping)[0] for b in fb]
+    t2 = time.perf_counter()
+    for g, a_inv, b_inv in zip(hg, ia, ib):
+        oracle.precondition(b_inv, g, a_inv)
+    t3 = time.perf_counter()
+    s_curv = sum(tokens * (di * (di + 1) + do * (do + 1)) for di, do in layers[:nl])
+    s_inv = sum(di ** 3 + do ** 3 for di, do in layers[:nl])
+    s_prec = sum(2 * do * di * (di + do) for di, do in layers[:nl])
+    est_ms = ((t1 - t0) * f_curv / s_curv + (t2 - t1) * f_inv / s_inv + (t3 - t2) * f_prec / s_prec) * 1e3
+    return {
+        "value": round(est_ms, 1),
+        "unit": "ms",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "fp64 oracle on the %d linears of one encoder block, one micro-batch of %d tokens: curvature "
+                  "%.2f s, inversion %.2f s, precondition %.2f s; each phase scaled by the step's useful flops "
+                  "over the sample's" % (nl, tokens, t1 - t0, t2 - t1, t3 - t2),
+    }
+
+
+if __name__ == "__main__":
+    main()

@@ -29,98 +29,194 @@ struct DiagLaunch {
     DiagItem it[DIAG_MAX_ITEMS];
 };
 
+constexpr int SB = 32;        // sub-block handled by one wave
+constexpr int LDT = NB + 4;   // LDS row stride in floats
+
+typedef float diag_floatx16 __attribute__((ext_vector_type(16)));
+
+enum DiagMask : int { DM_NONE = 0, DM_UPPER = 1, DM_LOWER = 2 };  // keep row <= col / row >= col
+
+__device__ inline float diag_bcast(float v, int src_lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+// One wave: acc = A^T B for a 32 x 32 output, A[k][m] = Aa[ak0 + k][am0 + m],
+// B[k][n] = Ba[bk0 + k][bn0 + n], k < K.  Masks act on the absolute LDS
+// coordinates (the arrays hold triangular matrices and their mirrors).
+__device__ inline diag_floatx16 sb_mma(const float (*Aa)[LDT], int ak0, int am0, int mask_a,
+                                       const float (*Ba)[LDT], int bk0, int bn0, int mask_b, int K, int lane)
+{
+    const int i = lane & 31, h = lane >> 5;
+    diag_floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll 8
+    for (int kk = 0; kk < K; kk += 2) {
+        const int ra = ak0 + kk + h, ca = am0 + i;
+        const int rb = bk0 + kk + h, cb = bn0 + i;
+        float a = Aa[ra][ca];
+        float b = Ba[rb][cb];
+        if ((mask_a == DM_UPPER && ra > ca) || (mask_a == DM_LOWER && ra < ca)) a = 0.f;
+        if ((mask_b == DM_UPPER && rb > cb) || (mask_b == DM_LOWER && rb < cb)) b = 0.f;
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    }
+    return acc;
+}
+
+// Store a wave's 32 x 32 result (MFMA accumulator layout) to C[cm0 + i][cn0 + j],
+// optionally also mirrored to Ct[cn0 + j][cm0 + i]; with `sub` the value
+// subtracted from what C holds (trailing update).
+__device__ inline void sb_store(diag_floatx16 acc, float (*C)[LDT], int cm0, int cn0, float scale, bool sub,
+                                float (*Ct)[LDT], int lane)
+{
+    const int j = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int i = 8 * (r >> 2) + 4 * h + (r & 3);
+        float v = scale * acc[r];
+        if (sub) v += C[cm0 + i][cn0 + j];
+        C[cm0 + i][cn0 + j] = v;
+        if (Ct != nullptr) Ct[cn0 + j][cm0 + i] = v;
+    }
+}
+
+// One wave factors the 32 x 32 diagonal sub-block at offset o (upper triangle of
+// Fs) as U^T U and inverts U.  Lane c (mod 32) keeps column c in registers; the
+// pivot row is passed around with readlane, so there is no LDS traffic and no
+// barrier inside.  Writes U (upper) to Fs and W = U^-1 (upper) plus its mirror
+// to Ss.  Returns the 1-based local index of the first bad pivot, or 0.
+__device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o, int lane)
+{
+    const int c = lane & 31;
+    float t[SB], rin[SB];
+    int bad = 0;
+#pragma unroll
+    for (int r = 0; r < SB; ++r) t[r] = (r <= c) ? Fs[o + r][o + c] : 0.f;
+#pragma unroll
+    for (int j = 0; j < SB; ++j) {
+        float piv = diag_bcast(t[j], j);
+        if (!(piv > 0.f) || !(piv <= 3.0e38f)) {
+            if (bad == 0) bad = j + 1;
+            piv = 1.f;
+        }
+        const float rinv = 1.0f / sqrtf(piv);
+        rin[j] = rinv;
+        const float u = t[j] * rinv;  // U[j][c] for c >= j
+        t[j] = u;
+#pragma unroll
+        for (int r = j + 1; r < SB; ++r) t[r] -= diag_bcast(u, r) * u;
+    }
+    float w[SB];
+#pragma unroll
+    for (int r = 0; r < SB; ++r) w[r] = (r == c) ? rin[r] : 0.f;
+#pragma unroll
+    for (int i = SB - 2; i >= 0; --i) {
+        float s = 0.f;
+#pragma unroll
+        for (int kx = i + 1; kx < SB; ++kx) s += diag_bcast(t[i], kx) * w[kx];  // U[i][kx] * W[kx][c]
+        if (i < c) w[i] = -s * rin[i];
+    }
+    if (lane < 32) {
+#pragma unroll
+        for (int r = 0; r < SB; ++r) {
+            if (r <= c) {
+                Fs[o + r][o + c] = t[r];
+                Ss[o + r][o + c] = w[r];
+                Ss[o + c][o + r] = w[r];
+            }
+        }
+    }
+    return bad;
+}
+
 // In:  F block = current (already updated) diagonal block, upper triangle.
 // Out: F block upper triangle = U_kk with U_kk^T U_kk = block,
 //      S block upper triangle = W = U_kk^-1, S block strict lower triangle = W^T.
-// A pivot that is not positive (or not finite) is recorded in *info as its
-// 1-based index in the whole matrix (first failure wins) and replaced by 1 so
-// that the arithmetic stays finite; the caller discards the result.
+// The block is handled in LDS as 4 x 4 sub-blocks of 32 with the same blocked
+// algorithm as the whole matrix: wave-level factorisation of a diagonal
+// sub-block, MFMA products for the panel solve, the trailing update and the
+// pairwise merges of the triangular inverse.  A block smaller than NB is padded
+// with the identity.  A pivot that is not positive (or not finite) is recorded
+// in *info as its 1-based index in the whole matrix (first failure wins) and
+// replaced by 1 so that the arithmetic stays finite; the caller discards the
+// result.
 __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaunch dl)
 {
-    __shared__ float T[NB][NB + 1];
-    __shared__ float dinv[NB];   // 1 / U[j][j]
+    __shared__ float Fs[NB][LDT];  // U above the diagonal, its mirror below
+    __shared__ float Ss[NB][LDT];  // W = U^-1 above the diagonal, its mirror below
 
     const DiagItem &it = dl.it[blockIdx.x];
     const int n = it.n;
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
 
     for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
         const int r = e / NB, c = e % NB;
-        float v = 0.f;
-        if (r < n && c < n && r <= c) v = it.F[(size_t)r * it.ldf + c];
-        T[r][c] = v;
+        float v = (r == c) ? 1.f : 0.f;
+        if (r < n && c < n) v = (r <= c) ? it.F[(size_t)r * it.ldf + c] : 0.f;
+        Fs[r][c] = v;
+        Ss[r][c] = 0.f;
     }
     __syncthreads();
 
-    // Right-looking factorisation.  Row j is final once steps < j are done; it
-    // is kept unscaled in T and the scale 1/U[j][j] is kept in dinv.
-    const int c = tid & (NB - 1);
-    const int par = tid >> 7;  // two threads per column: rows of even / odd offset
-    for (int j = 0; j < n; ++j) {
-        float piv = T[j][j];
-        if (!(piv > 0.f) || !(piv <= 3.0e38f)) {
-            if (tid == 0) atomicCAS(it.info, 0, it.pivot_base + j + 1);
-            piv = 1.f;
-        }
-        const float ujj = sqrtf(piv);
-        const float rinv = 1.0f / ujj;
-        if (tid == 0) dinv[j] = rinv;
-        if (c > j && c < n) {
-            const float ujc = T[j][c] * rinv;
-            for (int r = j + 1 + par; r <= c; r += 2) T[r][c] -= (T[j][r] * rinv) * ujc;
+    // Phase 1: right-looking factorisation over the four 32-wide panels.
+    for (int p = 0; p < NB / SB; ++p) {
+        const int o = p * SB;
+        if (wave == 0) {
+            const int bad = sb_factor_invert(Fs, Ss, o, lane);
+            if (bad != 0 && lane == 0 && o + bad <= n) atomicCAS(it.info, 0, it.pivot_base + o + bad);
         }
         __syncthreads();
-        if (tid == 0 && piv == 1.f && !(T[j][j] > 0.f)) T[j][j] = 1.f;
-    }
-    __syncthreads();
-
-    // U[j][c] = T[j][c] * dinv[j].  Scale in place (upper triangle, diagonal included).
-    for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
-        const int r = e / NB, cc = e % NB;
-        if (r < n && cc < n && r <= cc) T[r][cc] *= dinv[r];
-    }
-    __syncthreads();
-    for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
-        const int r = e / NB, cc = e % NB;
-        if (r < n && cc < n && r <= cc) it.F[(size_t)r * it.ldf + cc] = T[r][cc];
-    }
-
-    // W = U^-1 by back substitution, one column per pair of lanes: for column c,
-    // W[c][c] = 1/U[c][c] and, going up, W[i][c] = -(sum_{k=i+1..c} U[i][k] W[k][c]) / U[i][i].
-    // The two lanes of a pair split the sum by the parity of k and combine with a
-    // shuffle.  W[i][c] (i < c) is kept at T[c][i], the unused lower triangle.
-    {
-        const int col = tid >> 1;  // 0..127
-        const int p = tid & 1;
-        const bool active = col < n;
-        const float wcc = active ? dinv[col] : 0.f;
-        // all lanes of a wave run the same trip count (the largest column of the wave)
-        const int wave_last = min(n - 1, ((tid | 63) >> 1));
-        for (int i = wave_last - 1; i >= 0; --i) {
-            float part = 0.f;
-            if (active && i < col) {
-                // k runs over i+1..col; element k == col uses wcc
-                for (int k = i + 1 + p; k <= col; k += 2) {
-                    const float w = (k == col) ? wcc : T[col][k];
-                    part += T[i][k] * w;
-                }
+        // panel solve: U[p][q] = W_pp^T T[p][q], mirrored below the diagonal
+        for (int q = p + 1 + wave; q < NB / SB; q += 4) {
+            const diag_floatx16 acc = sb_mma(Ss, o, o, DM_UPPER, Fs, o, q * SB, DM_NONE, SB, lane);
+            sb_store(acc, Fs, o, q * SB, 1.f, false, Fs, lane);
+        }
+        __syncthreads();
+        // trailing update: T[q][r] -= U[p][q]^T U[p][r] for p < q <= r
+        int job = 0;
+        for (int q = p + 1; q < NB / SB; ++q)
+            for (int r = q; r < NB / SB; ++r, ++job) {
+                if ((job & 3) != wave) continue;
+                const diag_floatx16 acc = sb_mma(Fs, o, q * SB, DM_NONE, Fs, o, r * SB, DM_NONE, SB, lane);
+                sb_store(acc, Fs, q * SB, r * SB, -1.f, true, nullptr, lane);
             }
-            const float other = __shfl_xor(part, 1);
-            const float tot = part + other;
-            // both lanes of the pair store the same value, so each one later reads its own write
-            if (active && i < col) T[col][i] = -tot * dinv[i];
-        }
+        __syncthreads();
+    }
+
+    // U is final: write it out before the merges reuse the space above the diagonal.
+    for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
+        const int r = e / NB, c = e % NB;
+        if (r < n && c < n && r <= c) it.F[(size_t)r * it.ldf + c] = Fs[r][c];
     }
     __syncthreads();
-    for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
-        const int r = e / NB, cc = e % NB;
-        if (r < n && cc < n) {
-            float v;
-            if (r == cc) v = dinv[r];
-            else if (r < cc) v = T[cc][r];  // W[r][cc]
-            else v = T[r][cc];              // mirror: W[cc][r]
-            it.S[(size_t)r * it.lds + cc] = v;
+
+    // Phase 2: W = U^-1 by pairwise merges, [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
+    for (int b = SB; b < NB; b *= 2) {
+        const int nodes = NB / (2 * b), sub = b / SB;       // sub x sub output sub-blocks per node
+        const int jobs = nodes * sub * sub;
+        // Y = U12 W22 = L21^T W22, stored where U12 was
+        for (int job = wave; job < jobs; job += 4) {
+            const int nd = job / (sub * sub), bi = (job / sub) % sub, bj = job % sub;
+            const int r0 = nd * 2 * b, c1 = r0 + b;
+            const diag_floatx16 acc = sb_mma(Fs, c1, r0 + bi * SB, DM_NONE, Ss, c1, c1 + bj * SB, DM_UPPER, b, lane);
+            sb_store(acc, Fs, r0 + bi * SB, c1 + bj * SB, 1.f, false, nullptr, lane);
         }
+        __syncthreads();
+        // W12 = -W11 Y, read W11 through its mirror; mirrored again on output
+        for (int job = wave; job < jobs; job += 4) {
+            const int nd = job / (sub * sub), bi = (job / sub) % sub, bj = job % sub;
+            const int r0 = nd * 2 * b, c1 = r0 + b;
+            const diag_floatx16 acc = sb_mma(Ss, r0, r0 + bi * SB, DM_LOWER, Fs, r0, c1 + bj * SB, DM_NONE, b, lane);
+            sb_store(acc, Ss, r0 + bi * SB, c1 + bj * SB, -1.f, false, Ss, lane);
+        }
+        __syncthreads();
+    }
+
+    for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
+        const int r = e / NB, c = e % NB;
+        if (r < n && c < n) it.S[(size_t)r * it.lds + c] = Ss[r][c];
     }
 }
 

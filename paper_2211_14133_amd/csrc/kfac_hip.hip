@@ -64,14 +64,14 @@ struct TnBatch {
                 ++cnt;
                 ++i;
             }
-            lp.count = cnt;
-            lp.tile_mode = tile_mode;
-            lp.mask_a = mask_a;
-            lp.mask_b = mask_b;
-            lp.splits = splits;
-            lp.alpha = alpha;
-            lp.beta = beta;
-            lp.partial = partial;
+            lp.c.count = cnt;
+            lp.c.tile_mode = tile_mode;
+            lp.c.mask_a = mask_a;
+            lp.c.mask_b = mask_b;
+            lp.c.splits = splits;
+            lp.c.alpha = alpha;
+            lp.c.beta = beta;
+            lp.c.partial = partial;
             hipLaunchKernelGGL(tn_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, stream, lp);
             if (splits > 1)
                 hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / splits), dim3(TN_THREADS), 0, stream, lp);
@@ -110,7 +110,7 @@ bool curvature_plan(const kfac_curvature_item *items, int64_t count, CurvPlan &p
         kmin = std::min(kmin, items[i].n_tokens);
     }
     // a launch holds at most TN_MAX_PROBLEMS items; size the split for one launch
-    const int64_t launches = (count + TN_MAX_PROBLEMS - 1) / TN_MAX_PROBLEMS;
+    const int64_t launches = (count + SYRK_MAX_PROBLEMS - 1) / SYRK_MAX_PROBLEMS;
     pl.splits = choose_splits(std::max<int64_t>(1, tiles / std::max<int64_t>(1, launches)), kmin);
     pl.tiles = tiles;
     pl.ws = pl.splits > 1 ? align_up((size_t)tiles * pl.splits * BM * BN * sizeof(float), WS_ALIGN) : 0;
@@ -204,30 +204,41 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
     if (!curvature_plan(items, count, pl)) return KFAC_ERR_ARG;
     if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;
 
-    TnBatch b;
-    b.tile_mode = TILE_LOWER;
-    b.splits = pl.splits;
-    b.alpha = alpha;
-    b.beta = beta;
-    b.partial = static_cast<float *>(workspace);
-    // one launch per TN_MAX_PROBLEMS items; the partial buffer is indexed per launch, so
-    // give each launch its own slice
+    // One launch per SYRK_MAX_PROBLEMS items (a BERT-Large stage has 72 factors:
+    // one launch per micro-batch); each launch gets its own slice of the partial buffer.
     hipStream_t st = static_cast<hipStream_t>(stream);
-    size_t done = 0;
     float *part = static_cast<float *>(workspace);
-    while (done < (size_t)count) {
-        const size_t n = std::min<size_t>(TN_MAX_PROBLEMS, (size_t)count - done);
-        int64_t tiles = 0;
-        for (size_t i = done; i < done + n; ++i) {
-            const kfac_curvature_item &it = items[i];
-            const float *x = static_cast<const float *>(it.x);
-            b.add(x, (int)it.ldx, x, (int)it.ldx, it.factor, (int)it.ldf, (int)it.d, (int)it.d, (int)it.n_tokens,
-                  it.factor, (int)it.ldf);
-            tiles += tn_tiles((int)it.d, (int)it.d, TILE_LOWER);
+    for (int64_t done = 0; done < count;) {
+        const int64_t n = std::min<int64_t>(SYRK_MAX_PROBLEMS, count - done);
+        SyrkLaunch lp;
+        std::memset(&lp, 0, sizeof(lp));
+        int tiles = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            const kfac_curvature_item &it = items[done + i];
+            SyrkProblem &q = lp.p[i];
+            q.x = static_cast<const float *>(it.x);
+            q.factor = it.factor;
+            q.n = (int)it.n_tokens;
+            q.d = (int)it.d;
+            q.ldx = (int)it.ldx;
+            q.ldf = (int)it.ldf;
+            q.tile_begin = tiles;
+            tiles += tn_tiles(q.d, q.d, TILE_LOWER) * pl.splits;
         }
-        b.partial = part;
-        if (b.launch(st) != hipSuccess) return KFAC_ERR_HIP;
-        if (pl.splits > 1) part += (size_t)tiles * pl.splits * BM * BN;
+        lp.c.count = (int)n;
+        lp.c.tile_mode = TILE_LOWER;
+        lp.c.mask_a = MASK_NONE;
+        lp.c.mask_b = MASK_NONE;
+        lp.c.splits = pl.splits;
+        lp.c.alpha = alpha;
+        lp.c.beta = beta;
+        lp.c.partial = part;
+        hipLaunchKernelGGL(curvature_syrk_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lp);
+        if (pl.splits > 1) {
+            hipLaunchKernelGGL(curvature_reduce_kernel, dim3(tiles / pl.splits), dim3(TN_THREADS), 0, st, lp);
+            part += (size_t)tiles * BM * BN;
+        }
+        if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
         done += n;
     }
     return KFAC_OK;

@@ -47,16 +47,52 @@ struct TnProblem {
     int tile_begin;    // first logical tile (tile * splits + split) of this problem
 };
 
-struct TnLaunch {
-    TnProblem p[TN_MAX_PROBLEMS];
+struct TnCommon {
     int count;
     int tile_mode;  // TILE_LOWER / TILE_UPPER need M == N
     int mask_a;
     int mask_b;
-    int splits;     // > 1: partial tiles go to `partial`, tn_reduce_kernel finishes
+    int splits;     // > 1: partial tiles go to `partial`, the reduce kernel finishes
     float alpha;
     float beta;
     float *partial;  // [total logical tiles][BM * BN]
+};
+
+// General launch: up to TN_MAX_PROBLEMS arbitrary problems.
+struct TnLaunch {
+    TnProblem p[TN_MAX_PROBLEMS];
+    TnCommon c;
+    __device__ int tile_begin(int i) const { return p[i].tile_begin; }
+    __device__ TnProblem problem(int i) const { return p[i]; }
+};
+
+// Curvature launch: factor = beta * factor + alpha * x^T x.  Both operands are x
+// and the output is mirrored onto itself, so the descriptor is small enough for
+// every factor of a pipeline stage to go into one launch.
+constexpr int SYRK_MAX_PROBLEMS = 80;
+
+struct SyrkProblem {
+    const float *x;  // n x d, ldx
+    float *factor;   // d x d, ldf
+    int n, d, ldx, ldf;
+    int tile_begin;
+    int pad_;
+};
+
+struct SyrkLaunch {
+    SyrkProblem p[SYRK_MAX_PROBLEMS];
+    TnCommon c;
+    __device__ int tile_begin(int i) const { return p[i].tile_begin; }
+    __device__ TnProblem problem(int i) const
+    {
+        const SyrkProblem &q = p[i];
+        TnProblem r;
+        r.A = q.x; r.B = q.x; r.C = q.factor; r.Ct = q.factor; r.guard = nullptr;
+        r.M = q.d; r.N = q.d; r.K = q.n;
+        r.lda = q.ldx; r.ldb = q.ldx; r.ldc = q.ldf; r.ldct = q.ldf;
+        r.tile_begin = q.tile_begin;
+        return r;
+    }
 };
 
 __host__ __device__ inline int tn_tiles(int M, int N, int mode)
@@ -121,13 +157,15 @@ struct TnTile {
     bool diag;
 };
 
-__device__ inline TnTile tn_locate(const TnLaunch &lp, int t)
+template <class L>
+__device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
 {
+    const TnCommon &lp = ll.c;
     TnTile tl;
     int pi = 0;
     for (int i = 1; i < lp.count; ++i)
-        if (lp.p[i].tile_begin <= t) pi = i;
-    const TnProblem &pr = lp.p[pi];
+        if (ll.tile_begin(i) <= t) pi = i;
+    pr = ll.problem(pi);
     const int local = t - pr.tile_begin;
     const int tile = local / lp.splits;
     tl.prob = pi;
@@ -215,7 +253,7 @@ __device__ inline bool tn_keep(bool diag, int mode, int m, int n)
 // K loop of one tile.  FAST: both operands can be read with aligned 16-byte
 // loads over the whole tile width.
 template <bool FAST>
-__device__ inline void tn_mainloop(const TnLaunch &lp, const TnProblem &pr, const TnTile &tl,
+__device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, const TnTile &tl,
                                    float (&As)[2][BK][BM], float (&Bs)[2][BK][BN], floatx16 (&sum)[2][2])
 {
     const int tid = threadIdx.x;
@@ -307,14 +345,13 @@ __device__ inline void tn_mainloop(const TnLaunch &lp, const TnProblem &pr, cons
         for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
 }
 
-__global__ __launch_bounds__(TN_THREADS, 2) void tn_gemm_kernel(const TnLaunch lp)
+template <class L>
+__device__ inline void tn_tile_body(const L &ll, float (&As)[2][BK][BM], float (&Bs)[2][BK][BN])
 {
-    __shared__ float As[2][BK][BM];
-    __shared__ float Bs[2][BK][BN];
-
+    const TnCommon &lp = ll.c;
     const int tid = threadIdx.x;
-    const TnTile tl = tn_locate(lp, tn_logical_tile(blockIdx.x, gridDim.x));
-    const TnProblem &pr = lp.p[tl.prob];
+    TnProblem pr;
+    const TnTile tl = tn_locate(ll, tn_logical_tile(blockIdx.x, gridDim.x), pr);
     const int M = pr.M, N = pr.N;
 
     const bool fast_a = (tl.m0 + BM <= M) && ((pr.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.A) & 15) == 0);
@@ -428,11 +465,13 @@ __global__ __launch_bounds__(TN_THREADS, 2) void tn_gemm_kernel(const TnLaunch l
 // Second pass of a split-K launch: adds the partial tiles of each output tile in
 // split order (fixed order: the result does not depend on scheduling) and
 // applies the same epilogue as the main kernel.  One workgroup per output tile.
-__global__ __launch_bounds__(TN_THREADS) void tn_reduce_kernel(const TnLaunch lp)
+template <class L>
+__device__ inline void tn_reduce_body(const L &ll)
 {
+    const TnCommon &lp = ll.c;
     const int t0 = blockIdx.x * lp.splits;  // logical index of split 0 of this output tile
-    const TnTile tl = tn_locate(lp, t0);
-    const TnProblem &pr = lp.p[tl.prob];
+    TnProblem pr;
+    const TnTile tl = tn_locate(ll, t0, pr);
     if (pr.guard != nullptr && *pr.guard != 0) return;
     const float *P = lp.partial + (size_t)t0 * (BM * BN);
     const int tid = threadIdx.x;
@@ -463,5 +502,25 @@ __global__ __launch_bounds__(TN_THREADS) void tn_reduce_kernel(const TnLaunch lp
         }
     }
 }
+
+__global__ __launch_bounds__(TN_THREADS, 2) void tn_gemm_kernel(const TnLaunch lp)
+{
+    __shared__ float As[2][BK][BM];
+    __shared__ float Bs[2][BK][BN];
+    tn_tile_body(lp, As, Bs);
+}
+
+__global__ __launch_bounds__(TN_THREADS) void tn_reduce_kernel(const TnLaunch lp) { tn_reduce_body(lp); }
+
+// The curvature work item: the same tile body under its own name, so that its
+// launches can be told apart in a kernel trace.
+__global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_kernel(const SyrkLaunch lp)
+{
+    __shared__ float As[2][BK][BM];
+    __shared__ float Bs[2][BK][BN];
+    tn_tile_body(lp, As, Bs);
+}
+
+__global__ __launch_bounds__(TN_THREADS) void curvature_reduce_kernel(const SyrkLaunch lp) { tn_reduce_body(lp); }
 
 }  // namespace kfac
