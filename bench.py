@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--config", type=int, default=4, help="workload id (4 = BERT-Large stage, the headline)")
     ap.add_argument("--seed", type=int, default=221114133)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain 1 GiB device copies (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -53,6 +55,14 @@ def main():
     lib = binding.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": src.numel() * 4, "copies": 3}))
+        return
     cfg = synth.CONFIGS[args.config]
     if cfg["bf16"]:
         raise SystemExit("the bf16-input workload is not a benchmark configuration")

@@ -218,27 +218,29 @@ __device__ inline float4 tn_load4(const float *P, int k, int c, int ld, int K, i
     return v;
 }
 
-template <bool FAST>
+template <bool FAST, bool MASKED>
 __device__ inline float4 tn_fix4(float4 v, int k, int c, int K, int W, int mask)
 {
-    if (k >= K) v = make_float4(0.f, 0.f, 0.f, 0.f);
+    // branch-free on purpose: the K loop must stay one basic block
+    const bool kz = k >= K;
+    bool z0 = kz, z1 = kz, z2 = kz, z3 = kz;
     if (!FAST) {
-        if (c + 0 >= W) v.x = 0.f;
-        if (c + 1 >= W) v.y = 0.f;
-        if (c + 2 >= W) v.z = 0.f;
-        if (c + 3 >= W) v.w = 0.f;
+        z0 |= (c + 0 >= W);
+        z1 |= (c + 1 >= W);
+        z2 |= (c + 2 >= W);
+        z3 |= (c + 3 >= W);
     }
-    if (mask == MASK_KEEP_K_GE) {
-        if (k < c + 0) v.x = 0.f;
-        if (k < c + 1) v.y = 0.f;
-        if (k < c + 2) v.z = 0.f;
-        if (k < c + 3) v.w = 0.f;
-    } else if (mask == MASK_KEEP_K_LE) {
-        if (k > c + 0) v.x = 0.f;
-        if (k > c + 1) v.y = 0.f;
-        if (k > c + 2) v.z = 0.f;
-        if (k > c + 3) v.w = 0.f;
+    if (MASKED) {
+        const bool ge = (mask == MASK_KEEP_K_GE), le = (mask == MASK_KEEP_K_LE);
+        z0 |= (ge & (k < c + 0)) | (le & (k > c + 0));
+        z1 |= (ge & (k < c + 1)) | (le & (k > c + 1));
+        z2 |= (ge & (k < c + 2)) | (le & (k > c + 2));
+        z3 |= (ge & (k < c + 3)) | (le & (k > c + 3));
     }
+    v.x = z0 ? 0.f : v.x;
+    v.y = z1 ? 0.f : v.y;
+    v.z = z2 ? 0.f : v.z;
+    v.w = z3 ? 0.f : v.w;
     return v;
 }
 
@@ -250,11 +252,28 @@ __device__ inline bool tn_keep(bool diag, int mode, int m, int n)
     return !diag || (mode == TILE_LOWER ? n <= m : n >= m);
 }
 
+constexpr int TN_STAGES = 3;  // LDS ring: slab s lives in stage s % 3
+
+// sched_group_barrier masks
+constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200;
+
 // K loop of one tile.  FAST: both operands can be read with aligned 16-byte
 // loads over the whole tile width.
-template <bool FAST>
+//
+// Software pipeline (slab = BK rows of K; G = global load into staging
+// registers, W = staging -> LDS, R = LDS -> MFMA operand registers, M = MFMA):
+//   iteration s:  W(s+2)  G(s+3)  R(second half of s)  M(first half of s)
+//                 R(first half of s+1)  M(second half of s)  barrier
+// so every load is issued a full iteration (or half of one) before its use and
+// sits in the shadow of the 32 MFMAs of the iteration.  Three LDS stages make
+// one barrier per iteration enough: W(s+2) overwrites the stage of slab s-1,
+// which every wave finished reading before the previous barrier.  Loads past
+// the end of the K range are clamped to valid rows and their data is never
+// used, which keeps the loop body free of branches.
+template <bool FAST, bool MASKED>
 __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, const TnTile &tl,
-                                   float (&As)[2][BK][BM], float (&Bs)[2][BK][BN], floatx16 (&sum)[2][2])
+                                   float (&As)[TN_STAGES][BK][BM], float (&Bs)[TN_STAGES][BK][BN],
+                                   floatx16 (&sum)[2][2])
 {
     const int tid = threadIdx.x;
     const int M = pr.M, N = pr.N, K = pr.K;
@@ -278,55 +297,94 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    if (tl.kt1 <= tl.kt0) return;
+    const int nslab = tl.kt1 - tl.kt0;
+    if (nslab <= 0) return;
 
-    float4 ra[2], rb[2];
-    int k = tl.kbase + tl.kt0 * BK + lrow;
-    ra[0] = tn_load4<FAST>(A, k, ca, lda, K, M);
-    ra[1] = tn_load4<FAST>(A, k + 8, ca, lda, K, M);
-    rb[0] = tn_load4<FAST>(B, k, cb, ldb, K, N);
-    rb[1] = tn_load4<FAST>(B, k + 8, cb, ldb, K, N);
-    *reinterpret_cast<float4 *>(&As[0][lrow][lcol]) = tn_fix4<FAST>(ra[0], k, ca, K, M, mask_a);
-    *reinterpret_cast<float4 *>(&As[0][lrow + 8][lcol]) = tn_fix4<FAST>(ra[1], k + 8, ca, K, M, mask_a);
-    *reinterpret_cast<float4 *>(&Bs[0][lrow][lcol]) = tn_fix4<FAST>(rb[0], k, cb, K, N, mask_b);
-    *reinterpret_cast<float4 *>(&Bs[0][lrow + 8][lcol]) = tn_fix4<FAST>(rb[1], k + 8, cb, K, N, mask_b);
+    float4 ra[2], rb[2];      // staging registers of one slab
+    float2 fa[2][4], fb[2][4];  // MFMA operands: [half of the slab][k step pair]
+    int kg = tl.kbase + tl.kt0 * BK + lrow;  // K row of the slab in the staging registers
+
+#define TN_G()                                                         \
+    do {                                                               \
+        ra[0] = tn_load4<FAST>(A, kg, ca, lda, K, M);                  \
+        ra[1] = tn_load4<FAST>(A, kg + 8, ca, lda, K, M);              \
+        rb[0] = tn_load4<FAST>(B, kg, cb, ldb, K, N);                  \
+        rb[1] = tn_load4<FAST>(B, kg + 8, cb, ldb, K, N);              \
+    } while (0)
+#define TN_W(st)                                                                                                  \
+    do {                                                                                                          \
+        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(ra[0], kg, ca, K, M, mask_a);            \
+        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(ra[1], kg + 8, ca, K, M, mask_a);    \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(rb[0], kg, cb, K, N, mask_b);            \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(rb[1], kg + 8, cb, K, N, mask_b);    \
+        kg += BK;                                                                                                 \
+    } while (0)
+    // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2*step + lh
+#define TN_R(st, half)                                                                                            \
+    do {                                                                                                          \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                           \
+            fa[half][q] = *reinterpret_cast<const float2 *>(&As[st][8 * (half) + 2 * q + lh][wm + 2 * li]);       \
+            fb[half][q] = *reinterpret_cast<const float2 *>(&Bs[st][8 * (half) + 2 * q + lh][wn + 2 * li]);       \
+        }                                                                                                         \
+    } while (0)
+#define TN_M(half)                                                                                                \
+    do {                                                                                                          \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                           \
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].x, acc[0][0], 0, 0, 0);   \
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].y, acc[0][1], 0, 0, 0);   \
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].x, acc[1][0], 0, 0, 0);   \
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[1][1], 0, 0, 0);   \
+        }                                                                                                         \
+    } while (0)
+
+    // prologue: slabs 0 and 1 in LDS, slab 2 in flight, first half of slab 0 in registers
+    TN_G();
+    TN_W(0);
+    TN_G();
+    TN_W(1);
+    TN_G();
     __syncthreads();
+    TN_R(0, 0);
 
+    int st0 = 0, st1 = 1, st2 = 2;  // stages of slabs s, s+1, s+2
     int folded = 0;
-    for (int kt = tl.kt0; kt < tl.kt1; ++kt) {
-        const int cur = (kt - tl.kt0) & 1;
-        const bool more = (kt + 1 < tl.kt1);
-        k += BK;
-        if (more) {
-            ra[0] = tn_load4<FAST>(A, k, ca, lda, K, M);
-            ra[1] = tn_load4<FAST>(A, k + 8, ca, lda, K, M);
-            rb[0] = tn_load4<FAST>(B, k, cb, ldb, K, N);
-            rb[1] = tn_load4<FAST>(B, k + 8, cb, ldb, K, N);
-        }
-        // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2s + lh
-        float2 af[BK / 2], bf[BK / 2];
+    for (int s = 0; s < nslab; ++s) {
+        TN_W(st2);    // slab s+2 (loaded one iteration ago)
+        TN_G();       // slab s+3
+        TN_R(st0, 1);
+        TN_M(0);
+        TN_R(st1, 0);
+        TN_M(1);
+        // interleave: the LDS writes, global loads and the first batch of LDS reads go
+        // one by one between the first MFMAs; the second batch between the MFMAs of
+        // the second half
 #pragma unroll
-        for (int s = 0; s < BK / 2; ++s) {
-            af[s] = *reinterpret_cast<const float2 *>(&As[cur][2 * s + lh][wm + 2 * li]);
-            bf[s] = *reinterpret_cast<const float2 *>(&Bs[cur][2 * s + lh][wn + 2 * li]);
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
         }
-        // keep all LDS reads of the slab ahead of its MFMAs: the waits then count
-        // down read by read instead of draining before every group
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int s = 0; s < BK / 2; ++s) {
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s].x, bf[s].x, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s].x, bf[s].y, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s].y, bf[s].x, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s].y, bf[s].y, acc[1][1], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_DS_WRITE, 1, 0);
         }
-        if (more) {
-            *reinterpret_cast<float4 *>(&As[cur ^ 1][lrow][lcol]) = tn_fix4<FAST>(ra[0], k, ca, K, M, mask_a);
-            *reinterpret_cast<float4 *>(&As[cur ^ 1][lrow + 8][lcol]) = tn_fix4<FAST>(ra[1], k + 8, ca, K, M, mask_a);
-            *reinterpret_cast<float4 *>(&Bs[cur ^ 1][lrow][lcol]) = tn_fix4<FAST>(rb[0], k, cb, K, N, mask_b);
-            *reinterpret_cast<float4 *>(&Bs[cur ^ 1][lrow + 8][lcol]) = tn_fix4<FAST>(rb[1], k + 8, cb, K, N, mask_b);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, FAST ? 1 : 4, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 4, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 12, 0);
         __syncthreads();
+        const int t = st0;
+        st0 = st1;
+        st1 = st2;
+        st2 = t;
         if (++folded == TN_CHUNK_SLABS) {
             folded = 0;
 #pragma unroll
@@ -339,6 +397,10 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
                 }
         }
     }
+#undef TN_G
+#undef TN_W
+#undef TN_R
+#undef TN_M
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -346,7 +408,7 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
 }
 
 template <class L>
-__device__ inline void tn_tile_body(const L &ll, float (&As)[2][BK][BM], float (&Bs)[2][BK][BN])
+__device__ inline void tn_tile_body(const L &ll, float (&As)[TN_STAGES][BK][BM], float (&Bs)[TN_STAGES][BK][BN])
 {
     const TnCommon &lp = ll.c;
     const int tid = threadIdx.x;
@@ -369,10 +431,18 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[2][BK][BM], float (
 #pragma unroll
             for (int r = 0; r < 16; ++r) sum[i][j][r] = 0.f;
 
-    if (fast_a && fast_b)
-        tn_mainloop<true>(lp, pr, tl, As, Bs, sum);
-    else
-        tn_mainloop<false>(lp, pr, tl, As, Bs, sum);
+    const bool masked = (lp.mask_a | lp.mask_b) != 0;
+    if (fast_a && fast_b) {
+        if (masked)
+            tn_mainloop<true, true>(lp, pr, tl, As, Bs, sum);
+        else
+            tn_mainloop<true, false>(lp, pr, tl, As, Bs, sum);
+    } else {
+        if (masked)
+            tn_mainloop<false, true>(lp, pr, tl, As, Bs, sum);
+        else
+            tn_mainloop<false, false>(lp, pr, tl, As, Bs, sum);
+    }
 
     // Accumulator layout of MFMA 32x32: register r of lane (li, lh) is row
     // 8*(r/4) + 4*lh + r%4, column li of the block; block (bi, bj) interleaves
@@ -505,8 +575,8 @@ __device__ inline void tn_reduce_body(const L &ll)
 
 __global__ __launch_bounds__(TN_THREADS, 2) void tn_gemm_kernel(const TnLaunch lp)
 {
-    __shared__ float As[2][BK][BM];
-    __shared__ float Bs[2][BK][BN];
+    __shared__ float As[TN_STAGES][BK][BM];
+    __shared__ float Bs[TN_STAGES][BK][BN];
     tn_tile_body(lp, As, Bs);
 }
 
@@ -516,8 +586,8 @@ __global__ __launch_bounds__(TN_THREADS) void tn_reduce_kernel(const TnLaunch lp
 // launches can be told apart in a kernel trace.
 __global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_kernel(const SyrkLaunch lp)
 {
-    __shared__ float As[2][BK][BM];
-    __shared__ float Bs[2][BK][BN];
+    __shared__ float As[TN_STAGES][BK][BM];
+    __shared__ float Bs[TN_STAGES][BK][BN];
     tn_tile_body(lp, As, Bs);
 }
 
