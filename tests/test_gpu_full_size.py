@@ -1,0 +1,113 @@
+"""Parity at the benchmark's full size (one BERT-Large pipeline stage, 8 micro-batches),
+in the launch configuration bench.py times: grouped curvature (72 factors per launch),
+batched inversion (72 matrices), grouped precondition (36 layers).
+
+The oracle cannot redo the whole stage in seconds, so the check is made of
+ * sampled factor entries, each recomputed by the oracle as a plain dot product;
+ * every inverse through its residual against the GPU's own factor
+   (rows sampled; the fp64 products are formed on the host);
+ * every preconditioned gradient through sampled entries of B~ P A~ = G;
+ * two layers (one attention linear, the second feed-forward linear whose A is
+   4096-dimensional and the worst conditioned) redone end to end by the oracle.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2211_14133_amd import synth  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+def test_stage_full_size(oracle):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2211_14133_amd as k
+
+    cfg = synth.CONFIGS[4]
+    tokens, n_micro, blocks = cfg["tokens"], cfg["n_micro"], cfg["blocks"]
+    lam = synth.DAMPING
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.SEED)
+    layers, xs, grads = [], [[] for _ in range(n_micro)], []
+    for b in range(blocks):
+        for (name, d_in, d_out, gelu) in cfg["layers"]:
+            layers.append((name, d_in, d_out))
+            g = torch.zeros(d_out, d_in, device=dev, dtype=torch.float64)
+            for m in range(n_micro):
+                x = torch.randn(tokens, d_in, device=dev, generator=gen)
+                if gelu:
+                    x = torch.nn.functional.gelu(x)
+                e = torch.randn(tokens, d_out, device=dev, generator=gen) * 1e-3
+                xs[m] += [x, e]
+                g += e.double().t() @ x.double()
+            grads.append((g / (tokens * n_micro)).float())
+    facs = [torch.empty(d, d, device=dev) for (_, di, do) in layers for d in (di, do)]
+    invs = [torch.empty_like(f) for f in facs]
+    outs = [torch.empty_like(g) for g in grads]
+    alpha = 1.0 / (tokens * n_micro)
+    print("curvature", flush=True)
+    for m in range(n_micro):
+        k.kfac_curvature_grouped(xs[m], facs, alpha, 0.0 if m == 0 else 1.0)
+    print("inversion", flush=True)
+    infos = k.kfac_invert_batched(facs, lam, invs)
+    print("precondition", flush=True)
+    k.kfac_precondition_grouped(invs[1::2], invs[0::2], grads, outs)
+    torch.cuda.synchronize()
+    assert np.all(infos.cpu().numpy() == 0)
+
+    rng = np.random.default_rng(7)
+    # --- sampled factor entries against plain fp64 dot products
+    print("sampled factor entries", flush=True)
+    worst = 0.0
+    for fi in range(0, len(facs), 5):
+        d = facs[fi].shape[0]
+        scale = float(facs[fi].diagonal().abs().max())
+        for _ in range(4):
+            i, j = int(rng.integers(d)), int(rng.integers(d))
+            want = 0.0
+            for m in range(n_micro):
+                cols = xs[m][fi][:, [i, j]].cpu().numpy()
+                want += oracle.curvature_entry(cols, 0, 1, alpha)
+            got = float(facs[fi][i, j])
+            assert got == float(facs[fi][j, i])
+            worst = max(worst, abs(got - want) / scale)
+    print("  worst |err| / max diag = %.2e" % worst, flush=True)
+    assert worst <= 1e-5
+    # --- every inverse: residual of sampled rows, products in fp64
+    print("inverse residuals", flush=True)
+    for fi, (f, v) in enumerate(zip(facs, invs)):
+        d = f.shape[0]
+        rows = torch.from_numpy(rng.integers(d, size=8)).to(dev)
+        ft = f.double() + lam * torch.eye(d, device=dev, dtype=torch.float64)
+        res = ft[rows] @ v.double()
+        res[torch.arange(8), rows] -= 1.0
+        r = float(res.norm() / np.sqrt(8))
+        assert r <= 2e-3, (fi, d, r)
+        assert torch.equal(v, v.t())
+    # --- every preconditioned gradient: sampled entries of (B + lam I) P (A + lam I) = G
+    print("precondition identity", flush=True)
+    for li, (name, d_in, d_out) in enumerate(layers):
+        a = facs[2 * li].double() + lam * torch.eye(d_in, device=dev, dtype=torch.float64)
+        b = facs[2 * li + 1].double() + lam * torch.eye(d_out, device=dev, dtype=torch.float64)
+        rows = torch.from_numpy(rng.integers(d_out, size=4)).to(dev)
+        back = b[rows] @ outs[li].double() @ a
+        g = grads[li].double()[rows]
+        err = float((back - g).norm() / g.norm())
+        assert err <= 5e-3, (li, name, err)
+    # --- two layers end to end against the oracle
+    for li in (1, 5):
+        name, d_in, d_out = layers[li]
+        print("oracle chain for layer", li, name, d_in, d_out, flush=True)
+        hx = [xs[m][2 * li].cpu().numpy() for m in range(n_micro)]
+        he = [xs[m][2 * li + 1].cpu().numpy() for m in range(n_micro)]
+        g = grads[li].cpu().numpy()
+        oa, ob, oai, obi, op = oracle.kfac_chain(hx, he, g, lam)
+        ea = oracle.rel_fro(facs[2 * li].cpu().numpy(), oa)
+        eb = oracle.rel_fro(facs[2 * li + 1].cpu().numpy(), ob)
+        eai = oracle.rel_fro(invs[2 * li].cpu().numpy(), oai)
+        ep = oracle.rel_fro(outs[li].cpu().numpy(), op)
+        print("  A %.2e  B %.2e  A^-1 %.2e  P %.2e" % (ea, eb, eai, ep), flush=True)
+        assert ea <= 1e-4 and eb <= 1e-4 and ep <= 5e-3

@@ -342,3 +342,8 @@ def test_chain_config1_and_kronecker(k, oracle):
 
 def test_chain_config2_bert_base_block(k, oracle):
     run_chain(k, oracle, 2)
+
+
+def test_chain_config3_bert_large_block(k, oracle):
+    # the hard case for conditioning: FFN2's A factor has d = tokens = 4096 (smallest eigenvalue ~ damping)
+    run_chain(k, oracle, 3, layers=("q", "ffn1", "ffn2"))
