@@ -300,24 +300,25 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
     const int nslab = tl.kt1 - tl.kt0;
     if (nslab <= 0) return;
 
-    float4 ra[2], rb[2];      // staging registers of one slab
+    float4 ra[2][2], rb[2][2];  // two sets of staging registers (slabs alternate between them)
     float2 fa[2][4], fb[2][4];  // MFMA operands: [half of the slab][k step pair]
-    int kg = tl.kbase + tl.kt0 * BK + lrow;  // K row of the slab in the staging registers
+    int kw = tl.kbase + tl.kt0 * BK + lrow;  // K row (of this thread) of the next slab to go to LDS
 
-#define TN_G()                                                         \
-    do {                                                               \
-        ra[0] = tn_load4<FAST>(A, kg, ca, lda, K, M);                  \
-        ra[1] = tn_load4<FAST>(A, kg + 8, ca, lda, K, M);              \
-        rb[0] = tn_load4<FAST>(B, kg, cb, ldb, K, N);                  \
-        rb[1] = tn_load4<FAST>(B, kg + 8, cb, ldb, K, N);              \
+#define TN_G(set, ahead)                                                        \
+    do {                                                                        \
+        const int kg_ = kw + (ahead) * BK;                                      \
+        ra[set][0] = tn_load4<FAST>(A, kg_, ca, lda, K, M);                     \
+        ra[set][1] = tn_load4<FAST>(A, kg_ + 8, ca, lda, K, M);                 \
+        rb[set][0] = tn_load4<FAST>(B, kg_, cb, ldb, K, N);                     \
+        rb[set][1] = tn_load4<FAST>(B, kg_ + 8, cb, ldb, K, N);                 \
     } while (0)
-#define TN_W(st)                                                                                                  \
-    do {                                                                                                          \
-        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(ra[0], kg, ca, K, M, mask_a);            \
-        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(ra[1], kg + 8, ca, K, M, mask_a);    \
-        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(rb[0], kg, cb, K, N, mask_b);            \
-        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(rb[1], kg + 8, cb, K, N, mask_b);    \
-        kg += BK;                                                                                                 \
+#define TN_W(st, set)                                                                                                  \
+    do {                                                                                                               \
+        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(ra[set][0], kw, ca, K, M, mask_a);     \
+        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(ra[set][1], kw + 8, ca, K, M, mask_a); \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(rb[set][0], kw, cb, K, N, mask_b);     \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(rb[set][1], kw + 8, cb, K, N, mask_b); \
+        kw += BK;                                                                                                      \
     } while (0)
     // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2*step + lh
 #define TN_R(st, half)                                                                                            \
@@ -336,56 +337,60 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[1][1], 0, 0, 0);   \
         }                                                                                                         \
     } while (0)
+    // One iteration: slab s is consumed; slab s+2 (loaded two iterations ago into `set`)
+    // goes to LDS and slab s+4 is requested into the same registers.  The LDS writes,
+    // global loads and operand reads are spread one by one between the MFMAs.
+#define TN_ITER(set)                                                                 \
+    do {                                                                             \
+        TN_W(st2, set);                                                              \
+        TN_G(set, 1);                                                                \
+        TN_R(st0, 1);                                                                \
+        TN_M(0);                                                                     \
+        TN_R(st1, 0);                                                                \
+        TN_M(1);                                                                     \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                           \
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);                     \
+            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);                  \
+        }                                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                           \
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);                     \
+            __builtin_amdgcn_sched_group_barrier(SG_DS_WRITE, 1, 0);                 \
+        }                                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                           \
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);                     \
+            __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, FAST ? 1 : 4, 0);     \
+        }                                                                            \
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 4, 0);                         \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                           \
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);                     \
+            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);                  \
+        }                                                                            \
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 12, 0);                        \
+        __syncthreads();                                                             \
+        const int t_ = st0;                                                          \
+        st0 = st1;                                                                   \
+        st1 = st2;                                                                   \
+        st2 = t_;                                                                    \
+    } while (0)
 
-    // prologue: slabs 0 and 1 in LDS, slab 2 in flight, first half of slab 0 in registers
-    TN_G();
-    TN_W(0);
-    TN_G();
-    TN_W(1);
-    TN_G();
+    // prologue: slabs 0 and 1 in LDS, slabs 2 and 3 in flight, first half of slab 0 in registers
+    TN_G(0, 0);
+    TN_G(1, 1);
+    TN_W(0, 0);
+    TN_W(1, 1);
+    TN_G(0, 0);
+    TN_G(1, 1);
     __syncthreads();
     TN_R(0, 0);
 
     int st0 = 0, st1 = 1, st2 = 2;  // stages of slabs s, s+1, s+2
     int folded = 0;
-    for (int s = 0; s < nslab; ++s) {
-        TN_W(st2);    // slab s+2 (loaded one iteration ago)
-        TN_G();       // slab s+3
-        TN_R(st0, 1);
-        TN_M(0);
-        TN_R(st1, 0);
-        TN_M(1);
-        // interleave: the LDS writes, global loads and the first batch of LDS reads go
-        // one by one between the first MFMAs; the second batch between the MFMAs of
-        // the second half
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(SG_DS_WRITE, 1, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, FAST ? 1 : 4, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 4, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 12, 0);
-        __syncthreads();
-        const int t = st0;
-        st0 = st1;
-        st1 = st2;
-        st2 = t;
-        if (++folded == TN_CHUNK_SLABS) {
+    int s = 0;
+    for (; s + 1 < nslab; s += 2) {
+        TN_ITER(0);
+        TN_ITER(1);
+        folded += 2;
+        if (folded == TN_CHUNK_SLABS) {
             folded = 0;
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -397,6 +402,8 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
                 }
         }
     }
+    if (s < nslab) TN_ITER(0);
+#undef TN_ITER
 #undef TN_G
 #undef TN_W
 #undef TN_R
