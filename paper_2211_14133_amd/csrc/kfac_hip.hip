@@ -197,9 +197,9 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         if (it.x == nullptr || it.factor == nullptr) return KFAC_ERR_ARG;
         if (!fits_int(it.d) || !fits_int(it.n_tokens)) return KFAC_ERR_ARG;
         if (it.ldx < it.d || it.ldf < it.d || !fits_int(it.ldx) || !fits_int(it.ldf)) return KFAC_ERR_ARG;
-        if ((reinterpret_cast<uintptr_t>(it.x) & 3) || (reinterpret_cast<uintptr_t>(it.factor) & 3)) return KFAC_ERR_ARG;
+        if ((reinterpret_cast<uintptr_t>(it.x) & (dtype == KFAC_BF16 ? 1 : 3)) || (reinterpret_cast<uintptr_t>(it.factor) & 3))
+            return KFAC_ERR_ARG;
     }
-    if (dtype != KFAC_F32) return KFAC_ERR_UNSUPPORTED;
     CurvPlan pl;
     if (!curvature_plan(items, count, pl)) return KFAC_ERR_ARG;
     if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;
@@ -216,7 +216,7 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         for (int64_t i = 0; i < n; ++i) {
             const kfac_curvature_item &it = items[done + i];
             SyrkProblem &q = lp.p[i];
-            q.x = static_cast<const float *>(it.x);
+            q.x = it.x;
             q.factor = it.factor;
             q.n = (int)it.n_tokens;
             q.d = (int)it.d;
@@ -233,6 +233,7 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         lp.c.alpha = alpha;
         lp.c.beta = beta;
         lp.c.partial = part;
+        lp.c.in_bf16 = (dtype == KFAC_BF16) ? 1 : 0;
         hipLaunchKernelGGL(curvature_syrk_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lp);
         if (pl.splits > 1) {
             hipLaunchKernelGGL(curvature_reduce_kernel, dim3(tiles / pl.splits), dim3(TN_THREADS), 0, st, lp);

@@ -56,10 +56,12 @@ struct TnCommon {
     float alpha;
     float beta;
     float *partial;  // [total logical tiles][BM * BN]
+    int in_bf16;     // operands are bfloat16 (curvature launches only); products are exact in fp32
 };
 
 // General launch: up to TN_MAX_PROBLEMS arbitrary problems.
 struct TnLaunch {
+    static constexpr bool kAllowBf16 = false;
     TnProblem p[TN_MAX_PROBLEMS];
     TnCommon c;
     __device__ int tile_begin(int i) const { return p[i].tile_begin; }
@@ -72,7 +74,7 @@ struct TnLaunch {
 constexpr int SYRK_MAX_PROBLEMS = 80;
 
 struct SyrkProblem {
-    const float *x;  // n x d, ldx
+    const void *x;   // n x d, ldx (float32 or bfloat16)
     float *factor;   // d x d, ldf
     int n, d, ldx, ldf;
     int tile_begin;
@@ -80,6 +82,7 @@ struct SyrkProblem {
 };
 
 struct SyrkLaunch {
+    static constexpr bool kAllowBf16 = true;
     SyrkProblem p[SYRK_MAX_PROBLEMS];
     TnCommon c;
     __device__ int tile_begin(int i) const { return p[i].tile_begin; }
@@ -87,7 +90,7 @@ struct SyrkLaunch {
     {
         const SyrkProblem &q = p[i];
         TnProblem r;
-        r.A = q.x; r.B = q.x; r.C = q.factor; r.Ct = q.factor; r.guard = nullptr;
+        r.A = static_cast<const float *>(q.x); r.B = static_cast<const float *>(q.x); r.C = q.factor; r.Ct = q.factor; r.guard = nullptr;
         r.M = q.d; r.N = q.d; r.K = q.n;
         r.lda = q.ldx; r.ldb = q.ldx; r.ldc = q.ldf; r.ldct = q.ldf;
         r.tile_begin = q.tile_begin;
@@ -204,23 +207,45 @@ __device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
 // the load never depends on a branch; tn_fix4 zeroes what must not count after
 // the MFMA work of the current slab has been issued (the load latency is then
 // hidden behind it).
-template <bool FAST>
-__device__ inline float4 tn_load4(const float *P, int k, int c, int ld, int K, int W)
+// Staging type: what a thread keeps in registers between the global load and
+// the LDS store (four consecutive elements of an operand row).
+template <bool BF16> struct TnStage { typedef float4 type; };
+template <> struct TnStage<true> { typedef uint2 type; };  // four bfloat16
+
+template <bool FAST, bool BF16>
+__device__ inline typename TnStage<BF16>::type tn_load4(const void *Pv, int k, int c, int ld, int K, int W)
 {
     const int kc = min(k, K - 1);
-    const float *row = P + (size_t)kc * (size_t)ld;
-    if (FAST) return *reinterpret_cast<const float4 *>(row + c);
-    float4 v;
-    v.x = row[min(c + 0, W - 1)];
-    v.y = row[min(c + 1, W - 1)];
-    v.z = row[min(c + 2, W - 1)];
-    v.w = row[min(c + 3, W - 1)];
-    return v;
+    if constexpr (BF16) {
+        const unsigned short *row = static_cast<const unsigned short *>(Pv) + (size_t)kc * (size_t)ld;
+        if (FAST) return *reinterpret_cast<const uint2 *>(row + c);
+        const unsigned e0 = row[min(c + 0, W - 1)], e1 = row[min(c + 1, W - 1)];
+        const unsigned e2 = row[min(c + 2, W - 1)], e3 = row[min(c + 3, W - 1)];
+        return make_uint2(e0 | (e1 << 16), e2 | (e3 << 16));
+    } else {
+        const float *row = static_cast<const float *>(Pv) + (size_t)kc * (size_t)ld;
+        if (FAST) return *reinterpret_cast<const float4 *>(row + c);
+        float4 v;
+        v.x = row[min(c + 0, W - 1)];
+        v.y = row[min(c + 1, W - 1)];
+        v.z = row[min(c + 2, W - 1)];
+        v.w = row[min(c + 3, W - 1)];
+        return v;
+    }
 }
 
-template <bool FAST, bool MASKED>
-__device__ inline float4 tn_fix4(float4 v, int k, int c, int K, int W, int mask)
+__device__ inline float4 tn_widen(float4 v) { return v; }
+__device__ inline float4 tn_widen(uint2 v)
 {
+    // bfloat16 -> float32 is a 16-bit shift (exact)
+    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                       __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+}
+
+template <bool FAST, bool MASKED, class ST>
+__device__ inline float4 tn_fix4(ST raw, int k, int c, int K, int W, int mask)
+{
+    float4 v = tn_widen(raw);
     // branch-free on purpose: the K loop must stay one basic block
     const bool kz = k >= K;
     bool z0 = kz, z1 = kz, z2 = kz, z3 = kz;
@@ -270,15 +295,15 @@ constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_W
 // which every wave finished reading before the previous barrier.  Loads past
 // the end of the K range are clamped to valid rows and their data is never
 // used, which keeps the loop body free of branches.
-template <bool FAST, bool MASKED>
+template <bool FAST, bool MASKED, bool BF16>
 __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, const TnTile &tl,
                                    float (&As)[TN_STAGES][BK][BM], float (&Bs)[TN_STAGES][BK][BN],
                                    floatx16 (&sum)[2][2])
 {
     const int tid = threadIdx.x;
     const int M = pr.M, N = pr.N, K = pr.K;
-    const float *__restrict__ A = pr.A;
-    const float *__restrict__ B = pr.B;
+    const void *__restrict__ A = pr.A;
+    const void *__restrict__ B = pr.B;
     const int lda = pr.lda, ldb = pr.ldb;
     const int mask_a = lp.mask_a, mask_b = lp.mask_b;
 
@@ -300,24 +325,24 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
     const int nslab = tl.kt1 - tl.kt0;
     if (nslab <= 0) return;
 
-    float4 ra[2][2], rb[2][2];  // two sets of staging registers (slabs alternate between them)
+    typename TnStage<BF16>::type ra[2][2], rb[2][2];  // two sets of staging registers (slabs alternate)
     float2 fa[2][4], fb[2][4];  // MFMA operands: [half of the slab][k step pair]
     int kw = tl.kbase + tl.kt0 * BK + lrow;  // K row (of this thread) of the next slab to go to LDS
 
 #define TN_G(set, ahead)                                                        \
     do {                                                                        \
         const int kg_ = kw + (ahead) * BK;                                      \
-        ra[set][0] = tn_load4<FAST>(A, kg_, ca, lda, K, M);                     \
-        ra[set][1] = tn_load4<FAST>(A, kg_ + 8, ca, lda, K, M);                 \
-        rb[set][0] = tn_load4<FAST>(B, kg_, cb, ldb, K, N);                     \
-        rb[set][1] = tn_load4<FAST>(B, kg_ + 8, cb, ldb, K, N);                 \
+        ra[set][0] = tn_load4<FAST, BF16>(A, kg_, ca, lda, K, M);                     \
+        ra[set][1] = tn_load4<FAST, BF16>(A, kg_ + 8, ca, lda, K, M);                 \
+        rb[set][0] = tn_load4<FAST, BF16>(B, kg_, cb, ldb, K, N);                     \
+        rb[set][1] = tn_load4<FAST, BF16>(B, kg_ + 8, cb, ldb, K, N);                 \
     } while (0)
 #define TN_W(st, set)                                                                                                  \
     do {                                                                                                               \
-        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(ra[set][0], kw, ca, K, M, mask_a);     \
-        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(ra[set][1], kw + 8, ca, K, M, mask_a); \
-        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(rb[set][0], kw, cb, K, N, mask_b);     \
-        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(rb[set][1], kw + 8, cb, K, N, mask_b); \
+        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST, MASKED, typename TnStage<BF16>::type>(ra[set][0], kw, ca, K, M, mask_a);     \
+        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED, typename TnStage<BF16>::type>(ra[set][1], kw + 8, ca, K, M, mask_a); \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST, MASKED, typename TnStage<BF16>::type>(rb[set][0], kw, cb, K, N, mask_b);     \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED, typename TnStage<BF16>::type>(rb[set][1], kw + 8, cb, K, N, mask_b); \
         kw += BK;                                                                                                      \
     } while (0)
     // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2*step + lh
@@ -423,8 +448,11 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_STAGES][BK][BM],
     const TnTile tl = tn_locate(ll, tn_logical_tile(blockIdx.x, gridDim.x), pr);
     const int M = pr.M, N = pr.N;
 
-    const bool fast_a = (tl.m0 + BM <= M) && ((pr.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.A) & 15) == 0);
-    const bool fast_b = (tl.n0 + BN <= N) && ((pr.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.B) & 15) == 0);
+    // vector loads need 16-byte (fp32) / 8-byte (bf16) aligned rows
+    const bool bf16 = L::kAllowBf16 && lp.in_bf16 != 0;
+    const uintptr_t amask = bf16 ? 7 : 15;
+    const bool fast_a = (tl.m0 + BM <= M) && ((pr.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.A) & amask) == 0);
+    const bool fast_b = (tl.n0 + BN <= N) && ((pr.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.B) & amask) == 0);
 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -439,16 +467,28 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_STAGES][BK][BM],
             for (int r = 0; r < 16; ++r) sum[i][j][r] = 0.f;
 
     const bool masked = (lp.mask_a | lp.mask_b) != 0;
-    if (fast_a && fast_b) {
-        if (masked)
-            tn_mainloop<true, true>(lp, pr, tl, As, Bs, sum);
-        else
-            tn_mainloop<true, false>(lp, pr, tl, As, Bs, sum);
-    } else {
-        if (masked)
-            tn_mainloop<false, true>(lp, pr, tl, As, Bs, sum);
-        else
-            tn_mainloop<false, false>(lp, pr, tl, As, Bs, sum);
+    bool done = false;
+    if constexpr (L::kAllowBf16) {
+        if (bf16) {
+            if (fast_a && fast_b)
+                tn_mainloop<true, false, true>(lp, pr, tl, As, Bs, sum);
+            else
+                tn_mainloop<false, false, true>(lp, pr, tl, As, Bs, sum);
+            done = true;
+        }
+    }
+    if (!done) {
+        if (fast_a && fast_b) {
+            if (masked)
+                tn_mainloop<true, true, false>(lp, pr, tl, As, Bs, sum);
+            else
+                tn_mainloop<true, false, false>(lp, pr, tl, As, Bs, sum);
+        } else {
+            if (masked)
+                tn_mainloop<false, true, false>(lp, pr, tl, As, Bs, sum);
+            else
+                tn_mainloop<false, false, false>(lp, pr, tl, As, Bs, sum);
+        }
     }
 
     // Accumulator layout of MFMA 32x32: register r of lane (li, lh) is row

@@ -347,3 +347,58 @@ def test_chain_config2_bert_base_block(k, oracle):
 def test_chain_config3_bert_large_block(k, oracle):
     # the hard case for conditioning: FFN2's A factor has d = tokens = 4096 (smallest eigenvalue ~ damping)
     run_chain(k, oracle, 3, layers=("q", "ffn1", "ffn2"))
+
+
+# --------------------------------------------------- bf16 activations / errors
+
+BF16_FACTOR_TOL = 2e-2
+
+
+@pytest.mark.parametrize("n,d", [(256, 64), (1000, 300), (2048, 1024), (517, 129)])
+def test_curvature_bf16_inputs(k, oracle, n, d):
+    # the oracle sees the same bf16-rounded values, widened exactly; products of bf16 values are exact in fp32
+    x = synth.activations(5, 0, 0, 0, n, d, gelu=(d % 2 == 1), bf16=True)
+    xd = dev(x).to(torch.bfloat16)
+    assert torch.equal(xd.float().cpu(), torch.from_numpy(x))
+    f = torch.empty(d, d, device="cuda")
+    k.kfac_curvature(xd, f, 1.0 / n, 0.0)
+    err = oracle.rel_fro(host(f), oracle.curvature(x))
+    print("bf16 curvature n=%d d=%d rel_fro %.3g" % (n, d, err), flush=True)
+    assert err <= BF16_FACTOR_TOL and err <= 5e-7
+    assert np.array_equal(host(f), host(f).T)
+    # against the un-rounded fp32 inputs the error is the input rounding, far inside the gate
+    x32 = synth.activations(5, 0, 0, 0, n, d, gelu=(d % 2 == 1), bf16=False)
+    assert oracle.rel_fro(host(f), oracle.curvature(x32)) <= BF16_FACTOR_TOL
+    # strided bf16 input (odd offset: rows not 8-byte aligned)
+    big = dev(synth.activations(5, 0, 1, 0, n, d + 9, bf16=True)).to(torch.bfloat16)
+    xs = big[:, 3:3 + d]
+    k.kfac_curvature(xs, f, 1.0 / n, 0.0)
+    assert oracle.rel_fro(host(f), oracle.curvature(host(xs.float()))) <= 5e-7
+
+
+def test_curvature_bf16_hadamard_exact(k):
+    x = dev(synth.hadamard_columns(1024, 512)).to(torch.bfloat16)
+    f = torch.empty(512, 512, device="cuda")
+    k.kfac_curvature(x, f, 1.0 / 1024, 0.0)
+    assert np.array_equal(host(f), np.eye(512, dtype=np.float32))
+
+
+def test_chain_config5_bf16_attention_layer(k, oracle):
+    # stress workload, one attention linear (2048 x 2048, 8192 tokens, bf16 activations and errors)
+    c = synth.CONFIGS[5]
+    n, d = c["tokens"], 2048
+    x = synth.activations(5, 0, 0, 0, n, d, bf16=True)
+    e = synth.errors(5, 0, 0, 0, n, d, bf16=True)
+    g = synth.weight_gradient([e], [x])
+    a = torch.empty(d, d, device="cuda")
+    b = torch.empty(d, d, device="cuda")
+    k.kfac_curvature_grouped([dev(x).to(torch.bfloat16), dev(e).to(torch.bfloat16)], [a, b], 1.0 / n, 0.0)
+    ai, bi = torch.empty_like(a), torch.empty_like(b)
+    infos = k.kfac_invert_batched([a, b], synth.DAMPING, [ai, bi])
+    p = torch.empty(d, d, device="cuda")
+    k.kfac_precondition(bi, ai, dev(g), p)
+    assert host(infos).tolist() == [0, 0]
+    oa, ob, oai, obi, op = oracle.kfac_chain([x], [e], g, synth.DAMPING)
+    ea, eb, ep = oracle.rel_fro(host(a), oa), oracle.rel_fro(host(b), ob), oracle.rel_fro(host(p), op)
+    print("cfg 5 attention layer: A %.2e B %.2e P %.2e" % (ea, eb, ep), flush=True)
+    assert ea <= BF16_FACTOR_TOL and eb <= BF16_FACTOR_TOL and ep <= PRECOND_TOL
