@@ -11,9 +11,10 @@
 namespace kfac {
 
 constexpr int NB = 128;  // panel width of the blocked factorisation (= tile size of the engine)
+static_assert(NB == 128, "must equal INV_NB of the contraction engine");
 constexpr int DIAG_THREADS = 256;
 constexpr int DIAG_MAX_ITEMS = 80;
-constexpr int PREP_MAX_ITEMS = 64;
+constexpr int PREP_MAX_ITEMS = 80;
 
 struct DiagItem {
     float *F;    // top-left of the diagonal block inside the working copy (upper triangle valid)
@@ -246,12 +247,39 @@ __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl
     const PrepItem &it = pl.it[blockIdx.y];
     const int d = it.d;
     bool bad = false;
+    const bool vec = ((it.lds_ & 3) == 0) && ((reinterpret_cast<uintptr_t>(it.src) & 15) == 0);  // dst rows are aligned
     for (int r = blockIdx.x; r < d; r += gridDim.x) {
-        for (int c = threadIdx.x; c < d; c += blockDim.x) {
-            float v = it.src[(size_t)r * it.lds_ + c];
-            if (!(fabsf(v) <= 3.0e38f)) bad = true;
-            if (r == c) v += pl.damping;
-            it.dst[(size_t)r * it.ldd + c] = v;
+        const float *src = it.src + (size_t)r * it.lds_;
+        float *dst = it.dst + (size_t)r * it.ldd;
+        if (vec) {
+            for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+                float4 v;
+                if (c + 3 < d) {
+                    v = *reinterpret_cast<const float4 *>(src + c);
+                } else {
+                    v.x = src[c];
+                    v.y = (c + 1 < d) ? src[c + 1] : 0.f;
+                    v.z = (c + 2 < d) ? src[c + 2] : 0.f;
+                    v.w = 0.f;
+                }
+                if (!(fabsf(v.x) <= 3.0e38f) || !(fabsf(v.y) <= 3.0e38f) || !(fabsf(v.z) <= 3.0e38f) ||
+                    !(fabsf(v.w) <= 3.0e38f))
+                    bad = true;
+                if (r >= c && r < c + 4) {
+                    if (r == c) v.x += pl.damping;
+                    if (r == c + 1) v.y += pl.damping;
+                    if (r == c + 2) v.z += pl.damping;
+                    if (r == c + 3) v.w += pl.damping;
+                }
+                *reinterpret_cast<float4 *>(dst + c) = v;  // ld of the working copy is a multiple of 32 >= d
+            }
+        } else {
+            for (int c = threadIdx.x; c < d; c += blockDim.x) {
+                float v = src[c];
+                if (!(fabsf(v) <= 3.0e38f)) bad = true;
+                if (r == c) v += pl.damping;
+                dst[c] = v;
+            }
         }
     }
     if (bad) atomicCAS(it.info, 0, -1);

@@ -135,27 +135,79 @@ struct InvMat {
 };
 
 struct TriNode {
-    int mat, r0, b1, b2;
+    int mat, a, b, c;  // matrix, first block, blocks in the first part, blocks in the second part
 };
 
 // Balanced splitting of block range [lo, hi): returns the height of the node and
 // files it under that height.  Nodes of equal height are independent.
-int build_tree(int mat, int lo, int hi, int d, std::vector<std::vector<TriNode>> &levels)
+int build_tree(int mat, int lo, int hi, std::vector<std::vector<TriNode>> &levels)
 {
     if (hi - lo <= 1) return 0;
     const int mid = lo + (hi - lo + 1) / 2;
-    const int hl = build_tree(mat, lo, mid, d, levels);
-    const int hr = build_tree(mat, mid, hi, d, levels);
+    const int hl = build_tree(mat, lo, mid, levels);
+    const int hr = build_tree(mat, mid, hi, levels);
     const int h = 1 + std::max(hl, hr);
     if ((int)levels.size() <= h) levels.resize(h + 1);
-    TriNode nd;
-    nd.mat = mat;
-    nd.r0 = lo * NB;
-    nd.b1 = (mid - lo) * NB;
-    nd.b2 = std::min(hi * NB, d) - mid * NB;
-    levels[h].push_back(nd);
+    levels[h].push_back(TriNode{mat, lo, mid - lo, hi - mid});
     return h;
 }
+
+// Sends the nodes of one phase of the inversion to invert_gemm_kernel, as many per
+// launch as the kernel arguments hold.
+struct InvBatch {
+    const std::vector<InvMat> &mats;
+    std::vector<TriNode> nodes;
+    int op = 0, tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE;
+    float alpha = 1.f, beta = 0.f;
+
+    explicit InvBatch(const std::vector<InvMat> &m) : mats(m) {}
+
+    void add(int mat, int a, int b = 0, int c = 0) { nodes.push_back(TriNode{mat, a, b, c}); }
+
+    hipError_t launch(hipStream_t stream)
+    {
+        size_t i = 0;
+        while (i < nodes.size()) {
+            InvLaunch lp;
+            std::memset(&lp, 0, sizeof(lp));
+            for (size_t k = 0; k < mats.size(); ++k) {
+                lp.m[k].F = mats[k].F;
+                lp.m[k].S = mats[k].S;
+                lp.m[k].d = mats[k].d;
+                lp.m[k].ld = mats[k].ld;
+            }
+            int tiles = 0, cnt = 0;
+            while (i < nodes.size() && cnt < INV_MAX_NODES) {
+                const TriNode &nd = nodes[i++];
+                const InvDims dm = inv_dims(op, mats[(size_t)nd.mat].d, nd.a, nd.b, nd.c);
+                if (dm.M <= 0 || dm.N <= 0) continue;
+                lp.n[cnt].mat = (unsigned char)nd.mat;
+                lp.n[cnt].a = (unsigned char)nd.a;
+                lp.n[cnt].b = (unsigned char)nd.b;
+                lp.n[cnt].c = (unsigned char)nd.c;
+                lp.n[cnt].tile_begin = tiles;
+                tiles += tn_tiles(dm.M, dm.N, tile_mode);
+                ++cnt;
+            }
+            if (cnt == 0) continue;
+            lp.c.count = cnt;
+            lp.c.tile_mode = tile_mode;
+            lp.c.mask_a = mask_a;
+            lp.c.mask_b = mask_b;
+            lp.c.splits = 1;
+            lp.c.alpha = alpha;
+            lp.c.beta = beta;
+            lp.op = op;
+            hipLaunchKernelGGL(invert_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, stream, lp);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        nodes.clear();
+        return hipSuccess;
+    }
+};
+
+constexpr int SUPER_PANEL = 4;  // block rows factored before one trailing update (K = 512)
 
 }  // namespace
 
@@ -301,8 +353,22 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
             return KFAC_ERR_ARG;
         if (static_cast<const void *>(it.factor) == static_cast<const void *>(it.inv)) return KFAC_ERR_ARG;
     }
+    for (int64_t i = 0; i < count; ++i)
+        if (items[i].d > 255 * NB) return KFAC_ERR_UNSUPPORTED;  // block indices travel as bytes
     const size_t need = kfac_invert_batched_workspace(items, count);
     if (!ws_ok(workspace, workspace_bytes, need)) return KFAC_ERR_WORKSPACE;
+    if (count > INV_MAX_MATS) {
+        // more matrices than one launch describes: run the batch in slices, one after the other
+        char *base = static_cast<char *>(workspace);
+        for (int64_t i0 = 0; i0 < count; i0 += INV_MAX_MATS) {
+            const int64_t n = std::min<int64_t>(INV_MAX_MATS, count - i0);
+            const size_t bytes = kfac_invert_batched_workspace(items + i0, n);
+            const kfac_status stt = kfac_invert_batched(items + i0, n, damping, base, bytes, stream);
+            if (stt != KFAC_OK) return stt;
+            base += bytes;
+        }
+        return KFAC_OK;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     std::vector<InvMat> mats((size_t)count);
@@ -345,47 +411,56 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
     }
     if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
 
-    // 2. Blocked upper Cholesky M = U^T U, right-looking, one panel of every matrix per step.
-    TnBatch trsm, syrk;
-    trsm.tile_mode = TILE_FULL;
-    trsm.mask_a = MASK_KEEP_K_LE;  // U_kk^-1 is upper triangular: rows k <= column
-    syrk.tile_mode = TILE_UPPER;
-    syrk.alpha = -1.f;
-    syrk.beta = 1.f;
-    for (int kb = 0; kb < max_blk; ++kb) {
-        std::vector<DiagItem> ditems;
-        for (const InvMat &m : mats) {
-            if (kb >= m.nblk) continue;
-            const int r0 = kb * NB;
-            const int n = std::min(NB, m.d - r0);
-            const int rest = m.d - r0 - n;
-            DiagItem di;
-            di.F = m.F + (size_t)r0 * m.ld + r0;
-            di.S = m.S + (size_t)r0 * m.ld + r0;
-            di.info = m.info;
-            di.n = n;
-            di.ldf = m.ld;
-            di.lds = m.ld;
-            di.pivot_base = r0;
-            ditems.push_back(di);
-            if (rest > 0) {
-                float *panel = m.F + (size_t)r0 * m.ld + r0 + n;                 // n x rest, becomes U12
-                float *below = m.F + (size_t)(r0 + n) * m.ld + r0;               // rest x n, mirror of U12
-                float *trail = m.F + (size_t)(r0 + n) * m.ld + r0 + n;           // rest x rest
-                trsm.add(di.S, m.ld, panel, m.ld, panel, m.ld, n, rest, n, below, m.ld);
-                syrk.add(panel, m.ld, panel, m.ld, trail, m.ld, rest, rest, n);
+    // 2. Blocked upper Cholesky M = U^T U with panel width NB, all matrices advanced together.
+    //    Inside a super-panel of SUPER_PANEL block rows the factorisation is left-looking (a block
+    //    row is brought up to date just before it is factored); the rest of the matrix is updated
+    //    once per super-panel, so that it is read and written SUPER_PANEL times less often.
+    InvBatch solve(mats), rowup(mats), trail(mats);
+    solve.op = INV_PANEL_SOLVE;
+    solve.mask_a = MASK_KEEP_K_LE;  // U_jj^-1 is upper triangular: rows k <= column
+    rowup.op = INV_ROW_UPDATE;
+    rowup.alpha = -1.f;
+    rowup.beta = 1.f;
+    trail.op = INV_TRAIL_UPDATE;
+    trail.tile_mode = TILE_UPPER;
+    trail.alpha = -1.f;
+    trail.beta = 1.f;
+    for (int s0 = 0; s0 < max_blk; s0 += SUPER_PANEL) {
+        for (int j = s0; j < std::min(s0 + SUPER_PANEL, max_blk); ++j) {
+            std::vector<DiagItem> ditems;
+            for (size_t mi = 0; mi < mats.size(); ++mi) {
+                const InvMat &m = mats[mi];
+                if (j >= m.nblk) continue;
+                const int r0 = j * NB;
+                const int n = std::min(NB, m.d - r0);
+                DiagItem di;
+                di.F = m.F + (size_t)r0 * m.ld + r0;
+                di.S = m.S + (size_t)r0 * m.ld + r0;
+                di.info = m.info;
+                di.n = n;
+                di.ldf = m.ld;
+                di.lds = m.ld;
+                di.pivot_base = r0;
+                ditems.push_back(di);
+                if (j > s0) rowup.add((int)mi, s0, j);
+                if (m.d - r0 - n > 0) solve.add((int)mi, j);
             }
+            if (rowup.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+            for (size_t i0 = 0; i0 < ditems.size(); i0 += DIAG_MAX_ITEMS) {
+                const size_t n = std::min<size_t>(DIAG_MAX_ITEMS, ditems.size() - i0);
+                DiagLaunch dl;
+                std::memset(&dl, 0, sizeof(dl));
+                for (size_t i = 0; i < n; ++i) dl.it[i] = ditems[i0 + i];
+                hipLaunchKernelGGL(diag_block_kernel, dim3((unsigned)n), dim3(DIAG_THREADS), 0, st, dl);
+            }
+            if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
+            if (solve.launch(st) != hipSuccess) return KFAC_ERR_HIP;
         }
-        for (size_t i0 = 0; i0 < ditems.size(); i0 += DIAG_MAX_ITEMS) {
-            const size_t n = std::min<size_t>(DIAG_MAX_ITEMS, ditems.size() - i0);
-            DiagLaunch dl;
-            std::memset(&dl, 0, sizeof(dl));
-            for (size_t i = 0; i < n; ++i) dl.it[i] = ditems[i0 + i];
-            hipLaunchKernelGGL(diag_block_kernel, dim3((unsigned)n), dim3(DIAG_THREADS), 0, st, dl);
+        for (size_t mi = 0; mi < mats.size(); ++mi) {
+            const int e = std::min(s0 + SUPER_PANEL, mats[mi].nblk);
+            if (s0 < mats[mi].nblk && e < mats[mi].nblk) trail.add((int)mi, s0, e);
         }
-        if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
-        if (trsm.launch(st) != hipSuccess) return KFAC_ERR_HIP;
-        if (syrk.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+        if (trail.launch(st) != hipSuccess) return KFAC_ERR_HIP;
     }
 
     // 3. W = U^-1 by pairwise merging of already inverted diagonal ranges:
@@ -393,26 +468,16 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
     //    Y = U12 W22 goes where U12 was (the factor's upper blocks are no longer needed:
     //    later merges read the mirrored copy below the diagonal).
     std::vector<std::vector<TriNode>> levels;
-    for (size_t i = 0; i < mats.size(); ++i) build_tree((int)i, 0, mats[i].nblk, mats[i].d, levels);
-    TnBatch s1, s2;
-    s1.tile_mode = TILE_FULL;
+    for (size_t i = 0; i < mats.size(); ++i) build_tree((int)i, 0, mats[i].nblk, levels);
+    InvBatch s1(mats), s2(mats);
+    s1.op = INV_MERGE_Y;
     s1.mask_b = MASK_KEEP_K_LE;  // W22 upper triangular
-    s2.tile_mode = TILE_FULL;
+    s2.op = INV_MERGE_W;
     s2.mask_a = MASK_KEEP_K_GE;  // W11 read through its mirror below the diagonal
     s2.alpha = -1.f;
     for (size_t h = 1; h < levels.size(); ++h) {
-        for (const TriNode &nd : levels[h]) {
-            const InvMat &m = mats[(size_t)nd.mat];
-            const int c1 = nd.r0 + nd.b1;
-            const float *l21 = m.F + (size_t)c1 * m.ld + nd.r0;      // b2 x b1 = U12^T
-            const float *s22 = m.S + (size_t)c1 * m.ld + c1;         // b2 x b2
-            const float *s11 = m.S + (size_t)nd.r0 * m.ld + nd.r0;   // b1 x b1
-            float *y = m.F + (size_t)nd.r0 * m.ld + c1;              // b1 x b2
-            float *w12 = m.S + (size_t)nd.r0 * m.ld + c1;            // b1 x b2
-            float *w21 = m.S + (size_t)c1 * m.ld + nd.r0;            // b2 x b1 (mirror)
-            s1.add(l21, m.ld, s22, m.ld, y, m.ld, nd.b1, nd.b2, nd.b2);
-            s2.add(s11, m.ld, y, m.ld, w12, m.ld, nd.b1, nd.b2, nd.b1, w21, m.ld);
-        }
+        s1.nodes = levels[h];
+        s2.nodes = levels[h];
         if (s1.launch(st) != hipSuccess) return KFAC_ERR_HIP;
         if (s2.launch(st) != hipSuccess) return KFAC_ERR_HIP;
     }

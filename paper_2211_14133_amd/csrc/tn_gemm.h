@@ -98,6 +98,109 @@ struct SyrkLaunch {
     }
 };
 
+// Inversion launch: the problems of one phase of the blocked inversion are
+// described by (matrix, up to three block indices); pointers and sizes follow
+// from the matrix table, so a whole stage's worth of matrices (and a few hundred
+// merge nodes) fits into the kernel arguments of a single launch.
+constexpr int INV_NB = 128;  // panel width of the blocked factorisation (= BM = BN)
+constexpr int INV_MAX_MATS = 72;
+constexpr int INV_MAX_NODES = 224;
+
+enum InvOp : int {
+    INV_PANEL_SOLVE = 0,  // a = block row j:            U[j, j+1:] = W_jj^T M[j, j+1:]     (mirrored below)
+    INV_ROW_UPDATE = 1,   // a = first row s, b = row j:  M[j, j:] -= U[s:j, j]^T U[s:j, j:]
+    INV_TRAIL_UPDATE = 2, // a = s, b = e:                M[e:, e:] -= U[s:e, e:]^T U[s:e, e:] (upper tiles)
+    INV_MERGE_Y = 3,      // a = r0, b = b1, c = b2 (blocks): Y = U12 W22, stored over U12
+    INV_MERGE_W = 4       // same node:                  W12 = -W11 Y               (mirrored)
+};
+
+struct InvMatDesc {
+    float *F;  // working copy / factor U above the diagonal, U^T below
+    float *S;  // W = U^-1 above the diagonal, W^T below
+    int d;
+    int ld;
+};
+
+struct InvNode {
+    unsigned char mat, a, b, c;
+    int tile_begin;
+};
+
+struct InvDims {
+    int M, N, K;
+};
+
+__host__ __device__ inline InvDims inv_dims(int op, int d, int a, int b, int c)
+{
+    InvDims r;
+    if (op == INV_PANEL_SOLVE) {
+        const int r0 = a * INV_NB, n = min(INV_NB, d - r0);
+        r.M = n; r.N = d - r0 - n; r.K = n;
+    } else if (op == INV_ROW_UPDATE) {
+        const int r0 = b * INV_NB, n = min(INV_NB, d - r0);
+        r.M = n; r.N = d - r0; r.K = r0 - a * INV_NB;
+    } else if (op == INV_TRAIL_UPDATE) {
+        const int r0 = b * INV_NB;
+        r.M = d - r0; r.N = d - r0; r.K = r0 - a * INV_NB;
+    } else {
+        const int b1 = b * INV_NB, c1 = a * INV_NB + b1, b2 = min(c * INV_NB, d - c1);
+        r.M = b1; r.N = b2; r.K = (op == INV_MERGE_Y) ? b2 : b1;
+    }
+    return r;
+}
+
+struct InvLaunch {
+    static constexpr bool kAllowBf16 = false;
+    InvMatDesc m[INV_MAX_MATS];
+    InvNode n[INV_MAX_NODES];
+    TnCommon c;
+    int op;
+    __device__ int tile_begin(int i) const { return n[i].tile_begin; }
+    __device__ TnProblem problem(int i) const
+    {
+        const InvNode nd = n[i];
+        const InvMatDesc &mt = m[nd.mat];
+        const size_t ld = (size_t)mt.ld;
+        const InvDims dm = inv_dims(op, mt.d, nd.a, nd.b, nd.c);
+        TnProblem r;
+        r.M = dm.M; r.N = dm.N; r.K = dm.K;
+        r.lda = r.ldb = r.ldc = r.ldct = mt.ld;
+        r.tile_begin = nd.tile_begin;
+        r.guard = nullptr;
+        r.Ct = nullptr;
+        if (op == INV_PANEL_SOLVE) {
+            const size_t r0 = (size_t)nd.a * INV_NB, nn = (size_t)dm.M;
+            r.A = mt.S + r0 * ld + r0;
+            r.B = mt.F + r0 * ld + r0 + nn;
+            r.C = mt.F + r0 * ld + r0 + nn;
+            r.Ct = mt.F + (r0 + nn) * ld + r0;
+        } else if (op == INV_ROW_UPDATE) {
+            const size_t k0 = (size_t)nd.a * INV_NB, r0 = (size_t)nd.b * INV_NB;
+            r.A = mt.F + k0 * ld + r0;
+            r.B = mt.F + k0 * ld + r0;
+            r.C = mt.F + r0 * ld + r0;
+        } else if (op == INV_TRAIL_UPDATE) {
+            const size_t k0 = (size_t)nd.a * INV_NB, r0 = (size_t)nd.b * INV_NB;
+            r.A = mt.F + k0 * ld + r0;
+            r.B = mt.F + k0 * ld + r0;
+            r.C = mt.F + r0 * ld + r0;
+        } else {
+            const size_t r0 = (size_t)nd.a * INV_NB, c1 = r0 + (size_t)nd.b * INV_NB;
+            if (op == INV_MERGE_Y) {
+                r.A = mt.F + c1 * ld + r0;
+                r.B = mt.S + c1 * ld + c1;
+                r.C = mt.F + r0 * ld + c1;
+            } else {
+                r.A = mt.S + r0 * ld + r0;
+                r.B = mt.F + r0 * ld + c1;
+                r.C = mt.S + r0 * ld + c1;
+                r.Ct = mt.S + c1 * ld + r0;
+            }
+        }
+        return r;
+    }
+};
+
 __host__ __device__ inline int tn_tiles(int M, int N, int mode)
 {
     const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
@@ -165,9 +268,14 @@ __device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
 {
     const TnCommon &lp = ll.c;
     TnTile tl;
-    int pi = 0;
-    for (int i = 1; i < lp.count; ++i)
-        if (ll.tile_begin(i) <= t) pi = i;
+    int pi = 0, hi = lp.count;  // tile_begin is ascending: last problem with tile_begin <= t
+    while (hi - pi > 1) {
+        const int mid = (pi + hi) >> 1;
+        if (ll.tile_begin(mid) <= t)
+            pi = mid;
+        else
+            hi = mid;
+    }
     pr = ll.problem(pi);
     const int local = t - pr.tile_begin;
     const int tile = local / lp.splits;
@@ -639,5 +747,13 @@ __global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_kernel(const Syr
 }
 
 __global__ __launch_bounds__(TN_THREADS) void curvature_reduce_kernel(const SyrkLaunch lp) { tn_reduce_body(lp); }
+
+// The products of the blocked inversion (panel solves, row / trailing updates, merges).
+__global__ __launch_bounds__(TN_THREADS, 2) void invert_gemm_kernel(const InvLaunch lp)
+{
+    __shared__ float As[TN_STAGES][BK][BM];
+    __shared__ float Bs[TN_STAGES][BK][BN];
+    tn_tile_body(lp, As, Bs);
+}
 
 }  // namespace kfac
