@@ -35,6 +35,12 @@ constexpr int LDT = NB + 4;   // LDS row stride in floats
 
 typedef float diag_floatx16 __attribute__((ext_vector_type(16)));
 
+#ifdef DIAG_PROFILE
+#define DIAG_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_stamps[i] = (long long)__builtin_readcyclecounter(); } while (0)
+#else
+#define DIAG_STAMP(i) do {} while (0)
+#endif
+
 enum DiagMask : int { DM_NONE = 0, DM_UPPER = 1, DM_LOWER = 2 };  // keep row <= col / row >= col
 
 __device__ inline float diag_bcast(float v, int src_lane)
@@ -83,50 +89,54 @@ __device__ inline void sb_store(diag_floatx16 acc, float (*C)[LDT], int cm0, int
 }
 
 // One wave factors the 32 x 32 diagonal sub-block at offset o (upper triangle of
-// Fs) as U^T U and inverts U.  Lane c (mod 32) keeps column c in registers; the
-// pivot row is passed around with readlane, so there is no LDS traffic and no
-// barrier inside.  Writes U (upper) to Fs and W = U^-1 (upper) plus its mirror
-// to Ss.  Returns the 1-based local index of the first bad pivot, or 0.
+// Fs) as U^T U and inverts U, all in registers.  The symmetric block T and a
+// second matrix V (starting as the identity) are kept in MFMA accumulator layout
+// (lane = column, 16 rows per lane).  Step j takes the pivot with one readlane,
+// scales row j and applies the elimination of column j to T and V as rank-one
+// updates, one MFMA 32x32x2 each (the vector -u feeds the rows, the scaled pivot
+// row the columns; the second K slot is zero).  The same row operations that turn
+// T into U turn the identity into U^-T = W^T.  Row j of U and of W^T are final at
+// step j and go to LDS then (U above the diagonal of Fs; W above the diagonal of
+// Ss and its mirror below); nothing is read back and there is no barrier inside.  Returns the 1-based local index of the first bad pivot, or 0.
 __device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o, int lane)
 {
-    const int c = lane & 31;
-    float t[SB], rin[SB];
+    const int c = lane & 31, h = lane >> 5;
+    diag_floatx16 T, V;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int i = 8 * (r >> 2) + 4 * h + (r & 3);
+        T[r] = (i <= c) ? Fs[o + i][o + c] : Fs[o + c][o + i];
+        V[r] = (i == c) ? 1.f : 0.f;
+    }
     int bad = 0;
 #pragma unroll
-    for (int r = 0; r < SB; ++r) t[r] = (r <= c) ? Fs[o + r][o + c] : 0.f;
-#pragma unroll
     for (int j = 0; j < SB; ++j) {
-        float piv = diag_bcast(t[j], j);
+        const int hj = (j >> 2) & 1, rj = 4 * (j >> 3) + (j & 3);  // row j lives in half hj, register rj
+        float piv = diag_bcast(T[rj], j + 32 * hj);
         if (!(piv > 0.f) || !(piv <= 3.0e38f)) {
             if (bad == 0) bad = j + 1;
             piv = 1.f;
         }
-        const float rinv = 1.0f / sqrtf(piv);
-        rin[j] = rinv;
-        const float u = t[j] * rinv;  // U[j][c] for c >= j
-        t[j] = u;
-#pragma unroll
-        for (int r = j + 1; r < SB; ++r) t[r] -= diag_bcast(u, r) * u;
-    }
-    float w[SB];
-#pragma unroll
-    for (int r = 0; r < SB; ++r) w[r] = (r == c) ? rin[r] : 0.f;
-#pragma unroll
-    for (int i = SB - 2; i >= 0; --i) {
-        float s = 0.f;
-#pragma unroll
-        for (int kx = i + 1; kx < SB; ++kx) s += diag_bcast(t[i], kx) * w[kx];  // U[i][kx] * W[kx][c]
-        if (i < c) w[i] = -s * rin[i];
-    }
-    if (lane < 32) {
-#pragma unroll
-        for (int r = 0; r < SB; ++r) {
-            if (r <= c) {
-                Fs[o + r][o + c] = t[r];
-                Ss[o + r][o + c] = w[r];
-                Ss[o + c][o + r] = w[r];
-            }
-        }
+        float rinv = __builtin_amdgcn_rsqf(piv);
+        rinv = rinv * (1.5f - 0.5f * piv * rinv * rinv);  // one Newton step: full fp32 accuracy
+        const bool mine = (h == hj);
+        const float u = T[rj] * rinv;     // U[j][c] in the lanes of half hj
+        const float vrow = V[rj] * rinv;  // row j of U^-T = column j of W, final
+        // The lanes of the other half write to the padding columns instead of branching.
+        // All 32 columns are stored: the entries on the wrong side of the diagonal are
+        // either unused (Fs) or exact zeros that a later step overwrites (Ss).
+        float *ud = mine ? &Fs[o + j][o + c] : &Fs[o + j][NB];
+        float *wd = mine ? &Ss[o + c][o + j] : &Ss[o + j][NB];
+        float *vd = mine ? &Ss[o + j][o + c] : &Ss[o + j][NB + 1];
+        *ud = u;
+        *wd = vrow;
+        *vd = vrow;
+        const float au = (mine && c > j) ? -u : 0.f;  // rows below j are eliminated
+        const float bt = mine ? u : 0.f;
+        const float bv = mine ? vrow : 0.f;
+        T = __builtin_amdgcn_mfma_f32_32x32x2f32(au, bt, T, 0, 0, 0);
+        V = __builtin_amdgcn_mfma_f32_32x32x2f32(au, bv, V, 0, 0, 0);
+        // row j of V stays unscaled in the accumulator; it is never read again
     }
     return bad;
 }
@@ -152,29 +162,56 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
 
-    for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
-        const int r = e / NB, c = e % NB;
-        float v = (r == c) ? 1.f : 0.f;
-        if (r < n && c < n) v = (r <= c) ? it.F[(size_t)r * it.ldf + c] : 0.f;
-        Fs[r][c] = v;
-        Ss[r][c] = 0.f;
+    DIAG_STAMP(0);
+    // the working copy's rows are 16-byte aligned (ld multiple of 32, block offsets multiples of 128)
+    {
+        const int c4 = (tid & 31) << 2, r0 = tid >> 5;
+        float4 v[NB / 8];
+#pragma unroll
+        for (int q = 0; q < NB / 8; ++q) {
+            const int r = r0 + 8 * q;
+            v[q] = *reinterpret_cast<const float4 *>(&it.F[(size_t)min(r, n - 1) * it.ldf + min(c4, max(n - 4, 0))]);
+        }
+        const bool whole = (n == NB);
+#pragma unroll
+        for (int q = 0; q < NB / 8; ++q) {
+            const int r = r0 + 8 * q;
+            float e[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+            if (!whole) {  // ragged last block: reload element-wise and pad with the identity
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int c = c4 + t;
+                    e[t] = (r < n && c < n) ? it.F[(size_t)r * it.ldf + c] : ((r == c) ? 1.f : 0.f);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int c = c4 + t;
+                Fs[r][c] = (r <= c || r >= n || c >= n) ? e[t] : 0.f;
+                Ss[r][c] = 0.f;
+            }
+        }
     }
     __syncthreads();
 
+    DIAG_STAMP(1);
     // Phase 1: right-looking factorisation over the four 32-wide panels.
     for (int p = 0; p < NB / SB; ++p) {
         const int o = p * SB;
+        DIAG_STAMP(2 + 3 * p);
         if (wave == 0) {
             const int bad = sb_factor_invert(Fs, Ss, o, lane);
             if (bad != 0 && lane == 0 && o + bad <= n) atomicCAS(it.info, 0, it.pivot_base + o + bad);
         }
         __syncthreads();
+        DIAG_STAMP(3 + 3 * p);
         // panel solve: U[p][q] = W_pp^T T[p][q], mirrored below the diagonal
         for (int q = p + 1 + wave; q < NB / SB; q += 4) {
             const diag_floatx16 acc = sb_mma(Ss, o, o, DM_UPPER, Fs, o, q * SB, DM_NONE, SB, lane);
             sb_store(acc, Fs, o, q * SB, 1.f, false, Fs, lane);
         }
         __syncthreads();
+        DIAG_STAMP(4 + 3 * p);
         // trailing update: T[q][r] -= U[p][q]^T U[p][r] for p < q <= r
         int job = 0;
         for (int q = p + 1; q < NB / SB; ++q)
@@ -186,13 +223,28 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
         __syncthreads();
     }
 
+    DIAG_STAMP(14);
     // U is final: write it out before the merges reuse the space above the diagonal.
-    for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
-        const int r = e / NB, c = e % NB;
-        if (r < n && c < n && r <= c) it.F[(size_t)r * it.ldf + c] = Fs[r][c];
+    {
+        const int c4 = (tid & 31) << 2, r0 = tid >> 5;
+#pragma unroll
+        for (int q = 0; q < NB / 8; ++q) {
+            const int r = r0 + 8 * q;
+            if (n == NB && c4 >= r) {  // whole float4 on or above the diagonal
+                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) =
+                    make_float4(Fs[r][c4], Fs[r][c4 + 1], Fs[r][c4 + 2], Fs[r][c4 + 3]);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int c = c4 + t;
+                    if (r < n && c < n && r <= c) it.F[(size_t)r * it.ldf + c] = Fs[r][c];
+                }
+            }
+        }
     }
     __syncthreads();
 
+    DIAG_STAMP(15);
     // Phase 2: W = U^-1 by pairwise merges, [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
     for (int b = SB; b < NB; b *= 2) {
         const int nodes = NB / (2 * b), sub = b / SB;       // sub x sub output sub-blocks per node
@@ -215,10 +267,25 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
         __syncthreads();
     }
 
-    for (int e = tid; e < NB * NB; e += DIAG_THREADS) {
-        const int r = e / NB, c = e % NB;
-        if (r < n && c < n) it.S[(size_t)r * it.lds + c] = Ss[r][c];
+    DIAG_STAMP(16);
+    {
+        const int c4 = (tid & 31) << 2, r0 = tid >> 5;
+#pragma unroll
+        for (int q = 0; q < NB / 8; ++q) {
+            const int r = r0 + 8 * q;
+            if (n == NB) {
+                *reinterpret_cast<float4 *>(&it.S[(size_t)r * it.lds + c4]) =
+                    make_float4(Ss[r][c4], Ss[r][c4 + 1], Ss[r][c4 + 2], Ss[r][c4 + 3]);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int c = c4 + t;
+                    if (r < n && c < n) it.S[(size_t)r * it.lds + c] = Ss[r][c];
+                }
+            }
+        }
     }
+    DIAG_STAMP(17);
 }
 
 struct PrepItem {
