@@ -221,8 +221,8 @@ def cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping, f_curv, f_inv
     """Time the fp64 oracle, as it stands, on one layer of the workload and scale to a step."""
     from oracle import kfac_oracle as oracle
 
-    # sample: every linear of the first encoder block, micro-batch 0
-    nl = len(cfg["layers"])
+    # sample: every linear of the first two encoder blocks (or of the only one), micro-batch 0
+    nl = len(cfg["layers"]) * min(2, cfg["blocks"])
     hx = [xs[0][2 * i].cpu().numpy() for i in range(nl)]
     he = [xs[0][2 * i + 1].cpu().numpy() for i in range(nl)]
     hg = [grads[i].cpu().numpy() for i in range(nl)]
@@ -245,7 +245,7 @@ def cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping, f_curv, f_inv
         "unit": "ms",
         "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": "fp64 oracle on the %d linears of one encoder block, one micro-batch of %d tokens: curvature "
+        "sample": "fp64 oracle on the first %d linears of the stage, one micro-batch of %d tokens: curvature "
                   "%.2f s, inversion %.2f s, precondition %.2f s; each phase scaled by the step's useful flops "
                   "over the sample's" % (nl, tokens, t1 - t0, t2 - t1, t3 - t2),
     }

@@ -286,11 +286,19 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         lp.c.beta = beta;
         lp.c.partial = part;
         lp.c.in_bf16 = (dtype == KFAC_BF16) ? 1 : 0;
-        hipLaunchKernelGGL(curvature_syrk_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lp);
-        if (pl.splits > 1) {
-            hipLaunchKernelGGL(curvature_reduce_kernel, dim3(tiles / pl.splits), dim3(TN_THREADS), 0, st, lp);
-            part += (size_t)tiles * BM * BN;
+        if (dtype == KFAC_BF16) {
+            SyrkLaunchBf16 lb;
+            static_assert(sizeof(lb) == sizeof(lp), "both curvature launch types share one layout");
+            std::memcpy(&lb, &lp, sizeof(lp));
+            hipLaunchKernelGGL(curvature_syrk_bf16_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lb);
+            if (pl.splits > 1)
+                hipLaunchKernelGGL(curvature_reduce_bf16_kernel, dim3(tiles / pl.splits), dim3(TN_THREADS), 0, st, lb);
+        } else {
+            hipLaunchKernelGGL(curvature_syrk_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lp);
+            if (pl.splits > 1)
+                hipLaunchKernelGGL(curvature_reduce_kernel, dim3(tiles / pl.splits), dim3(TN_THREADS), 0, st, lp);
         }
+        if (pl.splits > 1) part += (size_t)tiles * BM * BN;
         if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
         done += n;
     }

@@ -29,7 +29,11 @@ constexpr int BN = 128;
 constexpr int BK = 16;
 constexpr int TN_THREADS = 256;
 constexpr int TN_MAX_PROBLEMS = 48;
+#ifdef TN_EXP_CHUNK
+constexpr int TN_CHUNK_SLABS = TN_EXP_CHUNK;
+#else
 constexpr int TN_CHUNK_SLABS = 8;  // fold the running sum every 8 * 16 = 128 rows of K
+#endif
 constexpr int SUPER_ROWS = 8;      // tiles of 8 consecutive tile-rows are scheduled together
 
 enum TileMode : int { TILE_FULL = 0, TILE_LOWER = 1, TILE_UPPER = 2 };
@@ -62,6 +66,7 @@ struct TnCommon {
 // General launch: up to TN_MAX_PROBLEMS arbitrary problems.
 struct TnLaunch {
     static constexpr bool kAllowBf16 = false;
+    static constexpr bool kAllowMask = true;
     TnProblem p[TN_MAX_PROBLEMS];
     TnCommon c;
     __device__ int tile_begin(int i) const { return p[i].tile_begin; }
@@ -81,8 +86,10 @@ struct SyrkProblem {
     int pad_;
 };
 
-struct SyrkLaunch {
-    static constexpr bool kAllowBf16 = true;
+template <bool BF16IN>
+struct SyrkLaunchT {
+    static constexpr bool kAllowBf16 = BF16IN;
+    static constexpr bool kAllowMask = false;
     SyrkProblem p[SYRK_MAX_PROBLEMS];
     TnCommon c;
     __device__ int tile_begin(int i) const { return p[i].tile_begin; }
@@ -97,6 +104,8 @@ struct SyrkLaunch {
         return r;
     }
 };
+typedef SyrkLaunchT<false> SyrkLaunch;      // float32 activations / errors
+typedef SyrkLaunchT<true> SyrkLaunchBf16;   // bfloat16 activations / errors
 
 // Inversion launch: the problems of one phase of the blocked inversion are
 // described by (matrix, up to three block indices); pointers and sizes follow
@@ -151,6 +160,7 @@ __host__ __device__ inline InvDims inv_dims(int op, int d, int a, int b, int c)
 
 struct InvLaunch {
     static constexpr bool kAllowBf16 = false;
+    static constexpr bool kAllowMask = true;
     InvMatDesc m[INV_MAX_MATS];
     InvNode n[INV_MAX_NODES];
     TnCommon c;
@@ -385,9 +395,45 @@ __device__ inline bool tn_keep(bool diag, int mode, int m, int n)
     return !diag || (mode == TILE_LOWER ? n <= m : n >= m);
 }
 
-constexpr int TN_STAGES = 3;  // LDS ring: slab s lives in stage s % 3
+#ifdef TN_EXP_PRIO
+#define TN_PRIO_HI() __builtin_amdgcn_s_setprio(1)
+#define TN_PRIO_LO() __builtin_amdgcn_s_setprio(0)
+#else
+#define TN_PRIO_HI() do {} while (0)
+#define TN_PRIO_LO() do {} while (0)
+#endif
+
+// timing experiments only (results are wrong with these): never defined in the product build
+__device__ inline void tn_exp_use(const float4 &v) { asm volatile("" ::"v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
+__device__ inline void tn_exp_use(const uint2 &v) { asm volatile("" ::"v"(v.x), "v"(v.y)); }
+#if defined(TN_EXP_NOLOAD)
+#define TN_EXP_W(a, b) do { kw += BK; } while (0)
+#define TN_EXP_G(a, b) do {} while (0)
+#elif defined(TN_EXP_GONLY)
+#define TN_EXP_W(a, b) do { kw += BK; tn_exp_use(ra[b][0]); tn_exp_use(ra[b][1]); tn_exp_use(rb[b][0]); tn_exp_use(rb[b][1]); } while (0)
+#define TN_EXP_G(a, b) TN_G(a, b)
+#elif defined(TN_EXP_WONLY)
+#define TN_EXP_W(a, b) TN_W(a, b)
+#define TN_EXP_G(a, b) do {} while (0)
+#else
+#define TN_EXP_W(a, b) TN_W(a, b)
+#define TN_EXP_G(a, b) TN_G(a, b)
+#endif
+#ifdef TN_EXP_NOBAR
+#define TN_EXP_SYNC() do {} while (0)
+#else
+#define TN_EXP_SYNC() __syncthreads()
+#endif
+
+constexpr int TN_STAGES = 3;      // LDS ring of the register-staged loop: slab s lives in stage s % 3
+constexpr int TN_LDS_STAGES = 4;  // stages allocated (the direct-to-LDS loop uses all four)
 
 // sched_group_barrier masks
+#ifdef TN_EXP_NOSCHED
+#define TN_SGB(m, n) do {} while (0)
+#else
+#define TN_SGB(m, n) __builtin_amdgcn_sched_group_barrier(m, n, 0)
+#endif
 constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200;
 
 // K loop of one tile.  FAST: both operands can be read with aligned 16-byte
@@ -405,7 +451,7 @@ constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_W
 // used, which keeps the loop body free of branches.
 template <bool FAST, bool MASKED, bool BF16>
 __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, const TnTile &tl,
-                                   float (&As)[TN_STAGES][BK][BM], float (&Bs)[TN_STAGES][BK][BN],
+                                   float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                    floatx16 (&sum)[2][2])
 {
     const int tid = threadIdx.x;
@@ -475,31 +521,33 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
     // global loads and operand reads are spread one by one between the MFMAs.
 #define TN_ITER(set)                                                                 \
     do {                                                                             \
-        TN_W(st2, set);                                                              \
-        TN_G(set, 1);                                                                \
+        TN_PRIO_HI();                                                                \
+        TN_EXP_W(st2, set);                                                          \
+        TN_EXP_G(set, 1);                                                            \
         TN_R(st0, 1);                                                                \
         TN_M(0);                                                                     \
         TN_R(st1, 0);                                                                \
         TN_M(1);                                                                     \
         _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                           \
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);                     \
-            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);                  \
+            TN_SGB(SG_MFMA, 1);                     \
+            TN_SGB(SG_DS_READ, 1);                  \
         }                                                                            \
         _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                           \
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);                     \
-            __builtin_amdgcn_sched_group_barrier(SG_DS_WRITE, 1, 0);                 \
+            TN_SGB(SG_MFMA, 1);                     \
+            TN_SGB(SG_DS_WRITE, 1);                 \
         }                                                                            \
         _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                           \
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);                     \
-            __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, FAST ? 1 : 4, 0);     \
+            TN_SGB(SG_MFMA, 1);                     \
+            TN_SGB(SG_VMEM_READ, FAST ? 1 : 4);     \
         }                                                                            \
-        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 4, 0);                         \
+        TN_SGB(SG_MFMA, 4);                         \
         _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                           \
-            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);                     \
-            __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);                  \
+            TN_SGB(SG_MFMA, 1);                     \
+            TN_SGB(SG_DS_READ, 1);                  \
         }                                                                            \
-        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 12, 0);                        \
-        __syncthreads();                                                             \
+        TN_SGB(SG_MFMA, 12);                        \
+        TN_PRIO_LO();                                                                \
+        TN_EXP_SYNC();                                                               \
         const int t_ = st0;                                                          \
         st0 = st1;                                                                   \
         st1 = st2;                                                                   \
@@ -547,8 +595,150 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
         for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands
+// at lds_row + 16 * l (lds_row must be the same for the whole wave).
+__device__ inline void tn_dma16(const float *gptr, const float *lds_row)
+{
+    // byte offset in LDS; the same for every lane of the wave, so it can live in a scalar register
+    const unsigned lds_addr = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(const __attribute__((address_space(3))) float *)lds_row);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
+// K loop for the common case (fp32 operands, aligned full-width tiles, no
+// masks, K range a multiple of BK): slabs go from global memory straight into
+// LDS (global_load_lds_dwordx4: lane l's 16 bytes land at base + 16*l, so one
+// wave instruction fills two 512-byte rows), without staging registers, LDS
+// stores or fix-up arithmetic.  Four LDS stages:
+//   iteration s:  D(s+3)  R(second half of s)  M(first half of s)
+//                 R(first half of s+1)  M(second half of s)  wait D(s+2)  barrier
+// D(s+3) overwrites the stage of slab s-1, which every wave finished reading
+// before the previous barrier.
+__device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
+                                          float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
+                                          floatx16 (&sum)[2][2])
+{
+    const int tid = threadIdx.x;
+    const int K = pr.K;
+    const float *__restrict__ A = pr.A;
+    const float *__restrict__ B = pr.B;
+    const size_t lda = (size_t)pr.lda, ldb = (size_t)pr.ldb;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int li = lane & 31, lh = lane >> 5;
+    const int drow = 2 * wave + lh;  // row of the slab this lane fetches (and drow + 8)
+    const float *ga = A + tl.m0 + 4 * li;
+    const float *gb = B + tl.n0 + 4 * li;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nslab = tl.kt1 - tl.kt0;
+    if (nslab <= 0) return;
+    float2 fa[2][4], fb[2][4];
+    int kd = tl.kbase + tl.kt0 * BK;  // first K row of the next slab to request
+
+    // rows past the end of the matrix are clamped: that data is never consumed.
+    // The load is written as inline assembly on purpose: issued through the
+    // builtin, the compiler drains vmcnt before every later LDS read (it cannot
+    // tell the ring stages apart), which would undo the pipeline.  The waits are
+    // placed by hand instead (TN_WAIT_ALL_BUT_NEWEST_SLAB before each barrier).
+#define TN_D(st)                                                                                   \
+    do {                                                                                           \
+        const size_t r0_ = (size_t)min(kd + drow, K - 1), r1_ = (size_t)min(kd + 8 + drow, K - 1); \
+        tn_dma16(ga + r0_ * lda, &As[st][2 * wave][0]);                                            \
+        tn_dma16(ga + r1_ * lda, &As[st][8 + 2 * wave][0]);                                        \
+        tn_dma16(gb + r0_ * ldb, &Bs[st][2 * wave][0]);                                            \
+        tn_dma16(gb + r1_ * ldb, &Bs[st][8 + 2 * wave][0]);                                        \
+        kd += BK;                                                                                  \
+    } while (0)
+#define TN_R(st, half)                                                                                            \
+    do {                                                                                                          \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                           \
+            fa[half][q] = *reinterpret_cast<const float2 *>(&As[st][8 * (half) + 2 * q + lh][wm + 2 * li]);       \
+            fb[half][q] = *reinterpret_cast<const float2 *>(&Bs[st][8 * (half) + 2 * q + lh][wn + 2 * li]);       \
+        }                                                                                                         \
+    } while (0)
+#define TN_M(half)                                                                                                \
+    do {                                                                                                          \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                           \
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].x, acc[0][0], 0, 0, 0);   \
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].y, acc[0][1], 0, 0, 0);   \
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].x, acc[1][0], 0, 0, 0);   \
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[1][1], 0, 0, 0);   \
+        }                                                                                                         \
+    } while (0)
+    // s_waitcnt vmcnt(4): everything but the four newest loads has landed (gfx9 encoding:
+    // vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; the other counters are left open)
+#define TN_WAIT_ALL_BUT_NEWEST_SLAB() __builtin_amdgcn_s_waitcnt(0x0F74)
+
+    TN_D(0);
+    TN_D(1);
+    TN_D(2);
+    TN_WAIT_ALL_BUT_NEWEST_SLAB();
+    __syncthreads();
+    TN_R(0, 0);
+
+    int folded = 0;
+    for (int s = 0; s < nslab; ++s) {
+        const int st0 = s & 3, st1 = (s + 1) & 3, st3 = (s + 3) & 3;
+        TN_D(st3);
+        TN_R(st0, 1);
+        TN_M(0);
+        TN_R(st1, 0);
+        TN_M(1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            TN_SGB(SG_MFMA, 1);
+            TN_SGB(SG_DS_READ, 1);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            TN_SGB(SG_MFMA, 1);
+            TN_SGB(SG_VMEM_READ, 1);
+        }
+        TN_SGB(SG_MFMA, 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            TN_SGB(SG_MFMA, 1);
+            TN_SGB(SG_DS_READ, 1);
+        }
+        TN_SGB(SG_MFMA, 12);
+        TN_WAIT_ALL_BUT_NEWEST_SLAB();
+        __syncthreads();
+        if (++folded == TN_CHUNK_SLABS) {
+            folded = 0;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    sum[i][j] += acc[i][j];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no load may still be writing LDS when the tile ends
+#undef TN_D
+#undef TN_R
+#undef TN_M
+#undef TN_WAIT_ALL_BUT_NEWEST_SLAB
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
+}
+
 template <class L>
-__device__ inline void tn_tile_body(const L &ll, float (&As)[TN_STAGES][BK][BM], float (&Bs)[TN_STAGES][BK][BN])
+__device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN])
 {
     const TnCommon &lp = ll.c;
     const int tid = threadIdx.x;
@@ -557,7 +747,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_STAGES][BK][BM],
     const int M = pr.M, N = pr.N;
 
     // vector loads need 16-byte (fp32) / 8-byte (bf16) aligned rows
-    const bool bf16 = L::kAllowBf16 && lp.in_bf16 != 0;
+    const bool bf16 = L::kAllowBf16;  // the bfloat16 curvature launch has a kernel of its own
     const uintptr_t amask = bf16 ? 7 : 15;
     const bool fast_a = (tl.m0 + BM <= M) && ((pr.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.A) & amask) == 0);
     const bool fast_b = (tl.n0 + BN <= N) && ((pr.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.B) & amask) == 0);
@@ -574,7 +764,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_STAGES][BK][BM],
 #pragma unroll
             for (int r = 0; r < 16; ++r) sum[i][j][r] = 0.f;
 
-    const bool masked = (lp.mask_a | lp.mask_b) != 0;
+    const bool masked = L::kAllowMask && (lp.mask_a | lp.mask_b) != 0;
     bool done = false;
     if constexpr (L::kAllowBf16) {
         if (bf16) {
@@ -585,15 +775,23 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_STAGES][BK][BM],
             done = true;
         }
     }
+    if (!done && fast_a && fast_b && !masked && (pr.K % BK) == 0) {
+        tn_mainloop_direct(pr, tl, As, Bs, sum);
+        done = true;
+    }
     if (!done) {
-        if (fast_a && fast_b) {
-            if (masked)
-                tn_mainloop<true, true, false>(lp, pr, tl, As, Bs, sum);
-            else
+        if constexpr (L::kAllowMask) {
+            if (masked) {
+                if (fast_a && fast_b)
+                    tn_mainloop<true, true, false>(lp, pr, tl, As, Bs, sum);
+                else
+                    tn_mainloop<false, true, false>(lp, pr, tl, As, Bs, sum);
+                done = true;
+            }
+        }
+        if (!done) {
+            if (fast_a && fast_b)
                 tn_mainloop<true, false, false>(lp, pr, tl, As, Bs, sum);
-        } else {
-            if (masked)
-                tn_mainloop<false, true, false>(lp, pr, tl, As, Bs, sum);
             else
                 tn_mainloop<false, false, false>(lp, pr, tl, As, Bs, sum);
         }
@@ -730,8 +928,8 @@ __device__ inline void tn_reduce_body(const L &ll)
 
 __global__ __launch_bounds__(TN_THREADS, 2) void tn_gemm_kernel(const TnLaunch lp)
 {
-    __shared__ float As[TN_STAGES][BK][BM];
-    __shared__ float Bs[TN_STAGES][BK][BN];
+    __shared__ float As[TN_LDS_STAGES][BK][BM];
+    __shared__ float Bs[TN_LDS_STAGES][BK][BN];
     tn_tile_body(lp, As, Bs);
 }
 
@@ -741,18 +939,28 @@ __global__ __launch_bounds__(TN_THREADS) void tn_reduce_kernel(const TnLaunch lp
 // launches can be told apart in a kernel trace.
 __global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_kernel(const SyrkLaunch lp)
 {
-    __shared__ float As[TN_STAGES][BK][BM];
-    __shared__ float Bs[TN_STAGES][BK][BN];
+    __shared__ float As[TN_LDS_STAGES][BK][BM];
+    __shared__ float Bs[TN_LDS_STAGES][BK][BN];
     tn_tile_body(lp, As, Bs);
 }
 
 __global__ __launch_bounds__(TN_THREADS) void curvature_reduce_kernel(const SyrkLaunch lp) { tn_reduce_body(lp); }
 
+// Same for bfloat16 inputs: widened exactly to float32 on the way to LDS, fp32 MFMA and accumulation.
+__global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_bf16_kernel(const SyrkLaunchBf16 lp)
+{
+    __shared__ float As[TN_LDS_STAGES][BK][BM];
+    __shared__ float Bs[TN_LDS_STAGES][BK][BN];
+    tn_tile_body(lp, As, Bs);
+}
+
+__global__ __launch_bounds__(TN_THREADS) void curvature_reduce_bf16_kernel(const SyrkLaunchBf16 lp) { tn_reduce_body(lp); }
+
 // The products of the blocked inversion (panel solves, row / trailing updates, merges).
 __global__ __launch_bounds__(TN_THREADS, 2) void invert_gemm_kernel(const InvLaunch lp)
 {
-    __shared__ float As[TN_STAGES][BK][BM];
-    __shared__ float Bs[TN_STAGES][BK][BN];
+    __shared__ float As[TN_LDS_STAGES][BK][BM];
+    __shared__ float Bs[TN_LDS_STAGES][BK][BN];
     tn_tile_body(lp, As, Bs);
 }
 
