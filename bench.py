@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 PEAK_F32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
 # HBM traffic of one curvature launch of the default workload, from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (None = not measured).
-CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 9.74e9  # profiles/curvature_syrk_pmc.txt: 8.65 GB fetched + 1.09 GB written
+CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 11.17e9  # profiles/curvature_syrk_pmc.txt: 10.08 GB fetched + 1.09 GB written
 
 
 def parse():

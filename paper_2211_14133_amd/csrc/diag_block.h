@@ -35,11 +35,6 @@ constexpr int LDT = NB + 4;   // LDS row stride in floats
 
 typedef float diag_floatx16 __attribute__((ext_vector_type(16)));
 
-#ifdef DIAG_PROFILE
-#define DIAG_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_stamps[i] = (long long)__builtin_readcyclecounter(); } while (0)
-#else
-#define DIAG_STAMP(i) do {} while (0)
-#endif
 
 enum DiagMask : int { DM_NONE = 0, DM_UPPER = 1, DM_LOWER = 2 };  // keep row <= col / row >= col
 
@@ -161,8 +156,6 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
     const int n = it.n;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-
-    DIAG_STAMP(0);
     // the working copy's rows are 16-byte aligned (ld multiple of 32, block offsets multiples of 128)
     {
         const int c4 = (tid & 31) << 2, r0 = tid >> 5;
@@ -193,25 +186,20 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
         }
     }
     __syncthreads();
-
-    DIAG_STAMP(1);
     // Phase 1: right-looking factorisation over the four 32-wide panels.
     for (int p = 0; p < NB / SB; ++p) {
         const int o = p * SB;
-        DIAG_STAMP(2 + 3 * p);
         if (wave == 0) {
             const int bad = sb_factor_invert(Fs, Ss, o, lane);
             if (bad != 0 && lane == 0 && o + bad <= n) atomicCAS(it.info, 0, it.pivot_base + o + bad);
         }
         __syncthreads();
-        DIAG_STAMP(3 + 3 * p);
         // panel solve: U[p][q] = W_pp^T T[p][q], mirrored below the diagonal
         for (int q = p + 1 + wave; q < NB / SB; q += 4) {
             const diag_floatx16 acc = sb_mma(Ss, o, o, DM_UPPER, Fs, o, q * SB, DM_NONE, SB, lane);
             sb_store(acc, Fs, o, q * SB, 1.f, false, Fs, lane);
         }
         __syncthreads();
-        DIAG_STAMP(4 + 3 * p);
         // trailing update: T[q][r] -= U[p][q]^T U[p][r] for p < q <= r
         int job = 0;
         for (int q = p + 1; q < NB / SB; ++q)
@@ -222,8 +210,6 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
             }
         __syncthreads();
     }
-
-    DIAG_STAMP(14);
     // U is final: write it out before the merges reuse the space above the diagonal.
     {
         const int c4 = (tid & 31) << 2, r0 = tid >> 5;
@@ -243,8 +229,6 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
         }
     }
     __syncthreads();
-
-    DIAG_STAMP(15);
     // Phase 2: W = U^-1 by pairwise merges, [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
     for (int b = SB; b < NB; b *= 2) {
         const int nodes = NB / (2 * b), sub = b / SB;       // sub x sub output sub-blocks per node
@@ -266,8 +250,6 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
         }
         __syncthreads();
     }
-
-    DIAG_STAMP(16);
     {
         const int c4 = (tid & 31) << 2, r0 = tid >> 5;
 #pragma unroll
@@ -285,7 +267,6 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
             }
         }
     }
-    DIAG_STAMP(17);
 }
 
 struct PrepItem {

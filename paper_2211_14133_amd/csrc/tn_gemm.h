@@ -29,11 +29,7 @@ constexpr int BN = 128;
 constexpr int BK = 16;
 constexpr int TN_THREADS = 256;
 constexpr int TN_MAX_PROBLEMS = 48;
-#ifdef TN_EXP_CHUNK
-constexpr int TN_CHUNK_SLABS = TN_EXP_CHUNK;
-#else
 constexpr int TN_CHUNK_SLABS = 8;  // fold the running sum every 8 * 16 = 128 rows of K
-#endif
 constexpr int SUPER_ROWS = 8;      // tiles of 8 consecutive tile-rows are scheduled together
 
 enum TileMode : int { TILE_FULL = 0, TILE_LOWER = 1, TILE_UPPER = 2 };
@@ -395,45 +391,11 @@ __device__ inline bool tn_keep(bool diag, int mode, int m, int n)
     return !diag || (mode == TILE_LOWER ? n <= m : n >= m);
 }
 
-#ifdef TN_EXP_PRIO
-#define TN_PRIO_HI() __builtin_amdgcn_s_setprio(1)
-#define TN_PRIO_LO() __builtin_amdgcn_s_setprio(0)
-#else
-#define TN_PRIO_HI() do {} while (0)
-#define TN_PRIO_LO() do {} while (0)
-#endif
-
-// timing experiments only (results are wrong with these): never defined in the product build
-__device__ inline void tn_exp_use(const float4 &v) { asm volatile("" ::"v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
-__device__ inline void tn_exp_use(const uint2 &v) { asm volatile("" ::"v"(v.x), "v"(v.y)); }
-#if defined(TN_EXP_NOLOAD)
-#define TN_EXP_W(a, b) do { kw += BK; } while (0)
-#define TN_EXP_G(a, b) do {} while (0)
-#elif defined(TN_EXP_GONLY)
-#define TN_EXP_W(a, b) do { kw += BK; tn_exp_use(ra[b][0]); tn_exp_use(ra[b][1]); tn_exp_use(rb[b][0]); tn_exp_use(rb[b][1]); } while (0)
-#define TN_EXP_G(a, b) TN_G(a, b)
-#elif defined(TN_EXP_WONLY)
-#define TN_EXP_W(a, b) TN_W(a, b)
-#define TN_EXP_G(a, b) do {} while (0)
-#else
-#define TN_EXP_W(a, b) TN_W(a, b)
-#define TN_EXP_G(a, b) TN_G(a, b)
-#endif
-#ifdef TN_EXP_NOBAR
-#define TN_EXP_SYNC() do {} while (0)
-#else
-#define TN_EXP_SYNC() __syncthreads()
-#endif
-
 constexpr int TN_STAGES = 3;      // LDS ring of the register-staged loop: slab s lives in stage s % 3
 constexpr int TN_LDS_STAGES = 4;  // stages allocated (the direct-to-LDS loop uses all four)
 
 // sched_group_barrier masks
-#ifdef TN_EXP_NOSCHED
-#define TN_SGB(m, n) do {} while (0)
-#else
 #define TN_SGB(m, n) __builtin_amdgcn_sched_group_barrier(m, n, 0)
-#endif
 constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200;
 
 // K loop of one tile.  FAST: both operands can be read with aligned 16-byte
@@ -521,9 +483,8 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
     // global loads and operand reads are spread one by one between the MFMAs.
 #define TN_ITER(set)                                                                 \
     do {                                                                             \
-        TN_PRIO_HI();                                                                \
-        TN_EXP_W(st2, set);                                                          \
-        TN_EXP_G(set, 1);                                                            \
+        TN_W(st2, set);                                                              \
+        TN_G(set, 1);                                                                \
         TN_R(st0, 1);                                                                \
         TN_M(0);                                                                     \
         TN_R(st1, 0);                                                                \
@@ -546,8 +507,7 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
             TN_SGB(SG_DS_READ, 1);                  \
         }                                                                            \
         TN_SGB(SG_MFMA, 12);                        \
-        TN_PRIO_LO();                                                                \
-        TN_EXP_SYNC();                                                               \
+        __syncthreads();                                                             \
         const int t_ = st0;                                                          \
         st0 = st1;                                                                   \
         st1 = st2;                                                                   \
