@@ -19,8 +19,9 @@
  *    (the paper computes everything in fp32) unless a dtype argument says
  *    otherwise.  Leading dimensions (ld*) count elements between rows.
  *  - Ownership: every buffer, the workspace included, belongs to the caller.
- *    The library allocates and frees nothing, keeps no pointer after the call
- *    returns and has no global state.
+ *    The library allocates no device memory, has no global state and keeps no
+ *    pointer after a call returns (the one exception, the host-side plan of
+ *    the chunked inversion, is described with it).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Work is only enqueued; no call synchronises with the host.
  *  - `workspace` is device scratch of at least the size the matching
@@ -130,6 +131,35 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
                                 void *workspace, size_t workspace_bytes, void *stream);
 size_t kfac_invert_batched_workspace(const kfac_invert_item *items, int64_t count);
 
+/* ------------------------------------------------------ chunked inversion
+ * Section 3.1 assigns work to bubbles only if it fits, and section 5 notes
+ * that the work for a single matrix has to be divisible to use bubbles well.
+ * A plan is the fixed sequence of kernel launches of one kfac_invert_batched
+ * call, recorded once; a scheduler runs it a few launches at a time, in
+ * order, on any stream, between other work.  Running all steps is exactly
+ * kfac_invert_batched.  `inv` buffers are written by the last steps only.
+ *
+ * The plan lives in host memory obtained from the C++ heap (this is the only
+ * allocation the library makes; it never allocates device memory).  It keeps
+ * the device pointers of `items` and of `workspace`: those must stay valid,
+ * and the workspace must not be used by anything else, until the plan has
+ * run to its end.  A plan can be reset and run again (next refresh).
+ */
+typedef struct kfac_invert_plan kfac_invert_plan;
+
+kfac_status kfac_invert_plan_create(const kfac_invert_item *items, int64_t count, float damping,
+                                    void *workspace, size_t workspace_bytes, kfac_invert_plan **plan);
+/* number of steps (one step = one kernel launch, at most two) */
+int64_t kfac_invert_plan_steps(const kfac_invert_plan *plan);
+/* index of the next step to run */
+int64_t kfac_invert_plan_position(const kfac_invert_plan *plan);
+/* model cost of a step in floating point operations (0 for copies, -1 for a bad index) */
+double kfac_invert_plan_step_flops(const kfac_invert_plan *plan, int64_t step);
+/* enqueue the next n_steps steps (fewer if the end is reached) on `stream` */
+kfac_status kfac_invert_plan_run(kfac_invert_plan *plan, int64_t n_steps, void *stream);
+kfac_status kfac_invert_plan_reset(kfac_invert_plan *plan);
+void kfac_invert_plan_destroy(kfac_invert_plan *plan);
+
 /* ------------------------------------------------------------- precondition
  * Section 2.3.1: (A (x) B)^-1 vec(G) = vec(B^-1 G A^-1), vec stacking columns.
  *
@@ -164,6 +194,49 @@ typedef struct {
 kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64_t count,
                                       void *workspace, size_t workspace_bytes, void *stream);
 size_t kfac_precondition_grouped_workspace(const kfac_precondition_item *items, int64_t count);
+
+/* ------------------------------------------- bubble filling (host side only)
+ * Section 3.1 "Automatic Work Assignments": K-FAC work is taken from a queue
+ * and put into the first pipeline bubble that is long enough and lies after the
+ * work it depends on; bubbles of later pipeline steps are used when the
+ * current ones are full; the result is a static schedule that is repeated.
+ *
+ * One pipeline step of one device is described by its bubbles (idle
+ * intervals, relative to the start of the step, sorted, not overlapping) and
+ * the step period (start-to-start time of consecutive steps, precondition
+ * included: rule 3 puts it after the last backward pass, outside the bubbles).
+ * Work w consists of chunk_count[w] indivisible chunks (durations in
+ * chunk_time, concatenated in work order), becomes available at release[w]
+ * (time in step 0, e.g. the end of the forward pass of its micro-batch: rule 1)
+ * and after every work listed in dep_ids[dep_begin[w] .. dep_begin[w+1])
+ * (rule 2: an inversion after all its curvature work; ids must be smaller
+ * than w).  Works are placed in index order, chunk by chunk, first fit.
+ *
+ * Outputs, one entry per chunk in the same order as chunk_time: the pipeline
+ * step (0, 1, ...) and bubble index it went to and its start time relative to
+ * that step's start.  *steps_needed receives the number of pipeline steps the
+ * whole queue takes (the refresh interval of section 3.1).
+ * Returns KFAC_ERR_ARG for malformed input and KFAC_ERR_UNSUPPORTED if a chunk
+ * is longer than every bubble (the work has to be cut finer).
+ */
+kfac_status kfac_assign_work(int64_t n_bubbles, const double *bubble_start, const double *bubble_length,
+                             double step_period,
+                             int64_t n_works, const int64_t *chunk_count, const double *chunk_time,
+                             const double *release, const int64_t *dep_begin, const int64_t *dep_ids,
+                             int64_t *out_step, int64_t *out_bubble, double *out_start,
+                             int64_t *steps_needed);
+
+/* Section 3.3 "Performance Modeling", closed forms for one pipeline step:
+ *   t_pipe   = c_f * t_f + c_b * t_b
+ *   t_bubble = t_pipe - n_micro * (t_f + t_b)
+ *   t_kfac   = n_micro * t_curv + t_inv + t_prec
+ *   ratio    = (n_micro * t_curv + t_inv) / t_bubble     (steps per refresh)
+ * c_f, c_b: forward / backward passes on the critical path of the schedule.
+ * out[0..4] = t_pipe, t_bubble, t_kfac, ratio, step time with bubble filling
+ * (t_pipe + t_prec).
+ */
+kfac_status kfac_perf_model(double c_f, double c_b, double t_f, double t_b, int64_t n_micro,
+                            double t_curv, double t_inv, double t_prec, double *out);
 
 /* ------------------------------------------------------------------- misc */
 const char *kfac_status_string(kfac_status status);

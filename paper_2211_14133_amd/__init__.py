@@ -1,6 +1,9 @@
 """MI355X-native K-FAC work items (curvature, inversion, precondition) behind a C ABI."""
 from .binding import (  # noqa: F401
+    InvertPlan,
     KfacError,
+    kfac_assign_work,
+    kfac_perf_model,
     kfac_curvature,
     kfac_curvature_grouped,
     kfac_curvature_grouped_workspace,

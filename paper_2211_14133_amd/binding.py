@@ -19,6 +19,8 @@ _i64 = ctypes.c_int64
 _f32 = ctypes.c_float
 _vp = ctypes.c_void_p
 _sz = ctypes.c_size_t
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int64)
 
 
 class CurvatureItem(ctypes.Structure):
@@ -48,6 +50,16 @@ SIGNATURES = {
     "kfac_precondition_workspace": (_sz, [_i64, _i64]),
     "kfac_precondition_grouped": (ctypes.c_int, [ctypes.POINTER(PreconditionItem), _i64, _vp, _sz, _vp]),
     "kfac_precondition_grouped_workspace": (_sz, [ctypes.POINTER(PreconditionItem), _i64]),
+    "kfac_invert_plan_create": (ctypes.c_int, [ctypes.POINTER(InvertItem), _i64, _f32, _vp, _sz, ctypes.POINTER(_vp)]),
+    "kfac_invert_plan_steps": (_i64, [_vp]),
+    "kfac_invert_plan_position": (_i64, [_vp]),
+    "kfac_invert_plan_step_flops": (ctypes.c_double, [_vp, _i64]),
+    "kfac_invert_plan_run": (ctypes.c_int, [_vp, _i64, _vp]),
+    "kfac_invert_plan_reset": (ctypes.c_int, [_vp]),
+    "kfac_invert_plan_destroy": (None, [_vp]),
+    "kfac_assign_work": (ctypes.c_int, [_i64, _dp, _dp, ctypes.c_double, _i64, _ip, _dp, _dp, _ip, _ip, _ip, _ip, _dp, _ip]),
+    "kfac_perf_model": (ctypes.c_int, [ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double, _i64,
+                                       ctypes.c_double, ctypes.c_double, ctypes.c_double, _dp]),
     "kfac_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "kfac_version": (ctypes.c_int, []),
 }
@@ -238,3 +250,90 @@ def kfac_precondition_grouped(b_invs, a_invs, grads, outs, workspace=None, strea
     ws, nbytes, keep = _workspace(need, grads[0], workspace)
     _check(lib.kfac_precondition_grouped(arr, len(grads), ws, nbytes, _stream(stream)))
     return outs
+
+
+class InvertPlan:
+    """Chunked form of kfac_invert_batched: the launch sequence is recorded once and run piecewise."""
+
+    def __init__(self, factors, damping, invs, infos=None, workspace=None):
+        lib = load()
+        if infos is None:
+            infos = torch.zeros(len(factors), dtype=torch.int32, device=factors[0].device)
+        self.infos = infos
+        self._keep = (list(factors), list(invs), infos)
+        arr = _inv_items(factors, invs, infos)
+        need = lib.kfac_invert_batched_workspace(arr, len(factors))
+        ws, nbytes, self._ws = _workspace(need, factors[0], workspace)
+        handle = ctypes.c_void_p()
+        _check(lib.kfac_invert_plan_create(arr, len(factors), damping, ws, nbytes, ctypes.byref(handle)))
+        self._h = handle
+
+    @property
+    def steps(self):
+        return int(load().kfac_invert_plan_steps(self._h))
+
+    @property
+    def position(self):
+        return int(load().kfac_invert_plan_position(self._h))
+
+    def step_flops(self, i):
+        return float(load().kfac_invert_plan_step_flops(self._h, i))
+
+    def run(self, n_steps, stream=None):
+        _check(load().kfac_invert_plan_run(self._h, n_steps, _stream(stream)))
+
+    def reset(self):
+        _check(load().kfac_invert_plan_reset(self._h))
+
+    def close(self):
+        if self._h is not None:
+            load().kfac_invert_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _darr(values):
+    return (ctypes.c_double * max(1, len(values)))(*[float(v) for v in values])
+
+
+def _iarr(values):
+    return (ctypes.c_int64 * max(1, len(values)))(*[int(v) for v in values])
+
+
+def kfac_assign_work(bubble_start, bubble_length, step_period, chunk_times, release, deps):
+    """Greedy assignment of work chunks to pipeline bubbles (host only).
+
+    chunk_times: per work, the list of its chunk durations; release: per work; deps: per work, ids of
+    earlier works it waits for.  Returns (per work: list of (step, bubble, start)), steps_needed.
+    """
+    lib = load()
+    n_works = len(chunk_times)
+    counts = [len(c) for c in chunk_times]
+    flat = [t for c in chunk_times for t in c]
+    dep_begin, dep_ids = [0], []
+    for d in deps:
+        dep_ids += list(d)
+        dep_begin.append(len(dep_ids))
+    n = len(flat)
+    out_step, out_bubble, out_start = _iarr([0] * n), _iarr([0] * n), _darr([0.0] * n)
+    needed = ctypes.c_int64(0)
+    _check(lib.kfac_assign_work(len(bubble_start), _darr(bubble_start), _darr(bubble_length), float(step_period),
+                                n_works, _iarr(counts), _darr(flat), _darr(release), _iarr(dep_begin), _iarr(dep_ids),
+                                out_step, out_bubble, out_start, ctypes.cast(ctypes.byref(needed), _ip)))
+    res, k = [], 0
+    for c in counts:
+        res.append([(int(out_step[k + i]), int(out_bubble[k + i]), float(out_start[k + i])) for i in range(c)])
+        k += c
+    return res, int(needed.value)
+
+
+def kfac_perf_model(c_f, c_b, t_f, t_b, n_micro, t_curv, t_inv, t_prec):
+    """Closed forms of the paper's performance model; returns a dict."""
+    out = _darr([0.0] * 5)
+    _check(load().kfac_perf_model(c_f, c_b, t_f, t_b, n_micro, t_curv, t_inv, t_prec, out))
+    return {"t_pipe": out[0], "t_bubble": out[1], "t_kfac": out[2], "ratio": out[3], "t_step": out[4]}

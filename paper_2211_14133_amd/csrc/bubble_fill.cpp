@@ -1,0 +1,95 @@
+// Host-side pieces around the work items: the greedy assignment of K-FAC work to
+// pipeline bubbles (section 3.1 of the paper) and the closed forms of its
+// performance model (section 3.3).  No device code here.
+#include <cstdint>
+#include <limits>
+#include <vector>
+
+#include "../../include/kfac.h"
+
+namespace {
+constexpr int64_t MAX_PIPELINE_STEPS = 1 << 20;
+}
+
+extern "C" {
+
+kfac_status kfac_assign_work(int64_t n_bubbles, const double *bubble_start, const double *bubble_length,
+                             double step_period,
+                             int64_t n_works, const int64_t *chunk_count, const double *chunk_time,
+                             const double *release, const int64_t *dep_begin, const int64_t *dep_ids,
+                             int64_t *out_step, int64_t *out_bubble, double *out_start,
+                             int64_t *steps_needed)
+{
+    if (n_bubbles <= 0 || n_works < 0 || !bubble_start || !bubble_length || !(step_period > 0.0)) return KFAC_ERR_ARG;
+    if (n_works > 0 && (!chunk_count || !chunk_time || !release || !dep_begin || !out_step || !out_bubble || !out_start))
+        return KFAC_ERR_ARG;
+    if (steps_needed == nullptr) return KFAC_ERR_ARG;
+    double longest = 0.0, prev_end = 0.0;
+    for (int64_t b = 0; b < n_bubbles; ++b) {
+        if (!(bubble_length[b] >= 0.0) || bubble_start[b] < prev_end || bubble_start[b] + bubble_length[b] > step_period)
+            return KFAC_ERR_ARG;
+        prev_end = bubble_start[b] + bubble_length[b];
+        if (bubble_length[b] > longest) longest = bubble_length[b];
+    }
+    // cursor[s][b]: first free time of bubble b in pipeline step s, relative to that step's start
+    std::vector<std::vector<double>> cursor;
+    std::vector<double> finish((size_t)n_works, 0.0);  // absolute completion time of each work
+    int64_t chunk = 0, last_step = -1;
+    for (int64_t w = 0; w < n_works; ++w) {
+        if (chunk_count[w] < 0 || dep_begin[w + 1] < dep_begin[w]) return KFAC_ERR_ARG;
+        double ready = release[w];
+        for (int64_t k = dep_begin[w]; k < dep_begin[w + 1]; ++k) {
+            const int64_t dep = dep_ids[k];
+            if (dep < 0 || dep >= w) return KFAC_ERR_ARG;
+            if (finish[(size_t)dep] > ready) ready = finish[(size_t)dep];
+        }
+        for (int64_t c = 0; c < chunk_count[w]; ++c, ++chunk) {
+            const double dur = chunk_time[chunk];
+            if (!(dur >= 0.0)) return KFAC_ERR_ARG;
+            if (dur > longest) return KFAC_ERR_UNSUPPORTED;
+            bool placed = false;
+            int64_t s = (int64_t)(ready / step_period);
+            if (s < 0) s = 0;
+            for (; s < MAX_PIPELINE_STEPS && !placed; ++s) {
+                while ((int64_t)cursor.size() <= s) cursor.emplace_back(bubble_start, bubble_start + n_bubbles);
+                const double base = (double)s * step_period;
+                for (int64_t b = 0; b < n_bubbles; ++b) {
+                    double t = cursor[(size_t)s][(size_t)b];
+                    if (ready - base > t) t = ready - base;
+                    if (t + dur <= bubble_start[b] + bubble_length[b]) {
+                        cursor[(size_t)s][(size_t)b] = t + dur;
+                        out_step[chunk] = s;
+                        out_bubble[chunk] = b;
+                        out_start[chunk] = t;
+                        ready = base + t + dur;
+                        if (s > last_step) last_step = s;
+                        placed = true;
+                        break;
+                    }
+                }
+            }
+            if (!placed) return KFAC_ERR_UNSUPPORTED;
+        }
+        finish[(size_t)w] = ready;
+    }
+    *steps_needed = last_step + 1;
+    return KFAC_OK;
+}
+
+kfac_status kfac_perf_model(double c_f, double c_b, double t_f, double t_b, int64_t n_micro,
+                            double t_curv, double t_inv, double t_prec, double *out)
+{
+    if (out == nullptr || n_micro <= 0 || !(t_f >= 0.0) || !(t_b >= 0.0) || !(c_f >= 0.0) || !(c_b >= 0.0))
+        return KFAC_ERR_ARG;
+    const double t_pipe = c_f * t_f + c_b * t_b;
+    const double t_bubble = t_pipe - (double)n_micro * (t_f + t_b);
+    const double fill = (double)n_micro * t_curv + t_inv;
+    out[0] = t_pipe;
+    out[1] = t_bubble;
+    out[2] = fill + t_prec;
+    out[3] = t_bubble > 0.0 ? fill / t_bubble : std::numeric_limits<double>::infinity();
+    out[4] = t_pipe + t_prec;
+    return KFAC_OK;
+}
+
+}  // extern "C"

@@ -7,6 +7,8 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstring>
+#include <functional>
+#include <new>
 #include <vector>
 
 #include "../../include/kfac.h"
@@ -30,9 +32,25 @@ inline bool ws_ok(const void *ws, size_t have, size_t need)
     return ws != nullptr && have >= need && (reinterpret_cast<uintptr_t>(ws) % WS_ALIGN) == 0;
 }
 
+// One kernel launch (or a launch with its second pass) of a recorded sequence.
+struct PlanStep {
+    std::function<void(hipStream_t)> run;
+    double flops;  // model cost: multiply-adds x 2 of the launch (0 for copies)
+};
+typedef std::vector<PlanStep> PlanSteps;
+
+inline double tn_problem_flops(int M, int N, int K, int tile_mode, int mask_a, int mask_b)
+{
+    double f = 2.0 * M * N * K;
+    if (tile_mode != TILE_FULL) f *= 0.5;
+    if (mask_a != MASK_NONE || mask_b != MASK_NONE) f *= (mask_a != MASK_NONE && mask_b != MASK_NONE) ? (2.0 / 3.0) : 0.5;
+    return f;
+}
+
 // Collects problems that share the launch parameters and sends them to the
-// engine in chunks of at most TN_MAX_PROBLEMS.
+// engine in chunks of at most TN_MAX_PROBLEMS (or records the launches).
 struct TnBatch {
+    PlanSteps *rec = nullptr;
     std::vector<TnProblem> probs;
     int tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE, splits = 1;
     float alpha = 1.f, beta = 0.f;
@@ -72,6 +90,18 @@ struct TnBatch {
             lp.c.alpha = alpha;
             lp.c.beta = beta;
             lp.c.partial = partial;
+            if (rec != nullptr) {
+                double fl = 0.0;
+                for (int k = 0; k < cnt; ++k) fl += tn_problem_flops(lp.p[k].M, lp.p[k].N, lp.p[k].K, tile_mode, mask_a, mask_b);
+                const int sp = splits;
+                rec->push_back(PlanStep{[lp, tiles, sp](hipStream_t s) {
+                                            hipLaunchKernelGGL(tn_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, s, lp);
+                                            if (sp > 1)
+                                                hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / sp), dim3(TN_THREADS), 0, s, lp);
+                                        },
+                                        fl});
+                continue;
+            }
             hipLaunchKernelGGL(tn_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, stream, lp);
             if (splits > 1)
                 hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / splits), dim3(TN_THREADS), 0, stream, lp);
@@ -155,6 +185,7 @@ int build_tree(int mat, int lo, int hi, std::vector<std::vector<TriNode>> &level
 // Sends the nodes of one phase of the inversion to invert_gemm_kernel, as many per
 // launch as the kernel arguments hold.
 struct InvBatch {
+    PlanSteps *rec = nullptr;
     const std::vector<InvMat> &mats;
     std::vector<TriNode> nodes;
     int op = 0, tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE;
@@ -198,6 +229,18 @@ struct InvBatch {
             lp.c.alpha = alpha;
             lp.c.beta = beta;
             lp.op = op;
+            if (rec != nullptr) {
+                double fl = 0.0;
+                for (int k = 0; k < cnt; ++k) {
+                    const InvDims dm = inv_dims(op, lp.m[lp.n[k].mat].d, lp.n[k].a, lp.n[k].b, lp.n[k].c);
+                    fl += tn_problem_flops(dm.M, dm.N, dm.K, tile_mode, mask_a, mask_b);
+                }
+                rec->push_back(PlanStep{[lp, tiles](hipStream_t s) {
+                                            hipLaunchKernelGGL(invert_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, s, lp);
+                                        },
+                                        fl});
+                continue;
+            }
             hipLaunchKernelGGL(invert_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, stream, lp);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
@@ -346,8 +389,13 @@ size_t kfac_invert_workspace(int64_t d)
     return fits_int(d) ? invert_item_bytes(d) : 0;
 }
 
-kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, float damping,
-                                void *workspace, size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+namespace {
+
+// Validates the arguments and records the launch sequence of a batched inversion.
+kfac_status invert_record(const kfac_invert_item *items, int64_t count, float damping,
+                          void *workspace, size_t workspace_bytes, PlanSteps &steps)
 {
     if (count == 0) return KFAC_OK;
     if (items == nullptr || count < 0) return KFAC_ERR_ARG;
@@ -371,13 +419,13 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
         for (int64_t i0 = 0; i0 < count; i0 += INV_MAX_MATS) {
             const int64_t n = std::min<int64_t>(INV_MAX_MATS, count - i0);
             const size_t bytes = kfac_invert_batched_workspace(items + i0, n);
-            const kfac_status stt = kfac_invert_batched(items + i0, n, damping, base, bytes, stream);
+            const kfac_status stt = invert_record(items + i0, n, damping, base, bytes, steps);
             if (stt != KFAC_OK) return stt;
             base += bytes;
         }
         return KFAC_OK;
     }
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = nullptr;  // launches are recorded, not issued
 
     std::vector<InvMat> mats((size_t)count);
     char *cur = static_cast<char *>(workspace);
@@ -414,16 +462,20 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
             dmax = std::max(dmax, m.d);
         }
         pl.damping = damping;
-        hipLaunchKernelGGL(invert_clear_info_kernel, dim3(1), dim3(64), 0, st, pl, (int)n);
-        hipLaunchKernelGGL(invert_prepare_kernel, dim3(std::min(dmax, 512), (unsigned)n), dim3(256), 0, st, pl);
+        const int nn = (int)n, gx = std::min(dmax, 512);
+        steps.push_back(PlanStep{[pl, nn, gx](hipStream_t s) {
+                                     hipLaunchKernelGGL(invert_clear_info_kernel, dim3(1), dim3(128), 0, s, pl, nn);
+                                     hipLaunchKernelGGL(invert_prepare_kernel, dim3(gx, (unsigned)nn), dim3(256), 0, s, pl);
+                                 },
+                                 0.0});
     }
-    if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
 
     // 2. Blocked upper Cholesky M = U^T U with panel width NB, all matrices advanced together.
     //    Inside a super-panel of SUPER_PANEL block rows the factorisation is left-looking (a block
     //    row is brought up to date just before it is factored); the rest of the matrix is updated
     //    once per super-panel, so that it is read and written SUPER_PANEL times less often.
     InvBatch solve(mats), rowup(mats), trail(mats);
+    solve.rec = rowup.rec = trail.rec = &steps;
     solve.op = INV_PANEL_SOLVE;
     solve.mask_a = MASK_KEEP_K_LE;  // U_jj^-1 is upper triangular: rows k <= column
     rowup.op = INV_ROW_UPDATE;
@@ -459,9 +511,14 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
                 DiagLaunch dl;
                 std::memset(&dl, 0, sizeof(dl));
                 for (size_t i = 0; i < n; ++i) dl.it[i] = ditems[i0 + i];
-                hipLaunchKernelGGL(diag_block_kernel, dim3((unsigned)n), dim3(DIAG_THREADS), 0, st, dl);
+                const unsigned nb = (unsigned)n;
+                double fl = 0.0;
+                for (size_t i = 0; i < n; ++i) fl += 2.0 / 3.0 * dl.it[i].n * (double)dl.it[i].n * dl.it[i].n;
+                steps.push_back(PlanStep{[dl, nb](hipStream_t s) {
+                                             hipLaunchKernelGGL(diag_block_kernel, dim3(nb), dim3(DIAG_THREADS), 0, s, dl);
+                                         },
+                                         fl});
             }
-            if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
             if (solve.launch(st) != hipSuccess) return KFAC_ERR_HIP;
         }
         for (size_t mi = 0; mi < mats.size(); ++mi) {
@@ -478,6 +535,7 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
     std::vector<std::vector<TriNode>> levels;
     for (size_t i = 0; i < mats.size(); ++i) build_tree((int)i, 0, mats[i].nblk, levels);
     InvBatch s1(mats), s2(mats);
+    s1.rec = s2.rec = &steps;
     s1.op = INV_MERGE_Y;
     s1.mask_b = MASK_KEEP_K_LE;  // W22 upper triangular
     s2.op = INV_MERGE_W;
@@ -492,6 +550,7 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
 
     // 4. inv = W W^T, read through the mirror: inv[i][j] = sum_{k >= max(i,j)} S[k][i] S[k][j].
     TnBatch lu;
+    lu.rec = &steps;
     lu.tile_mode = TILE_LOWER;
     lu.mask_a = MASK_KEEP_K_GE;
     lu.mask_b = MASK_KEEP_K_GE;
@@ -499,6 +558,73 @@ kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, fl
     if (lu.launch(st) != hipSuccess) return KFAC_ERR_HIP;
     return KFAC_OK;
 }
+
+}  // namespace
+
+// Opaque handle of a recorded inversion (host memory only).
+struct kfac_invert_plan {
+    PlanSteps steps;
+    int64_t next = 0;
+};
+
+extern "C" {
+
+kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, float damping,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    PlanSteps steps;
+    const kfac_status st = invert_record(items, count, damping, workspace, workspace_bytes, steps);
+    if (st != KFAC_OK) return st;
+    if (steps.empty()) return KFAC_OK;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    for (PlanStep &p : steps) p.run(hs);
+    return hipGetLastError() == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
+}
+
+kfac_status kfac_invert_plan_create(const kfac_invert_item *items, int64_t count, float damping,
+                                    void *workspace, size_t workspace_bytes, kfac_invert_plan **plan)
+{
+    if (plan == nullptr) return KFAC_ERR_ARG;
+    *plan = nullptr;
+    kfac_invert_plan *p = new (std::nothrow) kfac_invert_plan();
+    if (p == nullptr) return KFAC_ERR_ARG;
+    const kfac_status st = invert_record(items, count, damping, workspace, workspace_bytes, p->steps);
+    if (st != KFAC_OK) {
+        delete p;
+        return st;
+    }
+    *plan = p;
+    return KFAC_OK;
+}
+
+int64_t kfac_invert_plan_steps(const kfac_invert_plan *plan) { return plan ? (int64_t)plan->steps.size() : 0; }
+
+int64_t kfac_invert_plan_position(const kfac_invert_plan *plan) { return plan ? plan->next : 0; }
+
+double kfac_invert_plan_step_flops(const kfac_invert_plan *plan, int64_t step)
+{
+    if (plan == nullptr || step < 0 || step >= (int64_t)plan->steps.size()) return -1.0;
+    return plan->steps[(size_t)step].flops;
+}
+
+kfac_status kfac_invert_plan_run(kfac_invert_plan *plan, int64_t n_steps, void *stream)
+{
+    if (plan == nullptr || n_steps < 0) return KFAC_ERR_ARG;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int64_t end = std::min<int64_t>(plan->next + n_steps, (int64_t)plan->steps.size());
+    if (end == plan->next) return KFAC_OK;
+    for (; plan->next < end; ++plan->next) plan->steps[(size_t)plan->next].run(hs);
+    return hipGetLastError() == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
+}
+
+kfac_status kfac_invert_plan_reset(kfac_invert_plan *plan)
+{
+    if (plan == nullptr) return KFAC_ERR_ARG;
+    plan->next = 0;
+    return KFAC_OK;
+}
+
+void kfac_invert_plan_destroy(kfac_invert_plan *plan) { delete plan; }
 
 kfac_status kfac_invert(const float *factor, int64_t d, int64_t ldf, float damping,
                         float *inv, int64_t ldi, int32_t *info_dev,

@@ -402,3 +402,89 @@ def test_chain_config5_bf16_attention_layer(k, oracle):
     ea, eb, ep = oracle.rel_fro(host(a), oa), oracle.rel_fro(host(b), ob), oracle.rel_fro(host(p), op)
     print("cfg 5 attention layer: A %.2e B %.2e P %.2e" % (ea, eb, ep), flush=True)
     assert ea <= BF16_FACTOR_TOL and eb <= BF16_FACTOR_TOL and ep <= PRECOND_TOL
+
+
+# ------------------------------------------------ chunked inversion (plan API)
+
+def test_invert_plan_equals_batched_and_can_be_cut_anywhere(k, oracle):
+    ds = [64, 300, 513, 1024]
+    fs = [oracle.curvature(synth.activations(2, 2, i, 0, 2 * d + 8, d)).astype(np.float32) for i, d in enumerate(ds)]
+    fd = [dev(f) for f in fs]
+    ref = [torch.empty(d, d, device="cuda") for d in ds]
+    infos = k.kfac_invert_batched(fd, 1e-3, ref)
+    assert np.all(host(infos) == 0)
+    out = [torch.full((d, d), 5.0, device="cuda") for d in ds]
+    plan = k.InvertPlan(fd, 1e-3, out)
+    n = plan.steps
+    assert n > 10 and plan.position == 0
+    flops = [plan.step_flops(i) for i in range(n)]
+    assert all(f >= 0 for f in flops) and plan.step_flops(n) == -1.0
+    # model cost is in the right ball park: d^3 per matrix (triangular work counted at its useful share)
+    assert 0.5 * sum(d ** 3 for d in ds) <= sum(flops) <= 3.0 * sum(d ** 3 for d in ds)
+    side = torch.cuda.Stream()
+    rng = np.random.default_rng(0)
+    while plan.position < n:
+        before = plan.position
+        # the inverse is not touched before the last launches
+        if before < n - 2:
+            assert all(bool(torch.all(o == 5.0)) for o in out)
+        plan.run(int(rng.integers(1, 7)))
+        torch.cuda.synchronize()
+        # unrelated work on another stream between the pieces
+        with torch.cuda.stream(side):
+            torch.zeros(1 << 20, device="cuda").add_(1.0)
+        side.synchronize()
+        assert plan.position > before
+    assert plan.position == n
+    for o, r in zip(out, ref):
+        assert torch.equal(o, r)  # bitwise: the same launches in the same order
+    assert np.all(host(plan.infos) == 0)
+    # a plan can be run again after a reset (next refresh)
+    for o in out:
+        o.fill_(0.0)
+    plan.reset()
+    plan.run(n)
+    torch.cuda.synchronize()
+    for o, r in zip(out, ref):
+        assert torch.equal(o, r)
+    plan.close()
+
+
+# ----------------------------------------- K-block-diagonal factors (appendix)
+
+def test_block_diagonal_factors(k, oracle):
+    # appendix A.2: a factor of size K*d is replaced by K independent blocks of size d; every step of the
+    # path then runs on the blocks, addressed inside the big arrays through leading dimensions
+    n, d_in, d_out, kb = 600, 384, 256, 2
+    x = synth.activations(2, 3, 0, 0, n, d_in)
+    e = synth.errors(2, 3, 0, 0, n, d_out, scale=1.0)
+    g = synth.weight_gradient([e], [x])
+    xd, ed, gd = dev(x), dev(e), dev(g)
+    a = torch.zeros(d_in, d_in, device="cuda")
+    b = torch.zeros(d_out, d_out, device="cuda")
+    bi, bo = d_in // kb, d_out // kb
+    xs = [xd[:, i * bi:(i + 1) * bi] for i in range(kb)] + [ed[:, i * bo:(i + 1) * bo] for i in range(kb)]
+    fblocks = [a[i * bi:(i + 1) * bi, i * bi:(i + 1) * bi] for i in range(kb)] + \
+              [b[i * bo:(i + 1) * bo, i * bo:(i + 1) * bo] for i in range(kb)]
+    k.kfac_curvature_grouped(xs, fblocks, 1.0 / n, 0.0)
+    ai, binv = torch.zeros_like(a), torch.zeros_like(b)
+    iblocks = [ai[i * bi:(i + 1) * bi, i * bi:(i + 1) * bi] for i in range(kb)] + \
+              [binv[i * bo:(i + 1) * bo, i * bo:(i + 1) * bo] for i in range(kb)]
+    infos = k.kfac_invert_batched(fblocks, 1e-2, iblocks)
+    assert np.all(host(infos) == 0)
+    p = torch.empty_like(gd)
+    items = [(io, ii) for io in range(kb) for ii in range(kb)]
+    k.kfac_precondition_grouped([iblocks[kb + io] for io, ii in items], [iblocks[ii] for io, ii in items],
+                                [gd[io * bo:(io + 1) * bo, ii * bi:(ii + 1) * bi] for io, ii in items],
+                                [p[io * bo:(io + 1) * bo, ii * bi:(ii + 1) * bi] for io, ii in items])
+    # oracle: the dense factors with the off-diagonal blocks set to zero
+    oa, ob = oracle.curvature(x), oracle.curvature(e)
+    ma, mb = np.zeros_like(oa), np.zeros_like(ob)
+    for i in range(kb):
+        ma[i * bi:(i + 1) * bi, i * bi:(i + 1) * bi] = oa[i * bi:(i + 1) * bi, i * bi:(i + 1) * bi]
+        mb[i * bo:(i + 1) * bo, i * bo:(i + 1) * bo] = ob[i * bo:(i + 1) * bo, i * bo:(i + 1) * bo]
+    assert oracle.rel_fro(host(a), ma) <= FACTOR_TOL and oracle.rel_fro(host(b), mb) <= FACTOR_TOL
+    oai, _ = oracle.invert(ma, 1e-2)
+    obi, _ = oracle.invert(mb, 1e-2)
+    assert oracle.rel_fro(host(ai), oai) <= 1e-4 and oracle.rel_fro(host(binv), obi) <= 1e-4
+    assert oracle.rel_fro(host(p), oracle.precondition(obi, g, oai)) <= PRECOND_TOL
