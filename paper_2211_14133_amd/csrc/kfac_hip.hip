@@ -128,10 +128,15 @@ inline int choose_splits(int64_t tiles, int64_t K)
 struct CurvPlan {
     int splits;
     int64_t tiles;  // output tiles of all items
+    size_t pack;    // bytes of the repacked bf16 inputs (bf16 only), in front of the partial tiles
     size_t ws;
 };
 
-bool curvature_plan(const kfac_curvature_item *items, int64_t count, CurvPlan &pl)
+inline int pack_groups(int64_t n) { return (int)align_up((size_t)((n + 7) / 8), BF_SLAB_GROUPS); }
+inline int pack_cols(int64_t d) { return (int)align_up((size_t)d, BM); }
+inline size_t pack_bytes(int64_t n, int64_t d) { return align_up((size_t)pack_groups(n) * pack_cols(d) * 16, WS_ALIGN); }
+
+bool curvature_plan(const kfac_curvature_item *items, int64_t count, kfac_dtype dtype, CurvPlan &pl)
 {
     int64_t tiles = 0, kmin = INT64_MAX;
     for (int64_t i = 0; i < count; ++i) {
@@ -143,7 +148,10 @@ bool curvature_plan(const kfac_curvature_item *items, int64_t count, CurvPlan &p
     const int64_t launches = (count + SYRK_MAX_PROBLEMS - 1) / SYRK_MAX_PROBLEMS;
     pl.splits = choose_splits(std::max<int64_t>(1, tiles / std::max<int64_t>(1, launches)), kmin);
     pl.tiles = tiles;
-    pl.ws = pl.splits > 1 ? align_up((size_t)tiles * pl.splits * BM * BN * sizeof(float), WS_ALIGN) : 0;
+    pl.pack = 0;
+    if (dtype == KFAC_BF16)
+        for (int64_t i = 0; i < count; ++i) pl.pack += pack_bytes(items[i].n_tokens, items[i].d);
+    pl.ws = pl.pack + (pl.splits > 1 ? align_up((size_t)tiles * pl.splits * BM * BN * sizeof(float), WS_ALIGN) : 0);
     return true;
 }
 
@@ -274,10 +282,9 @@ int kfac_version(void) { return 100; }
 
 size_t kfac_curvature_grouped_workspace(const kfac_curvature_item *items, int64_t count, kfac_dtype dtype)
 {
-    (void)dtype;
     if (items == nullptr || count <= 0) return 0;
     CurvPlan pl;
-    if (!curvature_plan(items, count, pl)) return 0;
+    if (!curvature_plan(items, count, dtype, pl)) return 0;
     return pl.ws;
 }
 
@@ -296,18 +303,21 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
             return KFAC_ERR_ARG;
     }
     CurvPlan pl;
-    if (!curvature_plan(items, count, pl)) return KFAC_ERR_ARG;
+    if (!curvature_plan(items, count, dtype, pl)) return KFAC_ERR_ARG;
     if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;
 
     // One launch per SYRK_MAX_PROBLEMS items (a BERT-Large stage has 72 factors:
     // one launch per micro-batch); each launch gets its own slice of the partial buffer.
     hipStream_t st = static_cast<hipStream_t>(stream);
-    float *part = static_cast<float *>(workspace);
+    char *pack = static_cast<char *>(workspace);
+    float *part = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.pack);
     for (int64_t done = 0; done < count;) {
         const int64_t n = std::min<int64_t>(SYRK_MAX_PROBLEMS, count - done);
         SyrkLaunch lp;
         std::memset(&lp, 0, sizeof(lp));
-        int tiles = 0;
+        PackLaunch pk;
+        if (dtype == KFAC_BF16) std::memset(&pk, 0, sizeof(pk));
+        int tiles = 0, gmax = 0, cmax = 0;
         for (int64_t i = 0; i < n; ++i) {
             const kfac_curvature_item &it = items[done + i];
             SyrkProblem &q = lp.p[i];
@@ -317,6 +327,23 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
             q.d = (int)it.d;
             q.ldx = (int)it.ldx;
             q.ldf = (int)it.ldf;
+            if (dtype == KFAC_BF16) {
+                // the kernel reads the repacked copy: [groups of 8 tokens][padded columns][8]
+                PackItem &pi = pk.it[i];
+                pi.x = static_cast<const unsigned short *>(it.x);
+                pi.dst = reinterpret_cast<unsigned short *>(pack);
+                pi.n = q.n;
+                pi.d = q.d;
+                pi.ldx = q.ldx;
+                pi.dp = pack_cols(it.d);
+                pi.gp = pack_groups(it.n_tokens);
+                q.x = pack;
+                q.n = pi.gp * BF_KG;
+                q.ldx = pi.dp;
+                pack += pack_bytes(it.n_tokens, it.d);
+                gmax = std::max(gmax, pi.gp);
+                cmax = std::max(cmax, pi.dp);
+            }
             q.tile_begin = tiles;
             tiles += tn_tiles(q.d, q.d, TILE_LOWER) * pl.splits;
         }
@@ -328,14 +355,15 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         lp.c.alpha = alpha;
         lp.c.beta = beta;
         lp.c.partial = part;
-        lp.c.in_bf16 = (dtype == KFAC_BF16) ? 1 : 0;
         if (dtype == KFAC_BF16) {
-            SyrkLaunchBf16 lb;
-            static_assert(sizeof(lb) == sizeof(lp), "both curvature launch types share one layout");
+            SyrkLaunchPacked lb;
+            static_assert(sizeof(lb) == sizeof(lp), "the curvature launch types share one layout");
+            lp.c.slab_align = 2;  // slabs of the engine are 16 tokens, the bf16 loop steps by 32
             std::memcpy(&lb, &lp, sizeof(lp));
-            hipLaunchKernelGGL(curvature_syrk_bf16_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lb);
+            hipLaunchKernelGGL(pack_bf16_kernel, dim3((cmax + 255) / 256, gmax, (unsigned)n), dim3(256), 0, st, pk);
+            hipLaunchKernelGGL(curvature_syrk_bf16mfma_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lb);
             if (pl.splits > 1)
-                hipLaunchKernelGGL(curvature_reduce_bf16_kernel, dim3(tiles / pl.splits), dim3(TN_THREADS), 0, st, lb);
+                hipLaunchKernelGGL(curvature_reduce_packed_kernel, dim3(tiles / pl.splits), dim3(TN_THREADS), 0, st, lb);
         } else {
             hipLaunchKernelGGL(curvature_syrk_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lp);
             if (pl.splits > 1)

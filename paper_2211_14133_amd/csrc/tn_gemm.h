@@ -56,12 +56,12 @@ struct TnCommon {
     float alpha;
     float beta;
     float *partial;  // [total logical tiles][BM * BN]
-    int in_bf16;     // operands are bfloat16 (curvature launches only); products are exact in fp32
+    int slab_align;  // K ranges of split tiles are multiples of this many slabs (0 or 1: any)
 };
 
 // General launch: up to TN_MAX_PROBLEMS arbitrary problems.
 struct TnLaunch {
-    static constexpr bool kAllowBf16 = false;
+    static constexpr bool kPackedBf16 = false;
     static constexpr bool kAllowMask = true;
     TnProblem p[TN_MAX_PROBLEMS];
     TnCommon c;
@@ -75,16 +75,17 @@ struct TnLaunch {
 constexpr int SYRK_MAX_PROBLEMS = 80;
 
 struct SyrkProblem {
-    const void *x;   // n x d, ldx (float32 or bfloat16)
+    const void *x;   // float32 [n, d] with ldx, or the packed bfloat16 copy (then n, ldx are its padded sizes)
     float *factor;   // d x d, ldf
     int n, d, ldx, ldf;
     int tile_begin;
     int pad_;
 };
 
-template <bool BF16IN>
+// PACKED false: float32 x; true: bfloat16 x repacked for the bf16 MFMA (see pack_bf16_kernel)
+template <bool PACKED>
 struct SyrkLaunchT {
-    static constexpr bool kAllowBf16 = BF16IN;
+    static constexpr bool kPackedBf16 = PACKED;
     static constexpr bool kAllowMask = false;
     SyrkProblem p[SYRK_MAX_PROBLEMS];
     TnCommon c;
@@ -100,8 +101,8 @@ struct SyrkLaunchT {
         return r;
     }
 };
-typedef SyrkLaunchT<false> SyrkLaunch;      // float32 activations / errors
-typedef SyrkLaunchT<true> SyrkLaunchBf16;   // bfloat16 activations / errors
+typedef SyrkLaunchT<false> SyrkLaunch;       // float32 activations / errors
+typedef SyrkLaunchT<true> SyrkLaunchPacked;  // bfloat16 in k-interleaved layout, bf16 MFMA
 
 // Inversion launch: the problems of one phase of the blocked inversion are
 // described by (matrix, up to three block indices); pointers and sizes follow
@@ -155,7 +156,7 @@ __host__ __device__ inline InvDims inv_dims(int op, int d, int a, int b, int c)
 }
 
 struct InvLaunch {
-    static constexpr bool kAllowBf16 = false;
+    static constexpr bool kPackedBf16 = false;
     static constexpr bool kAllowMask = true;
     InvMatDesc m[INV_MAX_MATS];
     InvNode n[INV_MAX_NODES];
@@ -309,7 +310,8 @@ __device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
     if (lp.mask_b == MASK_KEEP_K_LE) ke = min(ke, tl.n0 + BN);
     kb = (kb / BK) * BK;
     const int nslab = ke > kb ? (ke - kb + BK - 1) / BK : 0;
-    const int per = (nslab + lp.splits - 1) / lp.splits;
+    int per = (nslab + lp.splits - 1) / lp.splits;
+    if (lp.slab_align > 1) per = (per + lp.slab_align - 1) / lp.slab_align * lp.slab_align;
     tl.kbase = kb;
     tl.kt0 = min(nslab, tl.split * per);
     tl.kt1 = min(nslab, tl.kt0 + per);
@@ -321,45 +323,23 @@ __device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
 // the load never depends on a branch; tn_fix4 zeroes what must not count after
 // the MFMA work of the current slab has been issued (the load latency is then
 // hidden behind it).
-// Staging type: what a thread keeps in registers between the global load and
-// the LDS store (four consecutive elements of an operand row).
-template <bool BF16> struct TnStage { typedef float4 type; };
-template <> struct TnStage<true> { typedef uint2 type; };  // four bfloat16
-
-template <bool FAST, bool BF16>
-__device__ inline typename TnStage<BF16>::type tn_load4(const void *Pv, int k, int c, int ld, int K, int W)
+template <bool FAST>
+__device__ inline float4 tn_load4(const float *P, int k, int c, int ld, int K, int W)
 {
     const int kc = min(k, K - 1);
-    if constexpr (BF16) {
-        const unsigned short *row = static_cast<const unsigned short *>(Pv) + (size_t)kc * (size_t)ld;
-        if (FAST) return *reinterpret_cast<const uint2 *>(row + c);
-        const unsigned e0 = row[min(c + 0, W - 1)], e1 = row[min(c + 1, W - 1)];
-        const unsigned e2 = row[min(c + 2, W - 1)], e3 = row[min(c + 3, W - 1)];
-        return make_uint2(e0 | (e1 << 16), e2 | (e3 << 16));
-    } else {
-        const float *row = static_cast<const float *>(Pv) + (size_t)kc * (size_t)ld;
-        if (FAST) return *reinterpret_cast<const float4 *>(row + c);
-        float4 v;
-        v.x = row[min(c + 0, W - 1)];
-        v.y = row[min(c + 1, W - 1)];
-        v.z = row[min(c + 2, W - 1)];
-        v.w = row[min(c + 3, W - 1)];
-        return v;
-    }
+    const float *row = P + (size_t)kc * (size_t)ld;
+    if (FAST) return *reinterpret_cast<const float4 *>(row + c);
+    float4 v;
+    v.x = row[min(c + 0, W - 1)];
+    v.y = row[min(c + 1, W - 1)];
+    v.z = row[min(c + 2, W - 1)];
+    v.w = row[min(c + 3, W - 1)];
+    return v;
 }
 
-__device__ inline float4 tn_widen(float4 v) { return v; }
-__device__ inline float4 tn_widen(uint2 v)
+template <bool FAST, bool MASKED>
+__device__ inline float4 tn_fix4(float4 v, int k, int c, int K, int W, int mask)
 {
-    // bfloat16 -> float32 is a 16-bit shift (exact)
-    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
-                       __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
-}
-
-template <bool FAST, bool MASKED, class ST>
-__device__ inline float4 tn_fix4(ST raw, int k, int c, int K, int W, int mask)
-{
-    float4 v = tn_widen(raw);
     // branch-free on purpose: the K loop must stay one basic block
     const bool kz = k >= K;
     bool z0 = kz, z1 = kz, z2 = kz, z3 = kz;
@@ -411,15 +391,15 @@ constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_W
 // which every wave finished reading before the previous barrier.  Loads past
 // the end of the K range are clamped to valid rows and their data is never
 // used, which keeps the loop body free of branches.
-template <bool FAST, bool MASKED, bool BF16>
+template <bool FAST, bool MASKED>
 __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, const TnTile &tl,
                                    float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                    floatx16 (&sum)[2][2])
 {
     const int tid = threadIdx.x;
     const int M = pr.M, N = pr.N, K = pr.K;
-    const void *__restrict__ A = pr.A;
-    const void *__restrict__ B = pr.B;
+    const float *__restrict__ A = pr.A;
+    const float *__restrict__ B = pr.B;
     const int lda = pr.lda, ldb = pr.ldb;
     const int mask_a = lp.mask_a, mask_b = lp.mask_b;
 
@@ -441,24 +421,24 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
     const int nslab = tl.kt1 - tl.kt0;
     if (nslab <= 0) return;
 
-    typename TnStage<BF16>::type ra[2][2], rb[2][2];  // two sets of staging registers (slabs alternate)
+    float4 ra[2][2], rb[2][2];  // two sets of staging registers (slabs alternate)
     float2 fa[2][4], fb[2][4];  // MFMA operands: [half of the slab][k step pair]
     int kw = tl.kbase + tl.kt0 * BK + lrow;  // K row (of this thread) of the next slab to go to LDS
 
 #define TN_G(set, ahead)                                                        \
     do {                                                                        \
         const int kg_ = kw + (ahead) * BK;                                      \
-        ra[set][0] = tn_load4<FAST, BF16>(A, kg_, ca, lda, K, M);                     \
-        ra[set][1] = tn_load4<FAST, BF16>(A, kg_ + 8, ca, lda, K, M);                 \
-        rb[set][0] = tn_load4<FAST, BF16>(B, kg_, cb, ldb, K, N);                     \
-        rb[set][1] = tn_load4<FAST, BF16>(B, kg_ + 8, cb, ldb, K, N);                 \
+        ra[set][0] = tn_load4<FAST>(A, kg_, ca, lda, K, M);                     \
+        ra[set][1] = tn_load4<FAST>(A, kg_ + 8, ca, lda, K, M);                 \
+        rb[set][0] = tn_load4<FAST>(B, kg_, cb, ldb, K, N);                     \
+        rb[set][1] = tn_load4<FAST>(B, kg_ + 8, cb, ldb, K, N);                 \
     } while (0)
 #define TN_W(st, set)                                                                                                  \
     do {                                                                                                               \
-        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST, MASKED, typename TnStage<BF16>::type>(ra[set][0], kw, ca, K, M, mask_a);     \
-        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED, typename TnStage<BF16>::type>(ra[set][1], kw + 8, ca, K, M, mask_a); \
-        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST, MASKED, typename TnStage<BF16>::type>(rb[set][0], kw, cb, K, N, mask_b);     \
-        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED, typename TnStage<BF16>::type>(rb[set][1], kw + 8, cb, K, N, mask_b); \
+        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(ra[set][0], kw, ca, K, M, mask_a);     \
+        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(ra[set][1], kw + 8, ca, K, M, mask_a); \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(rb[set][0], kw, cb, K, N, mask_b);     \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(rb[set][1], kw + 8, cb, K, N, mask_b); \
         kw += BK;                                                                                                      \
     } while (0)
     // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2*step + lh
@@ -697,6 +677,148 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
         for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
 }
 
+// ---------------------------------------------------------------------------
+// bfloat16 operands on the bf16 MFMA (v_mfma_f32_32x32x16_bf16).
+//
+// That instruction wants, per lane, eight consecutive K values of one column
+// (lane (i, h) holds k = 8h .. 8h+7 of column i).  The activations are stored
+// [tokens, d], so those eight values are d elements apart.  A small pre-pass
+// (pack_bf16_kernel) rewrites x as P[k / 8][column][k % 8], zero-padded to a
+// multiple of 32 tokens and 128 columns: the eight values are then 16 contiguous
+// bytes, a wave fetches 64 columns of a k-group with one global_load_lds_dwordx4
+// and reads its MFMA operands from LDS with ds_read_b128, all conflict-free and
+// without a transpose.  Slab = 32 tokens = 4 k-groups = 8 KB per operand, the
+// same LDS footprint as the fp32 loop.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int BF_KG = 8;           // K values per packed group
+constexpr int BF_SLAB_GROUPS = 4;  // groups per slab (32 tokens)
+
+struct PackItem {
+    const unsigned short *x;  // [n, d] bfloat16, ldx
+    unsigned short *dst;      // [gp][dp][8]
+    int n, d, ldx, dp, gp, pad_;
+};
+constexpr int PACK_MAX_ITEMS = 80;
+struct PackLaunch {
+    PackItem it[PACK_MAX_ITEMS];
+};
+
+__global__ __launch_bounds__(256) void pack_bf16_kernel(const PackLaunch pl)
+{
+    const PackItem &it = pl.it[blockIdx.z];
+    const int c = blockIdx.x * 256 + threadIdx.x, g = blockIdx.y;
+    if (c >= it.dp || g >= it.gp) return;
+    unsigned v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int k = g * 8 + e;
+        v[e] = (k < it.n && c < it.d) ? it.x[(size_t)k * it.ldx + c] : 0u;
+    }
+    uint4 o;
+    o.x = v[0] | (v[1] << 16);
+    o.y = v[2] | (v[3] << 16);
+    o.z = v[4] | (v[5] << 16);
+    o.w = v[6] | (v[7] << 16);
+    *reinterpret_cast<uint4 *>(it.dst + ((size_t)g * it.dp + c) * 8) = o;
+}
+
+// K loop on packed bf16 operands.  pr.A = pr.B = packed array, pr.lda = padded
+// column count, pr.K = padded token count.  Same pipeline as the direct fp32
+// loop with the operand registers double-buffered per slab (a single fp32
+// accumulation level: the tolerance of the bfloat16 variant does not need two):
+//   iteration s:  D(s+3)  R(s+1)  M(s)  wait D(s+2)  barrier
+__device__ inline void tn_mainloop_bf16_packed(const TnProblem &pr, const TnTile &tl,
+                                               float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
+                                               floatx16 (&sum)[2][2])
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int li = lane & 31, lh = lane >> 5;
+    const size_t row_bytes = (size_t)pr.lda * 16;  // one k-group of all columns
+    const int groups = pr.K / BF_KG;
+    const char *ga = reinterpret_cast<const char *>(pr.A) + ((size_t)tl.m0 + lane) * 16;
+    const char *gb = reinterpret_cast<const char *>(pr.B) + ((size_t)tl.n0 + lane) * 16;
+    const char *la = reinterpret_cast<const char *>(&As[0][0][0]);
+    const char *lb = reinterpret_cast<const char *>(&Bs[0][0][0]);
+    constexpr int STAGE_BYTES = BK * BM * 4;  // 8 KB
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int niter = (tl.kt1 - tl.kt0) / 2;  // slabs of 32 tokens (K ranges are multiples of 32)
+    if (niter <= 0) return;
+    int gd = (tl.kbase + tl.kt0 * BK) / BF_KG;  // first k-group of the next slab to request
+    uint4 fa[2][2][2], fb[2][2][2];              // [register set][k step][block]
+
+    // wave w fetches k-group gd + w: columns 0..63 and 64..127 of the tile, for both operands
+#define BF_D(st)                                                                                            \
+    do {                                                                                                    \
+        const size_t off_ = (size_t)min(gd + wave, groups - 1) * row_bytes;                                 \
+        const int ld_ = (st) * STAGE_BYTES + wave * 2048;                                                   \
+        tn_dma16(reinterpret_cast<const float *>(ga + off_), reinterpret_cast<const float *>(la + ld_));    \
+        tn_dma16(reinterpret_cast<const float *>(ga + off_ + 1024), reinterpret_cast<const float *>(la + ld_ + 1024)); \
+        tn_dma16(reinterpret_cast<const float *>(gb + off_), reinterpret_cast<const float *>(lb + ld_));    \
+        tn_dma16(reinterpret_cast<const float *>(gb + off_ + 1024), reinterpret_cast<const float *>(lb + ld_ + 1024)); \
+        gd += BF_SLAB_GROUPS;                                                                               \
+    } while (0)
+    // lane (li, lh) feeds columns 2*li, 2*li+1 of the wave tile with k-group 2t + lh
+#define BF_R(st, set)                                                                                       \
+    do {                                                                                                    \
+        _Pragma("unroll") for (int t = 0; t < 2; ++t) {                                                     \
+            const int u_ = (st) * STAGE_BYTES + ((2 * t + lh) * 128 + 2 * li) * 16;                         \
+            fa[set][t][0] = *reinterpret_cast<const uint4 *>(la + u_ + wm * 16);                            \
+            fa[set][t][1] = *reinterpret_cast<const uint4 *>(la + u_ + wm * 16 + 16);                       \
+            fb[set][t][0] = *reinterpret_cast<const uint4 *>(lb + u_ + wn * 16);                            \
+            fb[set][t][1] = *reinterpret_cast<const uint4 *>(lb + u_ + wn * 16 + 16);                       \
+        }                                                                                                   \
+    } while (0)
+#define BF_M(set)                                                                                           \
+    do {                                                                                                    \
+        _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                       \
+            _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                                \
+                _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                            \
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                  \
+                        __builtin_bit_cast(bf16x8, fa[set][t][bi]), __builtin_bit_cast(bf16x8, fb[set][t][bj]), \
+                        acc[bi][bj], 0, 0, 0);                                                              \
+    } while (0)
+#define BF_ITER(s_, cur, nxt)                                                                               \
+    do {                                                                                                    \
+        BF_D(((s_) + 3) & 3);                                                                               \
+        BF_R(((s_) + 1) & 3, nxt);                                                                          \
+        BF_M(cur);                                                                                          \
+        __builtin_amdgcn_s_waitcnt(0x0F74); /* vmcnt(4): all but the newest slab has landed */              \
+        __syncthreads();                                                                                    \
+    } while (0)
+
+    BF_D(0);
+    BF_D(1);
+    BF_D(2);
+    __builtin_amdgcn_s_waitcnt(0x0F74);
+    __syncthreads();
+    BF_R(0, 0);
+    int s = 0;
+    for (; s + 1 < niter; s += 2) {
+        BF_ITER(s, 0, 1);
+        BF_ITER(s + 1, 1, 0);
+    }
+    if (s < niter) BF_ITER(s, 0, 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+#undef BF_D
+#undef BF_R
+#undef BF_M
+#undef BF_ITER
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
+}
+
 template <class L>
 __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN])
 {
@@ -706,11 +828,9 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
     const TnTile tl = tn_locate(ll, tn_logical_tile(blockIdx.x, gridDim.x), pr);
     const int M = pr.M, N = pr.N;
 
-    // vector loads need 16-byte (fp32) / 8-byte (bf16) aligned rows
-    const bool bf16 = L::kAllowBf16;  // the bfloat16 curvature launch has a kernel of its own
-    const uintptr_t amask = bf16 ? 7 : 15;
-    const bool fast_a = (tl.m0 + BM <= M) && ((pr.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.A) & amask) == 0);
-    const bool fast_b = (tl.n0 + BN <= N) && ((pr.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.B) & amask) == 0);
+    // vector loads need 16-byte aligned rows
+    const bool fast_a = (tl.m0 + BM <= M) && ((pr.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.A) & 15) == 0);
+    const bool fast_b = (tl.n0 + BN <= N) && ((pr.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.B) & 15) == 0);
 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -726,14 +846,9 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
 
     const bool masked = L::kAllowMask && (lp.mask_a | lp.mask_b) != 0;
     bool done = false;
-    if constexpr (L::kAllowBf16) {
-        if (bf16) {
-            if (fast_a && fast_b)
-                tn_mainloop<true, false, true>(lp, pr, tl, As, Bs, sum);
-            else
-                tn_mainloop<false, false, true>(lp, pr, tl, As, Bs, sum);
-            done = true;
-        }
+    if constexpr (L::kPackedBf16) {
+        tn_mainloop_bf16_packed(pr, tl, As, Bs, sum);
+        done = true;
     }
     if (!done && fast_a && fast_b && !masked && (pr.K % BK) == 0) {
         tn_mainloop_direct(pr, tl, As, Bs, sum);
@@ -743,17 +858,17 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
         if constexpr (L::kAllowMask) {
             if (masked) {
                 if (fast_a && fast_b)
-                    tn_mainloop<true, true, false>(lp, pr, tl, As, Bs, sum);
+                    tn_mainloop<true, true>(lp, pr, tl, As, Bs, sum);
                 else
-                    tn_mainloop<false, true, false>(lp, pr, tl, As, Bs, sum);
+                    tn_mainloop<false, true>(lp, pr, tl, As, Bs, sum);
                 done = true;
             }
         }
         if (!done) {
             if (fast_a && fast_b)
-                tn_mainloop<true, false, false>(lp, pr, tl, As, Bs, sum);
+                tn_mainloop<true, false>(lp, pr, tl, As, Bs, sum);
             else
-                tn_mainloop<false, false, false>(lp, pr, tl, As, Bs, sum);
+                tn_mainloop<false, false>(lp, pr, tl, As, Bs, sum);
         }
     }
 
@@ -906,15 +1021,15 @@ __global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_kernel(const Syr
 
 __global__ __launch_bounds__(TN_THREADS) void curvature_reduce_kernel(const SyrkLaunch lp) { tn_reduce_body(lp); }
 
-// Same for bfloat16 inputs: widened exactly to float32 on the way to LDS, fp32 MFMA and accumulation.
-__global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_bf16_kernel(const SyrkLaunchBf16 lp)
+// bfloat16 inputs repacked by pack_bf16_kernel, multiplied by the bf16 MFMA, accumulated in fp32.
+__global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_bf16mfma_kernel(const SyrkLaunchPacked lp)
 {
     __shared__ float As[TN_LDS_STAGES][BK][BM];
     __shared__ float Bs[TN_LDS_STAGES][BK][BN];
     tn_tile_body(lp, As, Bs);
 }
 
-__global__ __launch_bounds__(TN_THREADS) void curvature_reduce_bf16_kernel(const SyrkLaunchBf16 lp) { tn_reduce_body(lp); }
+__global__ __launch_bounds__(TN_THREADS) void curvature_reduce_packed_kernel(const SyrkLaunchPacked lp) { tn_reduce_body(lp); }
 
 // The products of the blocked inversion (panel solves, row / trailing updates, merges).
 __global__ __launch_bounds__(TN_THREADS, 2) void invert_gemm_kernel(const InvLaunch lp)
