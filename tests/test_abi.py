@@ -100,3 +100,22 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2211_14133_amd" not in text and "kfac.h" not in text, f
+
+
+def test_plan_and_host_functions_reject_bad_arguments():
+    lib = binding.load()
+    handle = ctypes.c_void_p()
+    assert lib.kfac_invert_plan_create(None, 1, 0.1, None, 0, ctypes.byref(handle)) == 1
+    assert handle.value is None
+    assert lib.kfac_invert_plan_create(None, 0, 0.1, None, 0, None) == 1
+    # an empty plan is valid and has no steps
+    assert lib.kfac_invert_plan_create(None, 0, 0.1, None, 0, ctypes.byref(handle)) == 0
+    assert lib.kfac_invert_plan_steps(handle) == 0 and lib.kfac_invert_plan_position(handle) == 0
+    assert lib.kfac_invert_plan_run(handle, 5, None) == 0
+    assert lib.kfac_invert_plan_step_flops(handle, 0) == -1.0
+    assert lib.kfac_invert_plan_reset(handle) == 0
+    lib.kfac_invert_plan_destroy(handle)
+    assert lib.kfac_invert_plan_steps(None) == 0
+    assert lib.kfac_invert_plan_run(None, 1, None) == 1
+    assert lib.kfac_perf_model(1.0, 1.0, 1.0, 1.0, 0, 1.0, 1.0, 1.0, None) == 1
+    assert lib.kfac_assign_work(0, None, None, 1.0, 0, None, None, None, None, None, None, None, None, None) == 1

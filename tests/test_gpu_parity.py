@@ -488,3 +488,44 @@ def test_block_diagonal_factors(k, oracle):
     obi, _ = oracle.invert(mb, 1e-2)
     assert oracle.rel_fro(host(ai), oai) <= 1e-4 and oracle.rel_fro(host(binv), obi) <= 1e-4
     assert oracle.rel_fro(host(p), oracle.precondition(obi, g, oai)) <= PRECOND_TOL
+
+
+def test_inversion_and_precondition_are_deterministic(k, oracle):
+    d = 640
+    a = dev(oracle.curvature(synth.activations(2, 4, 0, 0, 1500, d, gelu=True)).astype(np.float32))
+    g = dev(np.random.default_rng(3).standard_normal((d, d)).astype(np.float32))
+    first_inv = first_p = None
+    for _ in range(3):
+        inv = torch.empty(d, d, device="cuda")
+        k.kfac_invert(a, 1e-3, inv)
+        p = torch.empty(d, d, device="cuda")
+        k.kfac_precondition(inv, inv, g, p)
+        if first_inv is None:
+            first_inv, first_p = inv.clone(), p.clone()
+        assert torch.equal(inv, first_inv) and torch.equal(p, first_p)
+
+
+def test_chain_config5_largest_factor(k, oracle):
+    # the largest and worst conditioned factor of all workloads: the second feed-forward linear of the stress
+    # block, A is 8192 x 8192 from 8192 bf16 GELU tokens (smallest eigenvalue about the damping)
+    c = synth.CONFIGS[5]
+    n, d_in, d_out = c["tokens"], 8192, 2048
+    print("generating", flush=True)
+    x = synth.activations(5, 0, 5, 0, n, d_in, gelu=True, bf16=True)
+    e = synth.errors(5, 0, 5, 0, n, d_out, bf16=True)
+    g = synth.weight_gradient([e], [x])
+    a = torch.empty(d_in, d_in, device="cuda")
+    b = torch.empty(d_out, d_out, device="cuda")
+    k.kfac_curvature_grouped([dev(x).to(torch.bfloat16), dev(e).to(torch.bfloat16)], [a, b], 1.0 / n, 0.0)
+    ai, bi = torch.empty_like(a), torch.empty_like(b)
+    infos = k.kfac_invert_batched([a, b], synth.DAMPING, [ai, bi])
+    p = torch.empty(d_out, d_in, device="cuda")
+    k.kfac_precondition(bi, ai, dev(g), p)
+    torch.cuda.synchronize()
+    assert host(infos).tolist() == [0, 0]
+    print("oracle chain (8192-dimensional inverse in fp64)", flush=True)
+    oa, ob, oai, obi, op = oracle.kfac_chain([x], [e], g, synth.DAMPING)
+    ea, eb = oracle.rel_fro(host(a), oa), oracle.rel_fro(host(b), ob)
+    eai, ep = oracle.rel_fro(host(ai), oai), oracle.rel_fro(host(p), op)
+    print("cfg 5 ffn2: A %.2e B %.2e A^-1 %.2e P %.2e" % (ea, eb, eai, ep), flush=True)
+    assert ea <= BF16_FACTOR_TOL and eb <= BF16_FACTOR_TOL and ep <= PRECOND_TOL
