@@ -372,7 +372,7 @@ __device__ inline bool tn_keep(bool diag, int mode, int m, int n)
 }
 
 constexpr int TN_STAGES = 3;      // LDS ring of the register-staged loop: slab s lives in stage s % 3
-constexpr int TN_LDS_STAGES = 4;  // stages allocated (the direct-to-LDS loop uses all four)
+constexpr int TN_LDS_STAGES = 4;  // stages allocated (the direct-to-LDS loops use all of them; a fifth did not pay)
 
 // sched_group_barrier masks
 #define TN_SGB(m, n) __builtin_amdgcn_sched_group_barrier(m, n, 0)
@@ -618,18 +618,18 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
     } while (0)
     // s_waitcnt vmcnt(4): everything but the four newest loads has landed (gfx9 encoding:
     // vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; the other counters are left open)
-#define TN_WAIT_ALL_BUT_NEWEST_SLAB() __builtin_amdgcn_s_waitcnt(0x0F74)
+#define TN_WAIT_ALL_BUT_NEWEST_SLAB() __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * (TN_LDS_STAGES - 3)))
 
-    TN_D(0);
-    TN_D(1);
-    TN_D(2);
+    // prologue: request slabs 0 .. S-2, wait for the first two
+#pragma unroll
+    for (int q = 0; q < TN_LDS_STAGES - 1; ++q) TN_D(q);
     TN_WAIT_ALL_BUT_NEWEST_SLAB();
     __syncthreads();
     TN_R(0, 0);
 
     int folded = 0;
     for (int s = 0; s < nslab; ++s) {
-        const int st0 = s & 3, st1 = (s + 1) & 3, st3 = (s + 3) & 3;
+        const int st0 = s % TN_LDS_STAGES, st1 = (s + 1) % TN_LDS_STAGES, st3 = (s + TN_LDS_STAGES - 1) % TN_LDS_STAGES;
         TN_D(st3);
         TN_R(st0, 1);
         TN_M(0);
