@@ -1,0 +1,188 @@
+// Curvature of bfloat16 activations on the bf16 MFMA with 256 x 256 tiles.
+//
+// The 128 x 128 kernel of tn_gemm.h is bound by what one CU can keep in flight:
+// with bf16 MFMA a 32-token slab is consumed eight times faster than an fp32
+// slab of the same bytes, and 160 KB of LDS cannot hold enough slabs to cover
+// the memory latency.  Flops per byte double with the tile edge, so this kernel
+// gives one workgroup (4 waves, one per SIMD) a 256 x 256 tile, each wave a
+// 128 x 128 quarter as 4 x 4 MFMA 32x32x16 blocks (256 accumulator registers).
+// Operands come from the packed layout of pack_bf16_kernel
+// (P[token / 8][column][token % 8]); a slab of 32 tokens is 16 KB per operand and
+// goes straight into a 4-stage LDS ring (128 KB) with global_load_lds_dwordx4.
+//   iteration s:  D(s+3)  R(s, 2nd half)  M(s, 1st half)  R(s+1, 1st half)
+//                 M(s, 2nd half)  wait D(s+2)  barrier
+// Lower-triangular tile set, mirrored stores (bitwise symmetric result), alpha /
+// beta as in the engine.  One fp32 accumulation level: the tolerance of the bf16
+// variant (2e-2 on the factor) does not need the chunked sum of the fp32 path.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tn_gemm.h"
+
+namespace kfac {
+
+constexpr int B2_TILE = 256;
+constexpr int B2_STAGE_BYTES = BF_SLAB_GROUPS * B2_TILE * 16;  // 16 KB per operand per stage
+constexpr int B2_STAGES = 4;
+
+// Same descriptor table as the other curvature launches (SyrkProblem: x = packed
+// copy, n = padded tokens, ldx = padded columns (a multiple of 256), tile_begin
+// in 256-tiles).
+struct Syrk256Launch {
+    SyrkProblem p[SYRK_MAX_PROBLEMS];
+    int count;
+    float alpha, beta;
+};
+
+__host__ __device__ inline int b2_tiles(int d)
+{
+    const int nt = (d + B2_TILE - 1) / B2_TILE;
+    return nt * (nt + 1) / 2;
+}
+
+__global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const Syrk256Launch lp)
+{
+    __shared__ __attribute__((aligned(16))) char lds_a[B2_STAGES * B2_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char lds_b[B2_STAGES * B2_STAGE_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+    // which tile
+    const int t = tn_logical_tile(blockIdx.x, gridDim.x);
+    int pi = 0, hi = lp.count;
+    while (hi - pi > 1) {
+        const int mid = (pi + hi) >> 1;
+        if (lp.p[mid].tile_begin <= t)
+            pi = mid;
+        else
+            hi = mid;
+    }
+    const SyrkProblem &pr = lp.p[pi];
+    const int d = pr.d;
+    int ti, tj;
+    tn_decode_lower(t - pr.tile_begin, (d + B2_TILE - 1) / B2_TILE, ti, tj);
+    const int m0 = ti * B2_TILE, n0 = tj * B2_TILE;
+    const bool diag = (ti == tj);
+
+    const size_t row_bytes = (size_t)pr.ldx * 16;  // one k-group of all columns
+    const int groups = pr.n / BF_KG;
+    const int niter = groups / BF_SLAB_GROUPS;
+    const char *ga = static_cast<const char *>(pr.x) + ((size_t)m0 + lane) * 16;
+    const char *gb = static_cast<const char *>(pr.x) + ((size_t)n0 + lane) * 16;
+
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    uint4 fa[2][4], fb[2][4];  // [k step parity][block]
+    int gd = 0;                // first k-group of the next slab to request
+
+    // wave w fetches k-group gd + w: the 256 columns of each operand in four 64-column pieces
+#define B2_D(st)                                                                                              \
+    do {                                                                                                      \
+        const size_t off_ = (size_t)min(gd + wave, groups - 1) * row_bytes;                                   \
+        const int ld_ = (st) * B2_STAGE_BYTES + wave * (B2_TILE * 16);                                        \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                       \
+            tn_dma16(reinterpret_cast<const float *>(ga + off_ + q * 1024),                                   \
+                     reinterpret_cast<const float *>(lds_a + ld_ + q * 1024));                                \
+            tn_dma16(reinterpret_cast<const float *>(gb + off_ + q * 1024),                                   \
+                     reinterpret_cast<const float *>(lds_b + ld_ + q * 1024));                                \
+        }                                                                                                     \
+        gd += BF_SLAB_GROUPS;                                                                                 \
+    } while (0)
+    // k step t of a slab uses k-groups 2t and 2t+1 (one per half wave); block b of the wave tile is
+    // columns 32b .. 32b+31, so a ds_read_b128 touches 32 consecutive 16-byte units (no conflicts)
+#define B2_R(st, t, set)                                                                                      \
+    do {                                                                                                      \
+        const int u_ = (st) * B2_STAGE_BYTES + ((2 * (t) + lh) * B2_TILE + li) * 16;                          \
+        _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                       \
+            fa[set][b] = *reinterpret_cast<const uint4 *>(lds_a + u_ + (wm + 32 * b) * 16);                   \
+            fb[set][b] = *reinterpret_cast<const uint4 *>(lds_b + u_ + (wn + 32 * b) * 16);                   \
+        }                                                                                                     \
+    } while (0)
+#define B2_M(set)                                                                                             \
+    do {                                                                                                      \
+        _Pragma("unroll") for (int bi = 0; bi < 4; ++bi)                                                      \
+            _Pragma("unroll") for (int bj = 0; bj < 4; ++bj)                                                  \
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
+                    __builtin_bit_cast(bf16x8, fa[set][bi]), __builtin_bit_cast(bf16x8, fb[set][bj]),         \
+                    acc[bi][bj], 0, 0, 0);                                                                    \
+    } while (0)
+
+    B2_D(0);
+    B2_D(1);
+    B2_D(2);
+    __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8): slabs 0 and 1 have landed
+    __syncthreads();
+    B2_R(0, 0, 0);
+    for (int s = 0; s < niter; ++s) {
+        const int st0 = s & 3, st1 = (s + 1) & 3, st3 = (s + 3) & 3;
+        // The scheduling barriers pin this order: each batch of LDS reads is issued a whole batch
+        // of 16 MFMAs (512 cycles) before its data is needed; without them the compiler sinks the
+        // reads to just in front of their use and, with one wave per SIMD, nothing hides the latency.
+        B2_D(st3);
+        B2_R(st0, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        B2_M(0);
+        __builtin_amdgcn_sched_barrier(0);
+        B2_R(st1, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        B2_M(1);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0F78);  // everything but the newest slab (8 loads) has landed
+        __syncthreads();
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing may still be writing LDS
+#undef B2_D
+#undef B2_R
+#undef B2_M
+
+    // accumulator register r of lane (li, lh) in block (bi, bj): row 32 bi + 8 (r/4) + 4 lh + r%4, column 32 bj + li
+    float *__restrict__ C = pr.factor;
+    const size_t ldf = (size_t)pr.ldf;
+    const float alpha = lp.alpha, beta = lp.beta;
+    const bool vec_t = ((pr.ldf & 3) == 0) && ((reinterpret_cast<uintptr_t>(C) & 15) == 0);
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 4; ++bj) {
+            const int n = n0 + wn + 32 * bj + li;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int mq = m0 + wm + 32 * bi + 8 * q + 4 * lh;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int m = mq + e;
+                    v[e] = alpha * acc[bi][bj][4 * q + e];
+                    if (m < d && n < d && (!diag || n <= m)) {
+                        float *dst = C + (size_t)m * ldf + n;
+                        if (beta != 0.f) v[e] += beta * (*dst);
+                        *dst = v[e];
+                    }
+                }
+                // mirror: four consecutive rows of C are four consecutive columns of the transposed tile
+                if (n < d) {
+                    if (!diag && mq + 3 < d && vec_t) {
+                        *reinterpret_cast<float4 *>(C + (size_t)n * ldf + mq) = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int m = mq + e;
+                            if (m < d && (!diag || n < m)) C[(size_t)n * ldf + m] = v[e];
+                        }
+                    }
+                }
+            }
+        }
+}
+
+}  // namespace kfac

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/kfac.h"
+#include "bf16_syrk256.h"
 #include "diag_block.h"
 #include "tn_gemm.h"
 
@@ -133,7 +134,7 @@ struct CurvPlan {
 };
 
 inline int pack_groups(int64_t n) { return (int)align_up((size_t)((n + 7) / 8), BF_SLAB_GROUPS); }
-inline int pack_cols(int64_t d) { return (int)align_up((size_t)d, BM); }
+inline int pack_cols(int64_t d) { return (int)align_up((size_t)d, B2_TILE); }
 inline size_t pack_bytes(int64_t n, int64_t d) { return align_up((size_t)pack_groups(n) * pack_cols(d) * 16, WS_ALIGN); }
 
 bool curvature_plan(const kfac_curvature_item *items, int64_t count, kfac_dtype dtype, CurvPlan &pl)
@@ -355,12 +356,30 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         lp.c.alpha = alpha;
         lp.c.beta = beta;
         lp.c.partial = part;
-        if (dtype == KFAC_BF16) {
+        int tiles256 = 0;
+        if (dtype == KFAC_BF16)
+            for (int64_t i = 0; i < n; ++i) tiles256 += b2_tiles(lp.p[i].d);
+        if (dtype == KFAC_BF16 && tiles256 >= 192) {
+            // enough 256 x 256 tiles to occupy the chip: twice the flops per byte fetched
+            Syrk256Launch l2;
+            std::memset(&l2, 0, sizeof(l2));
+            int tb = 0;
+            for (int64_t i = 0; i < n; ++i) {
+                l2.p[i] = lp.p[i];
+                l2.p[i].tile_begin = tb;
+                tb += b2_tiles(lp.p[i].d);
+            }
+            l2.count = (int)n;
+            l2.alpha = alpha;
+            l2.beta = beta;
+            hipLaunchKernelGGL(pack_bf16_kernel, dim3((cmax + PACK_COLS - 1) / PACK_COLS, gmax / BF_SLAB_GROUPS, (unsigned)n), dim3(256), 0, st, pk);
+            hipLaunchKernelGGL(curvature_syrk_bf16_256_kernel, dim3(tb), dim3(256), 0, st, l2);
+        } else if (dtype == KFAC_BF16) {
             SyrkLaunchPacked lb;
             static_assert(sizeof(lb) == sizeof(lp), "the curvature launch types share one layout");
             lp.c.slab_align = 2;  // slabs of the engine are 16 tokens, the bf16 loop steps by 32
             std::memcpy(&lb, &lp, sizeof(lp));
-            hipLaunchKernelGGL(pack_bf16_kernel, dim3((cmax + 255) / 256, gmax, (unsigned)n), dim3(256), 0, st, pk);
+            hipLaunchKernelGGL(pack_bf16_kernel, dim3((cmax + PACK_COLS - 1) / PACK_COLS, gmax / BF_SLAB_GROUPS, (unsigned)n), dim3(256), 0, st, pk);
             hipLaunchKernelGGL(curvature_syrk_bf16mfma_kernel, dim3(tiles), dim3(TN_THREADS), 0, st, lb);
             if (pl.splits > 1)
                 hipLaunchKernelGGL(curvature_reduce_packed_kernel, dim3(tiles / pl.splits), dim3(TN_THREADS), 0, st, lb);

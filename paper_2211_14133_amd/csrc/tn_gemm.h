@@ -684,7 +684,7 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
 // (lane (i, h) holds k = 8h .. 8h+7 of column i).  The activations are stored
 // [tokens, d], so those eight values are d elements apart.  A small pre-pass
 // (pack_bf16_kernel) rewrites x as P[k / 8][column][k % 8], zero-padded to a
-// multiple of 32 tokens and 128 columns: the eight values are then 16 contiguous
+// multiple of 32 tokens and 256 columns: the eight values are then 16 contiguous
 // bytes, a wave fetches 64 columns of a k-group with one global_load_lds_dwordx4
 // and reads its MFMA operands from LDS with ds_read_b128, all conflict-free and
 // without a transpose.  Slab = 32 tokens = 4 k-groups = 8 KB per operand, the
@@ -703,23 +703,52 @@ struct PackLaunch {
     PackItem it[PACK_MAX_ITEMS];
 };
 
+// One workgroup repacks 32 tokens x 512 columns through LDS, so that both sides move
+// 16 bytes per lane in 1 KB runs per wave: row-major reads (eight columns of a token),
+// packed writes (eight tokens of a column).
+constexpr int PACK_COLS = 512;
+constexpr int PACK_ROWS = BF_KG * BF_SLAB_GROUPS;  // 32 tokens
+constexpr int PACK_LDS_ROW = PACK_COLS * 2 + 16;   // bytes per token row in LDS
+
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const PackLaunch pl)
 {
+    __shared__ __attribute__((aligned(16))) unsigned char tile[PACK_ROWS * PACK_LDS_ROW];
     const PackItem &it = pl.it[blockIdx.z];
-    const int c = blockIdx.x * 256 + threadIdx.x, g = blockIdx.y;
-    if (c >= it.dp || g >= it.gp) return;
-    unsigned v[8];
+    const int c0 = blockIdx.x * PACK_COLS, g0 = blockIdx.y * BF_SLAB_GROUPS;
+    if (c0 >= it.dp || g0 >= it.gp) return;  // whole workgroup leaves together (gp is a multiple of 4)
+    const int t = threadIdx.x;
+    const int cu = t & 63, col = c0 + 8 * cu;
+    const bool vec = ((it.ldx & 7) == 0) && ((reinterpret_cast<uintptr_t>(it.x) & 15) == 0);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int k = g * 8 + e;
-        v[e] = (k < it.n && c < it.d) ? it.x[(size_t)k * it.ldx + c] : 0u;
+    for (int r = 0; r < PACK_ROWS / 4; ++r) {
+        const int row = (t >> 6) + 4 * r;
+        const int k = g0 * BF_KG + row;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (k < it.n && col < it.d) {
+            const unsigned short *src = it.x + (size_t)k * it.ldx + col;
+            if (vec && col + 8 <= it.d) {
+                v = *reinterpret_cast<const uint4 *>(src);
+            } else {
+                unsigned h[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) h[e] = (col + e < it.d) ? src[e] : 0u;
+                v = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            }
+        }
+        *reinterpret_cast<uint4 *>(tile + row * PACK_LDS_ROW + cu * 16) = v;
     }
-    uint4 o;
-    o.x = v[0] | (v[1] << 16);
-    o.y = v[2] | (v[3] << 16);
-    o.z = v[4] | (v[5] << 16);
-    o.w = v[6] | (v[7] << 16);
-    *reinterpret_cast<uint4 *>(it.dst + ((size_t)g * it.dp + c) * 8) = o;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 2 * BF_SLAB_GROUPS; ++r) {
+        const int gi = r >> 1, c = t + 256 * (r & 1);
+        if (c0 + c >= it.dp) continue;
+        unsigned h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            h[e] = *reinterpret_cast<const unsigned short *>(tile + (BF_KG * gi + e) * PACK_LDS_ROW + 2 * c);
+        *reinterpret_cast<uint4 *>(it.dst + ((size_t)(g0 + gi) * it.dp + c0 + c) * 8) =
+            make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
 }
 
 // K loop on packed bf16 operands.  pr.A = pr.B = packed array, pr.lda = padded
@@ -791,7 +820,9 @@ __device__ inline void tn_mainloop_bf16_packed(const TnProblem &pr, const TnTile
     do {                                                                                                    \
         BF_D(((s_) + 3) & 3);                                                                               \
         BF_R(((s_) + 1) & 3, nxt);                                                                          \
+        __builtin_amdgcn_sched_barrier(0); /* keep the reads of the next slab ahead of these MFMAs */       \
         BF_M(cur);                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
         __builtin_amdgcn_s_waitcnt(0x0F74); /* vmcnt(4): all but the newest slab has landed */              \
         __syncthreads();                                                                                    \
     } while (0)

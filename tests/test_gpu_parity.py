@@ -529,3 +529,16 @@ def test_chain_config5_largest_factor(k, oracle):
     eai, ep = oracle.rel_fro(host(ai), oai), oracle.rel_fro(host(p), op)
     print("cfg 5 ffn2: A %.2e B %.2e A^-1 %.2e P %.2e" % (ea, eb, eai, ep), flush=True)
     assert ea <= BF16_FACTOR_TOL and eb <= BF16_FACTOR_TOL and ep <= PRECOND_TOL
+
+
+def test_curvature_bf16_large_tiles(k, oracle):
+    # enough 256 x 256 tiles for the large-tile bf16 kernel; ragged size, accumulation over two micro-batches
+    n, d = 600, 5000
+    xs = [synth.activations(5, 1, m, 0, n, d, bf16=True) for m in range(2)]
+    f = torch.empty(d, d, device="cuda")
+    for m, x in enumerate(xs):
+        k.kfac_curvature(dev(x).to(torch.bfloat16), f, 1.0 / (2 * n), 0.0 if m == 0 else 1.0)
+    err = oracle.rel_fro(host(f), oracle.curvature(xs))
+    print("bf16 large tiles rel_fro %.3g" % err, flush=True)
+    assert err <= BF16_FACTOR_TOL and err <= 2e-6
+    assert np.array_equal(host(f), host(f).T)
