@@ -91,19 +91,20 @@ struct TnBatch {
             lp.c.alpha = alpha;
             lp.c.beta = beta;
             lp.c.partial = partial;
+            const int grid = tn_balance_xcds(lp, tiles);
             if (rec != nullptr) {
                 double fl = 0.0;
                 for (int k = 0; k < cnt; ++k) fl += tn_problem_flops(lp.p[k].M, lp.p[k].N, lp.p[k].K, tile_mode, mask_a, mask_b);
                 const int sp = splits;
-                rec->push_back(PlanStep{[lp, tiles, sp](hipStream_t s) {
-                                            hipLaunchKernelGGL(tn_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, s, lp);
+                rec->push_back(PlanStep{[lp, tiles, sp, grid](hipStream_t s) {
+                                            hipLaunchKernelGGL(tn_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
                                             if (sp > 1)
                                                 hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / sp), dim3(TN_THREADS), 0, s, lp);
                                         },
                                         fl});
                 continue;
             }
-            hipLaunchKernelGGL(tn_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, stream, lp);
+            hipLaunchKernelGGL(tn_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, stream, lp);
             if (splits > 1)
                 hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / splits), dim3(TN_THREADS), 0, stream, lp);
             const hipError_t e = hipGetLastError();
@@ -238,19 +239,20 @@ struct InvBatch {
             lp.c.alpha = alpha;
             lp.c.beta = beta;
             lp.op = op;
+            const int grid = tn_balance_xcds(lp, tiles);
             if (rec != nullptr) {
                 double fl = 0.0;
                 for (int k = 0; k < cnt; ++k) {
                     const InvDims dm = inv_dims(op, lp.m[lp.n[k].mat].d, lp.n[k].a, lp.n[k].b, lp.n[k].c);
                     fl += tn_problem_flops(dm.M, dm.N, dm.K, tile_mode, mask_a, mask_b);
                 }
-                rec->push_back(PlanStep{[lp, tiles](hipStream_t s) {
-                                            hipLaunchKernelGGL(invert_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, s, lp);
+                rec->push_back(PlanStep{[lp, grid](hipStream_t s) {
+                                            hipLaunchKernelGGL(invert_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
                                         },
                                         fl});
                 continue;
             }
-            hipLaunchKernelGGL(invert_gemm_kernel, dim3(tiles), dim3(TN_THREADS), 0, stream, lp);
+            hipLaunchKernelGGL(invert_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, stream, lp);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }

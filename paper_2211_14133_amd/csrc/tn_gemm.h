@@ -57,6 +57,8 @@ struct TnCommon {
     float beta;
     float *partial;  // [total logical tiles][BM * BN]
     int slab_align;  // K ranges of split tiles are multiples of this many slabs (0 or 1: any)
+    int xcd_balanced;  // 0: each XCD takes a contiguous eighth of the tiles; 1: the ranges xcd_begin[]
+    int xcd_begin[9];  // XCD x works on logical tiles xcd_begin[x] .. xcd_begin[x+1]-1 (equal cost, see tn_balance_xcds)
 };
 
 // General launch: up to TN_MAX_PROBLEMS arbitrary problems.
@@ -65,8 +67,8 @@ struct TnLaunch {
     static constexpr bool kAllowMask = true;
     TnProblem p[TN_MAX_PROBLEMS];
     TnCommon c;
-    __device__ int tile_begin(int i) const { return p[i].tile_begin; }
-    __device__ TnProblem problem(int i) const { return p[i]; }
+    __host__ __device__ int tile_begin(int i) const { return p[i].tile_begin; }
+    __host__ __device__ TnProblem problem(int i) const { return p[i]; }
 };
 
 // Curvature launch: factor = beta * factor + alpha * x^T x.  Both operands are x
@@ -89,8 +91,8 @@ struct SyrkLaunchT {
     static constexpr bool kAllowMask = false;
     SyrkProblem p[SYRK_MAX_PROBLEMS];
     TnCommon c;
-    __device__ int tile_begin(int i) const { return p[i].tile_begin; }
-    __device__ TnProblem problem(int i) const
+    __host__ __device__ int tile_begin(int i) const { return p[i].tile_begin; }
+    __host__ __device__ TnProblem problem(int i) const
     {
         const SyrkProblem &q = p[i];
         TnProblem r;
@@ -162,8 +164,8 @@ struct InvLaunch {
     InvNode n[INV_MAX_NODES];
     TnCommon c;
     int op;
-    __device__ int tile_begin(int i) const { return n[i].tile_begin; }
-    __device__ TnProblem problem(int i) const
+    __host__ __device__ int tile_begin(int i) const { return n[i].tile_begin; }
+    __host__ __device__ TnProblem problem(int i) const
     {
         const InvNode nd = n[i];
         const InvMatDesc &mt = m[nd.mat];
@@ -217,7 +219,7 @@ __host__ __device__ inline int tn_tiles(int M, int N, int mode)
 // Order of the tiles of one problem: bands of SUPER_ROWS tile-rows, column by
 // column inside a band, so that tiles running at the same time share operand
 // columns (they hit in the XCD's L2).
-__device__ inline void tn_decode_full(int idx, int tm, int tn, int &ti, int &tj)
+__host__ __device__ inline void tn_decode_full(int idx, int tm, int tn, int &ti, int &tj)
 {
     const int band = idx / (SUPER_ROWS * tn);
     const int r = idx - band * SUPER_ROWS * tn;
@@ -226,7 +228,7 @@ __device__ inline void tn_decode_full(int idx, int tm, int tn, int &ti, int &tj)
     ti = band * SUPER_ROWS + r % rows;
 }
 
-__device__ inline void tn_decode_lower(int idx, int nt, int &ti, int &tj)
+__host__ __device__ inline void tn_decode_lower(int idx, int nt, int &ti, int &tj)
 {
     int r0 = 0, r1 = 0;
     for (;;) {
@@ -256,13 +258,42 @@ __device__ inline void tn_decode_lower(int idx, int nt, int &ti, int &tj)
     }
 }
 
-// blockIdx -> logical tile, so that each XCD (blocks are dealt round-robin to
-// the 8 XCDs) works on one contiguous range of logical tiles.
+// blockIdx -> logical tile.  Workgroups are dealt round-robin to the 8 XCDs and
+// dispatched in order; each XCD has its own L2.  Every XCD works on one contiguous
+// range of logical tiles (neighbouring tiles share operand panels, which then hit
+// in that L2).  When all tiles cost the same the ranges are plain eighths.  When
+// they do not (triangular operands clip K, problems of mixed size) the host cuts
+// the list into eight ranges of equal cost instead (tn_balance_xcds): with plain
+// eighths one XCD would hold the long tiles and finish long after the others.
+// The grid then has 8 * (longest range) workgroups and the surplus ones of the
+// shorter ranges leave at once (return value -1).
 __device__ inline int tn_logical_tile(int bid, int nblocks)
 {
     const int base = nblocks >> 3, rem = nblocks & 7;
     const int xcd = bid & 7, q = bid >> 3;
     return xcd * base + min(xcd, rem) + q;
+}
+
+__device__ inline int tn_logical_tile(int bid, int nblocks, const TnCommon &c)
+{
+    if (!c.xcd_balanced) return tn_logical_tile(bid, nblocks);
+    const int xcd = bid & 7;
+    const int t = c.xcd_begin[xcd] + (bid >> 3);
+    return t < c.xcd_begin[xcd + 1] ? t : -1;
+}
+
+// K range of a tile that can hold non-zeros under the operand masks: first row kb (a multiple
+// of BK) and length in slabs of BK.
+__host__ __device__ inline void tn_k_range(const TnCommon &lp, int K, int m0, int n0, int &kb, int &nslab)
+{
+    kb = 0;
+    int ke = K;
+    if (lp.mask_a == MASK_KEEP_K_GE) kb = max(kb, m0);
+    if (lp.mask_a == MASK_KEEP_K_LE) ke = min(ke, m0 + BM);
+    if (lp.mask_b == MASK_KEEP_K_GE) kb = max(kb, n0);
+    if (lp.mask_b == MASK_KEEP_K_LE) ke = min(ke, n0 + BN);
+    kb = (kb / BK) * BK;
+    nslab = ke > kb ? (ke - kb + BK - 1) / BK : 0;
 }
 
 struct TnTile {
@@ -302,20 +333,63 @@ __device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
     tl.diag = (lp.tile_mode != TILE_FULL) && (tl.ti == tl.tj);
     tl.m0 = tl.ti * BM;
     tl.n0 = tl.tj * BN;
-    // K range that can hold non-zeros under the operand masks, in slabs of BK
-    int kb = 0, ke = pr.K;
-    if (lp.mask_a == MASK_KEEP_K_GE) kb = max(kb, tl.m0);
-    if (lp.mask_a == MASK_KEEP_K_LE) ke = min(ke, tl.m0 + BM);
-    if (lp.mask_b == MASK_KEEP_K_GE) kb = max(kb, tl.n0);
-    if (lp.mask_b == MASK_KEEP_K_LE) ke = min(ke, tl.n0 + BN);
-    kb = (kb / BK) * BK;
-    const int nslab = ke > kb ? (ke - kb + BK - 1) / BK : 0;
+    int kb, nslab;
+    tn_k_range(lp, pr.K, tl.m0, tl.n0, kb, nslab);
     int per = (nslab + lp.splits - 1) / lp.splits;
     if (lp.slab_align > 1) per = (per + lp.slab_align - 1) / lp.slab_align * lp.slab_align;
     tl.kbase = kb;
     tl.kt0 = min(nslab, tl.split * per);
     tl.kt1 = min(nslab, tl.kt0 + per);
     return tl;
+}
+
+// Host side of the cost-balanced XCD ranges: cuts the logical tiles of a launch into eight
+// contiguous ranges of (nearly) equal cost, cost of a tile = slabs of its K range plus a
+// constant for its prologue and epilogue, and returns the number of workgroups to launch.
+template <class L>
+inline int tn_balance_xcds(L &ll, int total_tiles)
+{
+    TnCommon &c = ll.c;
+    c.xcd_balanced = 0;
+    if (total_tiles < 64) return total_tiles;
+    constexpr int TILE_OVERHEAD = 4;
+    auto for_each_cost = [&](auto &&fn) {
+        for (int pi = 0; pi < c.count; ++pi) {
+            const TnProblem pr = ll.problem(pi);
+            const int end = pi + 1 < c.count ? ll.tile_begin(pi + 1) : total_tiles;
+            const int tm = (pr.M + BM - 1) / BM, tn = (pr.N + BN - 1) / BN;
+            for (int t = pr.tile_begin; t < end; ++t) {
+                const int local = t - pr.tile_begin, tile = local / c.splits, split = local - tile * c.splits;
+                int ti, tj;
+                if (c.tile_mode == TILE_FULL) {
+                    tn_decode_full(tile, tm, tn, ti, tj);
+                } else {
+                    tn_decode_lower(tile, tm, ti, tj);
+                    if (c.tile_mode == TILE_UPPER) { const int sw = ti; ti = tj; tj = sw; }
+                }
+                int kb, nslab;
+                tn_k_range(c, pr.K, ti * BM, tj * BN, kb, nslab);
+                int per = (nslab + c.splits - 1) / c.splits;
+                if (c.slab_align > 1) per = (per + c.slab_align - 1) / c.slab_align * c.slab_align;
+                const int kt0 = min(nslab, split * per), kt1 = min(nslab, kt0 + per);
+                fn(t, kt1 - kt0 + TILE_OVERHEAD);
+            }
+        }
+    };
+    long long total = 0;
+    for_each_cost([&](int, int w) { total += w; });
+    int x = 1;
+    long long run = 0;
+    c.xcd_begin[0] = 0;
+    for_each_cost([&](int t, int w) {
+        while (x < 8 && run * 8 >= (long long)x * total) c.xcd_begin[x++] = t;
+        run += w;
+    });
+    while (x <= 8) c.xcd_begin[x++] = total_tiles;
+    int longest = 0;
+    for (int i = 0; i < 8; ++i) longest = max(longest, c.xcd_begin[i + 1] - c.xcd_begin[i]);
+    c.xcd_balanced = 1;
+    return 8 * longest;
 }
 
 // Unconditional load of four consecutive elements of operand row k starting at
@@ -856,7 +930,9 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
     const TnCommon &lp = ll.c;
     const int tid = threadIdx.x;
     TnProblem pr;
-    const TnTile tl = tn_locate(ll, tn_logical_tile(blockIdx.x, gridDim.x), pr);
+    const int logical = tn_logical_tile(blockIdx.x, gridDim.x, lp);
+    if (logical < 0) return;  // surplus workgroup of a short XCD range (the whole workgroup leaves)
+    const TnTile tl = tn_locate(ll, logical, pr);
     const int M = pr.M, N = pr.N;
 
     // vector loads need 16-byte aligned rows
@@ -888,10 +964,36 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
     if (!done) {
         if constexpr (L::kAllowMask) {
             if (masked) {
-                if (fast_a && fast_b)
-                    tn_mainloop<true, true>(lp, pr, tl, As, Bs, sum);
-                else
+                if (fast_a && fast_b) {
+                    // A triangular operand is only partly kept where K runs through the tile's own
+                    // diagonal block (at most BM rows of K per masked operand); outside of it the
+                    // clipped K range holds whole rows.  Those slabs take the direct loop, which is
+                    // faster than the masked one; short remainders are not worth its start-up.
+                    int p0 = pr.K, p1 = 0;  // hull of the partly kept K rows
+                    if (lp.mask_a != MASK_NONE) { p0 = min(p0, tl.m0); p1 = max(p1, tl.m0 + BM); }
+                    if (lp.mask_b != MASK_NONE) { p0 = min(p0, tl.n0); p1 = max(p1, tl.n0 + BN); }
+                    int s0 = max(tl.kt0, min(tl.kt1, (p0 - tl.kbase) / BK));             // first masked slab
+                    int s1 = max(s0, min(tl.kt1, (p1 - tl.kbase + BK - 1) / BK));        // one past the last
+                    constexpr int MIN_DIRECT = 8;
+                    const bool direct_ok = (pr.K % BK) == 0;
+                    if (!direct_ok || s0 - tl.kt0 < MIN_DIRECT) s0 = tl.kt0;
+                    if (!direct_ok || tl.kt1 - s1 < MIN_DIRECT) s1 = tl.kt1;
+                    TnTile seg = tl;
+                    if (s0 > tl.kt0) {
+                        seg.kt0 = tl.kt0; seg.kt1 = s0;
+                        tn_mainloop_direct(pr, seg, As, Bs, sum);
+                        __syncthreads();
+                    }
+                    seg.kt0 = s0; seg.kt1 = s1;
+                    tn_mainloop<true, true>(lp, pr, seg, As, Bs, sum);
+                    if (s1 < tl.kt1) {
+                        __syncthreads();
+                        seg.kt0 = s1; seg.kt1 = tl.kt1;
+                        tn_mainloop_direct(pr, seg, As, Bs, sum);
+                    }
+                } else {
                     tn_mainloop<false, true>(lp, pr, tl, As, Bs, sum);
+                }
                 done = true;
             }
         }
@@ -907,8 +1009,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
     // 8*(r/4) + 4*lh + r%4, column li of the block; block (bi, bj) interleaves
     // rows/columns with stride 2 (see the operand feed above).
     if (lp.splits > 1) {
-        const int t = tn_logical_tile(blockIdx.x, gridDim.x);
-        float *P = lp.partial + (size_t)t * (BM * BN);
+        float *P = lp.partial + (size_t)logical * (BM * BN);
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi)
 #pragma unroll
