@@ -172,6 +172,20 @@ def main():
     f_total = f_curv + f_inv + f_prec
     achieved = f_curv_launch / (launch_ms * 1e-3) / 1e12
 
+    # what the matrix cores sustain on this chip with nothing else in the way (register-only MFMA loop)
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    probe_flops = ctypes.c_double(0.0)
+    probe_ms = []
+    for _ in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        check(lib.kfac_mfma_probe(binding.KFAC_F32, 4000, ctypes.c_void_p(sink.data_ptr()),
+                                  ctypes.byref(probe_flops), sp))
+        e1.record(stream)
+        torch.cuda.synchronize()
+        probe_ms.append(e0.elapsed_time(e1))
+    measured_peak = probe_flops.value / (min(probe_ms[1:]) * 1e-3) / 1e12
+
     result = {
         "metric": "kfac_step_ms_bert_large_stage (curvature + inversion + precondition)",
         "value": round(ms_per_step, 3),
@@ -206,6 +220,8 @@ def main():
             "unit": "TFLOP/s",
             "frac": round(achieved / PEAK_F32_MFMA_TFLOPS, 4),
             "traffic": CURVATURE_TRAFFIC_BYTES_PER_LAUNCH,
+            "measured_mfma_peak": round(measured_peak, 1),
+            "frac_of_measured_peak": round(achieved / measured_peak, 4),
             "launch_ms": round(launch_ms, 4),
             "flops_per_launch": f_curv_launch,
         },

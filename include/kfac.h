@@ -242,6 +242,17 @@ kfac_status kfac_perf_model(double c_f, double c_b, double t_f, double t_b, int6
 const char *kfac_status_string(kfac_status status);
 
 /* Library version as major * 10000 + minor * 100 + patch. */
+/* Measurement aid (not a step of the method): enqueues a kernel whose waves do nothing but
+ * matrix-core instructions on registers, so that a caller can time what the matrix cores of this
+ * chip sustain and report a kernel against that ceiling as well as against the published peak.
+ *   dtype     KFAC_F32: MFMA 32x32x2 (4096 flops each); KFAC_BF16: MFMA 32x32x16 (32768 flops each)
+ *   iters     loop iterations per wave (> 0); each iteration issues 8 independent MFMAs
+ *   sink      device buffer of at least 256 bytes, caller-owned (in practice never written)
+ *   flops     host pointer; receives the floating-point operations the launch performs
+ * The launch is asynchronous on `stream`.  Errors: KFAC_ERR_ARG for null pointers, iters <= 0 or an
+ * unknown dtype; KFAC_ERR_HIP if the launch fails. */
+kfac_status kfac_mfma_probe(kfac_dtype dtype, int64_t iters, void *sink, double *flops, void *stream);
+
 int kfac_version(void);
 
 #ifdef __cplusplus

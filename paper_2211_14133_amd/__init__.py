@@ -4,6 +4,7 @@ from .binding import (  # noqa: F401
     KfacError,
     kfac_assign_work,
     kfac_perf_model,
+    kfac_mfma_probe,
     kfac_curvature,
     kfac_curvature_grouped,
     kfac_curvature_grouped_workspace,

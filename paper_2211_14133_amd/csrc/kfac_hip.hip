@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <new>
@@ -13,6 +14,7 @@
 
 #include "../../include/kfac.h"
 #include "bf16_syrk256.h"
+#include "mfma_probe.h"
 #include "diag_block.h"
 #include "tn_gemm.h"
 
@@ -277,6 +279,23 @@ const char *kfac_status_string(kfac_status s)
         case KFAC_ERR_HIP: return "HIP launch error";
     }
     return "unknown status";
+}
+
+kfac_status kfac_mfma_probe(kfac_dtype dtype, int64_t iters, void *sink, double *flops, void *stream)
+{
+    if (sink == nullptr || flops == nullptr || iters <= 0 || iters > INT32_MAX) return KFAC_ERR_ARG;
+    if (dtype != KFAC_F32 && dtype != KFAC_BF16) return KFAC_ERR_ARG;
+    constexpr int WORKGROUPS = 256 * 2 * 8;  // eight rounds of two workgroups per CU
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const double per_mfma = dtype == KFAC_F32 ? 4096.0 : 32768.0;
+    *flops = (double)WORKGROUPS * 4.0 * (double)iters * PROBE_MFMA_PER_ITER * per_mfma;
+    if (dtype == KFAC_F32)
+        hipLaunchKernelGGL(mfma_probe_f32_kernel, dim3(WORKGROUPS), dim3(256), 0, st, 1.0f, 2.0f, (int)iters,
+                           static_cast<float *>(sink));
+    else
+        hipLaunchKernelGGL(mfma_probe_bf16_kernel, dim3(WORKGROUPS), dim3(256), 0, st, 0x3f803f80u, 0x3f003f00u, (int)iters,
+                           static_cast<float *>(sink));
+    return hipGetLastError() == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
 }
 
 int kfac_version(void) { return 100; }

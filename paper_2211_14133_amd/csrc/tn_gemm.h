@@ -622,19 +622,37 @@ __device__ inline void tn_dma16(const float *gptr, const float *lds_row)
                  : "memory", "m0");
 }
 
+// Same with the address split into a wave-uniform base (scalar registers) and a 32-bit
+// per-lane byte offset: the K loop then advances the base with scalar arithmetic and needs no
+// vector instruction per load.
+__device__ inline void tn_dma16_s(const float *sbase, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
 // K loop for the common case (fp32 operands, aligned full-width tiles, no
 // masks, K range a multiple of BK): slabs go from global memory straight into
 // LDS (global_load_lds_dwordx4: lane l's 16 bytes land at base + 16*l, so one
 // wave instruction fills two 512-byte rows), without staging registers, LDS
 // stores or fix-up arithmetic.  Four LDS stages:
-//   iteration s:  D(s+3)  R(second half of s)  M(first half of s)
-//                 R(first half of s+1)  M(second half of s)  wait D(s+2)  barrier
+//   iteration s:  R(second half of s)  M(first half of s) with the four loads D(s+3) between
+//                 its MFMAs  R(first half of s+1)  M(second half of s) with "wait D(s+2),
+//                 barrier" in its middle
 // D(s+3) overwrites the stage of slab s-1, which every wave finished reading
 // before the previous barrier.
+//
+// A wave issues in order and an MFMA 32x32x2 keeps the matrix core busy for 64 cycles, so
+// whatever is not an MFMA must be little and sit between MFMAs.  The loop is unrolled over
+// the four stages (LDS addresses become immediates), the loads take a scalar base that is
+// advanced with scalar arithmetic, and scheduling barriers pin the order written here.
 __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
                                           float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                           floatx16 (&sum)[2][2])
 {
+    static_assert(TN_LDS_STAGES == 4, "the loop below is unrolled over four stages");
     const int tid = threadIdx.x;
     const int K = pr.K;
     const float *__restrict__ A = pr.A;
@@ -644,8 +662,6 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int li = lane & 31, lh = lane >> 5;
     const int drow = 2 * wave + lh;  // row of the slab this lane fetches (and drow + 8)
-    const float *ga = A + tl.m0 + 4 * li;
-    const float *gb = B + tl.n0 + 4 * li;
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -658,21 +674,38 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
     const int nslab = tl.kt1 - tl.kt0;
     if (nslab <= 0) return;
     float2 fa[2][4], fb[2][4];
-    int kd = tl.kbase + tl.kt0 * BK;  // first K row of the next slab to request
+    int kd = tl.kbase + tl.kt0 * BK;  // first K row of the next slab to request (wave-uniform)
 
-    // rows past the end of the matrix are clamped: that data is never consumed.
-    // The load is written as inline assembly on purpose: issued through the
-    // builtin, the compiler drains vmcnt before every later LDS read (it cannot
-    // tell the ring stages apart), which would undo the pipeline.  The waits are
-    // placed by hand instead (TN_WAIT_ALL_BUT_NEWEST_SLAB before each barrier).
-#define TN_D(st)                                                                                   \
+    // per-lane byte offsets of the four loads of a slab, relative to the slab's first row
+    const unsigned va0 = (unsigned)(((size_t)drow * lda + tl.m0 + 4 * li) * sizeof(float));
+    const unsigned va1 = va0 + (unsigned)(8 * lda * sizeof(float));
+    const unsigned vb0 = (unsigned)(((size_t)drow * ldb + tl.n0 + 4 * li) * sizeof(float));
+    const unsigned vb1 = vb0 + (unsigned)(8 * ldb * sizeof(float));
+    // LDS byte addresses of this wave's rows in stage 0
+    const unsigned la0 = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(const __attribute__((address_space(3))) float *)&As[0][2 * wave][0]);
+    const unsigned lb0 = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(const __attribute__((address_space(3))) float *)&Bs[0][2 * wave][0]);
+    constexpr unsigned STAGE = BK * BM * sizeof(float), HALF = 8 * BM * sizeof(float);
+
+    // Slabs past the end of the K range are clamped to the last one: that data is never consumed.
+    // The load is inline assembly on purpose: issued through the builtin, the compiler drains
+    // vmcnt before every later LDS read (it cannot tell the ring stages apart), which would undo
+    // the pipeline.  The waits are placed by hand instead (TN_WAIT_ALL_BUT_NEWEST_SLAB).
+    const float *sa = A, *sb = B;  // bases of the slab being requested
+#define TN_DBASE()                                            \
+    do {                                                      \
+        const size_t kc_ = (size_t)min(kd, K - BK);           \
+        sa = A + kc_ * lda;                                   \
+        sb = B + kc_ * ldb;                                   \
+        kd += BK;                                             \
+    } while (0)
+#define TN_D1(st, w)                                                                               \
     do {                                                                                           \
-        const size_t r0_ = (size_t)min(kd + drow, K - 1), r1_ = (size_t)min(kd + 8 + drow, K - 1); \
-        tn_dma16(ga + r0_ * lda, &As[st][2 * wave][0]);                                            \
-        tn_dma16(ga + r1_ * lda, &As[st][8 + 2 * wave][0]);                                        \
-        tn_dma16(gb + r0_ * ldb, &Bs[st][2 * wave][0]);                                            \
-        tn_dma16(gb + r1_ * ldb, &Bs[st][8 + 2 * wave][0]);                                        \
-        kd += BK;                                                                                  \
+        if ((w) == 0) tn_dma16_s(sa, va0, la0 + (st) * STAGE);                                     \
+        if ((w) == 1) tn_dma16_s(sa, va1, la0 + (st) * STAGE + HALF);                              \
+        if ((w) == 2) tn_dma16_s(sb, vb0, lb0 + (st) * STAGE);                                     \
+        if ((w) == 3) tn_dma16_s(sb, vb1, lb0 + (st) * STAGE + HALF);                              \
     } while (0)
 #define TN_R(st, half)                                                                                            \
     do {                                                                                                          \
@@ -681,69 +714,92 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
             fb[half][q] = *reinterpret_cast<const float2 *>(&Bs[st][8 * (half) + 2 * q + lh][wn + 2 * li]);       \
         }                                                                                                         \
     } while (0)
-#define TN_M(half)                                                                                                \
-    do {                                                                                                          \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                           \
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].x, acc[0][0], 0, 0, 0);   \
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].y, acc[0][1], 0, 0, 0);   \
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].x, acc[1][0], 0, 0, 0);   \
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[1][1], 0, 0, 0);   \
-        }                                                                                                         \
+#define TN_MQ(half, q)                                                                                        \
+    do {                                                                                                      \
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].x, acc[0][0], 0, 0, 0);   \
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].y, acc[0][1], 0, 0, 0);   \
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].x, acc[1][0], 0, 0, 0);   \
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[1][1], 0, 0, 0);   \
     } while (0)
+#define TN_PIN() __builtin_amdgcn_sched_barrier(0)
     // s_waitcnt vmcnt(4): everything but the four newest loads has landed (gfx9 encoding:
     // vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; the other counters are left open)
-#define TN_WAIT_ALL_BUT_NEWEST_SLAB() __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * (TN_LDS_STAGES - 3)))
+#define TN_WAIT_ALL_BUT_NEWEST_SLAB() __builtin_amdgcn_s_waitcnt(0x0F74)
+    // one slab: consumes the slab in stage st0, reads ahead into st1, requests into st3
+#define TN_ITER(st0, st1, st3)                                                                     \
+    do {                                                                                           \
+        TN_R(st0, 1);                                                                              \
+        TN_DBASE();                                                                                \
+        TN_PIN();                                                                                  \
+        TN_MQ(0, 0);                                                                               \
+        TN_PIN();                                                                                  \
+        TN_D1(st3, 0);                                                                             \
+        TN_PIN();                                                                                  \
+        TN_MQ(0, 1);                                                                               \
+        TN_PIN();                                                                                  \
+        TN_D1(st3, 1);                                                                             \
+        TN_PIN();                                                                                  \
+        TN_MQ(0, 2);                                                                               \
+        TN_PIN();                                                                                  \
+        TN_D1(st3, 2);                                                                             \
+        TN_PIN();                                                                                  \
+        TN_MQ(0, 3);                                                                               \
+        TN_PIN();                                                                                  \
+        TN_D1(st3, 3);                                                                             \
+        TN_PIN();                                                                                  \
+        TN_R(st1, 0);                                                                              \
+        TN_PIN();                                                                                  \
+        TN_MQ(1, 0);                                                                               \
+        TN_MQ(1, 1);                                                                               \
+        TN_PIN();                                                                                  \
+        TN_WAIT_ALL_BUT_NEWEST_SLAB();                                                             \
+        __syncthreads();                                                                           \
+        TN_PIN();                                                                                  \
+        TN_MQ(1, 2);                                                                               \
+        TN_MQ(1, 3);                                                                               \
+        TN_PIN();                                                                                  \
+        if (++folded == TN_CHUNK_SLABS) {                                                          \
+            folded = 0;                                                                            \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i)                                          \
+                _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                    \
+                    sum[i][j] += acc[i][j];                                                        \
+                    _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;             \
+                }                                                                                  \
+        }                                                                                          \
+    } while (0)
 
-    // prologue: request slabs 0 .. S-2, wait for the first two
+    // prologue: request slabs 0 .. 2, wait for the first two
 #pragma unroll
-    for (int q = 0; q < TN_LDS_STAGES - 1; ++q) TN_D(q);
+    for (int q = 0; q < TN_LDS_STAGES - 1; ++q) {
+        TN_DBASE();
+        TN_D1(q, 0);
+        TN_D1(q, 1);
+        TN_D1(q, 2);
+        TN_D1(q, 3);
+    }
     TN_WAIT_ALL_BUT_NEWEST_SLAB();
     __syncthreads();
     TN_R(0, 0);
 
     int folded = 0;
-    for (int s = 0; s < nslab; ++s) {
-        const int st0 = s % TN_LDS_STAGES, st1 = (s + 1) % TN_LDS_STAGES, st3 = (s + TN_LDS_STAGES - 1) % TN_LDS_STAGES;
-        TN_D(st3);
-        TN_R(st0, 1);
-        TN_M(0);
-        TN_R(st1, 0);
-        TN_M(1);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            TN_SGB(SG_MFMA, 1);
-            TN_SGB(SG_DS_READ, 1);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            TN_SGB(SG_MFMA, 1);
-            TN_SGB(SG_VMEM_READ, 1);
-        }
-        TN_SGB(SG_MFMA, 8);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            TN_SGB(SG_MFMA, 1);
-            TN_SGB(SG_DS_READ, 1);
-        }
-        TN_SGB(SG_MFMA, 12);
-        TN_WAIT_ALL_BUT_NEWEST_SLAB();
-        __syncthreads();
-        if (++folded == TN_CHUNK_SLABS) {
-            folded = 0;
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    sum[i][j] += acc[i][j];
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-                }
-        }
+    int s = 0;
+    for (; s + 4 <= nslab; s += 4) {
+        TN_ITER(0, 1, 3);
+        TN_ITER(1, 2, 0);
+        TN_ITER(2, 3, 1);
+        TN_ITER(3, 0, 2);
     }
+    const int rest = nslab - s;  // s is a multiple of four here: the stages continue at 0
+    if (rest > 0) TN_ITER(0, 1, 3);
+    if (rest > 1) TN_ITER(1, 2, 0);
+    if (rest > 2) TN_ITER(2, 3, 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no load may still be writing LDS when the tile ends
-#undef TN_D
+#undef TN_DBASE
+#undef TN_D1
 #undef TN_R
-#undef TN_M
+#undef TN_MQ
+#undef TN_PIN
+#undef TN_ITER
 #undef TN_WAIT_ALL_BUT_NEWEST_SLAB
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -957,7 +1013,9 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
         tn_mainloop_bf16_packed(pr, tl, As, Bs, sum);
         done = true;
     }
-    if (!done && fast_a && fast_b && !masked && (pr.K % BK) == 0) {
+    // (the direct loop addresses a slab with 32-bit byte offsets from its first row)
+    const bool direct_ok = (pr.K % BK) == 0 && pr.lda < (1 << 25) && pr.ldb < (1 << 25);
+    if (!done && fast_a && fast_b && !masked && direct_ok) {
         tn_mainloop_direct(pr, tl, As, Bs, sum);
         done = true;
     }
@@ -975,7 +1033,6 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
                     int s0 = max(tl.kt0, min(tl.kt1, (p0 - tl.kbase) / BK));             // first masked slab
                     int s1 = max(s0, min(tl.kt1, (p1 - tl.kbase + BK - 1) / BK));        // one past the last
                     constexpr int MIN_DIRECT = 8;
-                    const bool direct_ok = (pr.K % BK) == 0;
                     if (!direct_ok || s0 - tl.kt0 < MIN_DIRECT) s0 = tl.kt0;
                     if (!direct_ok || tl.kt1 - s1 < MIN_DIRECT) s1 = tl.kt1;
                     TnTile seg = tl;
