@@ -9,8 +9,8 @@
 // Operands come from the packed layout of pack_bf16_kernel
 // (P[token / 8][column][token % 8]); a slab of 32 tokens is 16 KB per operand and
 // goes straight into a 4-stage LDS ring (128 KB) with global_load_lds_dwordx4.
-//   iteration s:  D(s+3)  R(s, 2nd half)  M(s, 1st half)  R(s+1, 1st half)
-//                 M(s, 2nd half)  wait D(s+2)  barrier
+//   iteration s:  M(s, 1st half) with R(s, 2nd half) and half of D(s+3) between its MFMAs,
+//                 M(s, 2nd half) with R(s+1, 1st half) and the rest of D(s+3),  wait D(s+2)  barrier
 // Lower-triangular tile set, mirrored stores (bitwise symmetric result), alpha /
 // beta as in the engine.  One fp32 accumulation level: the tolerance of the bf16
 // variant (2e-2 on the factor) does not need the chunked sum of the fp32 path.
@@ -71,8 +71,15 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const S
     const size_t row_bytes = (size_t)pr.ldx * 16;  // one k-group of all columns
     const int groups = pr.n / BF_KG;
     const int niter = groups / BF_SLAB_GROUPS;
-    const char *ga = static_cast<const char *>(pr.x) + ((size_t)m0 + lane) * 16;
-    const char *gb = static_cast<const char *>(pr.x) + ((size_t)n0 + lane) * 16;
+    const char *xp = static_cast<const char *>(pr.x);
+    // per-lane byte offsets inside a k-group row (32 bits: padded columns * 16 < 2^32 is checked on the host)
+    const unsigned va = (unsigned)(((size_t)m0 + lane) * 16);
+    const unsigned vb = (unsigned)(((size_t)n0 + lane) * 16);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned la0 = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(const __attribute__((address_space(3))) char *)lds_a) + wave_s * (B2_TILE * 16);
+    const unsigned lb0 = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(const __attribute__((address_space(3))) char *)lds_b) + wave_s * (B2_TILE * 16);
 
     floatx16 acc[4][4];
 #pragma unroll
@@ -84,66 +91,123 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const S
 
     uint4 fa[2][4], fb[2][4];  // [k step parity][block]
     int gd = 0;                // first k-group of the next slab to request
+    const char *sbase = xp;    // k-group row this wave requests (wave-uniform: scalar registers)
 
-    // wave w fetches k-group gd + w: the 256 columns of each operand in four 64-column pieces
-#define B2_D(st)                                                                                              \
-    do {                                                                                                      \
-        const size_t off_ = (size_t)min(gd + wave, groups - 1) * row_bytes;                                   \
-        const int ld_ = (st) * B2_STAGE_BYTES + wave * (B2_TILE * 16);                                        \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                       \
-            tn_dma16(reinterpret_cast<const float *>(ga + off_ + q * 1024),                                   \
-                     reinterpret_cast<const float *>(lds_a + ld_ + q * 1024));                                \
-            tn_dma16(reinterpret_cast<const float *>(gb + off_ + q * 1024),                                   \
-                     reinterpret_cast<const float *>(lds_b + ld_ + q * 1024));                                \
-        }                                                                                                     \
-        gd += BF_SLAB_GROUPS;                                                                                 \
+    // Wave w fetches k-group gd + w: the 256 columns of each operand in four 64-column pieces
+    // (piece q of A is load 2q, of B load 2q+1).  The address is a scalar base plus a loop-invariant
+    // per-lane offset, so that the loop has no vector arithmetic: with an MFMA that occupies the
+    // matrix core for only 32 cycles, every other vector instruction costs MFMA issue slots.
+#define B2_DBASE()                                                                         \
+    do {                                                                                   \
+        sbase = xp + (size_t)min(gd + wave_s, groups - 1) * row_bytes;                     \
+        gd += BF_SLAB_GROUPS;                                                              \
+    } while (0)
+#define B2_D1(st, w)                                                                                           \
+    do {                                                                                                       \
+        if (((w) & 1) == 0)                                                                                    \
+            tn_dma16_s(reinterpret_cast<const float *>(sbase + ((w) >> 1) * 1024), va,                         \
+                       la0 + (st) * B2_STAGE_BYTES + ((w) >> 1) * 1024);                                       \
+        else                                                                                                   \
+            tn_dma16_s(reinterpret_cast<const float *>(sbase + ((w) >> 1) * 1024), vb,                         \
+                       lb0 + (st) * B2_STAGE_BYTES + ((w) >> 1) * 1024);                                       \
     } while (0)
     // k step t of a slab uses k-groups 2t and 2t+1 (one per half wave); block b of the wave tile is
     // columns 32b .. 32b+31, so a ds_read_b128 touches 32 consecutive 16-byte units (no conflicts)
-#define B2_R(st, t, set)                                                                                      \
+#define B2_RA(st, t, set)                                                                                     \
     do {                                                                                                      \
         const int u_ = (st) * B2_STAGE_BYTES + ((2 * (t) + lh) * B2_TILE + li) * 16;                          \
-        _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                       \
+        _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                         \
             fa[set][b] = *reinterpret_cast<const uint4 *>(lds_a + u_ + (wm + 32 * b) * 16);                   \
-            fb[set][b] = *reinterpret_cast<const uint4 *>(lds_b + u_ + (wn + 32 * b) * 16);                   \
-        }                                                                                                     \
     } while (0)
-#define B2_M(set)                                                                                             \
+#define B2_RB(st, t, set)                                                                                     \
     do {                                                                                                      \
-        _Pragma("unroll") for (int bi = 0; bi < 4; ++bi)                                                      \
-            _Pragma("unroll") for (int bj = 0; bj < 4; ++bj)                                                  \
-                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
-                    __builtin_bit_cast(bf16x8, fa[set][bi]), __builtin_bit_cast(bf16x8, fb[set][bj]),         \
-                    acc[bi][bj], 0, 0, 0);                                                                    \
+        const int u_ = (st) * B2_STAGE_BYTES + ((2 * (t) + lh) * B2_TILE + li) * 16;                          \
+        _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                         \
+            fb[set][b] = *reinterpret_cast<const uint4 *>(lds_b + u_ + (wn + 32 * b) * 16);                   \
+    } while (0)
+#define B2_MG(set, bi)                                                                                        \
+    do {                                                                                                      \
+        _Pragma("unroll") for (int bj = 0; bj < 4; ++bj)                                                      \
+            acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                            \
+                __builtin_bit_cast(bf16x8, fa[set][bi]), __builtin_bit_cast(bf16x8, fb[set][bj]),             \
+                acc[bi][bj], 0, 0, 0);                                                                        \
+    } while (0)
+#define B2_PIN() __builtin_amdgcn_sched_barrier(0)
+    // One slab.  The order is pinned: reads and loads sit in small pieces between groups of four MFMAs,
+    // each operand read a whole batch of 16 MFMAs ahead of its use.
+#define B2_ITER(st0, st1, st3)                                                             \
+    do {                                                                                   \
+        B2_DBASE();                                                                        \
+        B2_PIN();                                                                          \
+        B2_MG(0, 0);                                                                       \
+        B2_PIN();                                                                          \
+        B2_RA(st0, 1, 1);                                                                  \
+        B2_D1(st3, 0);                                                                     \
+        B2_PIN();                                                                          \
+        B2_MG(0, 1);                                                                       \
+        B2_PIN();                                                                          \
+        B2_RB(st0, 1, 1);                                                                  \
+        B2_D1(st3, 1);                                                                     \
+        B2_PIN();                                                                          \
+        B2_MG(0, 2);                                                                       \
+        B2_PIN();                                                                          \
+        B2_D1(st3, 2);                                                                     \
+        B2_PIN();                                                                          \
+        B2_MG(0, 3);                                                                       \
+        B2_PIN();                                                                          \
+        B2_D1(st3, 3);                                                                     \
+        B2_PIN();                                                                          \
+        B2_MG(1, 0);                                                                       \
+        B2_PIN();                                                                          \
+        B2_RA(st1, 0, 0);                                                                  \
+        B2_D1(st3, 4);                                                                     \
+        B2_PIN();                                                                          \
+        B2_MG(1, 1);                                                                       \
+        B2_PIN();                                                                          \
+        B2_RB(st1, 0, 0);                                                                  \
+        B2_D1(st3, 5);                                                                     \
+        B2_PIN();                                                                          \
+        B2_MG(1, 2);                                                                       \
+        B2_PIN();                                                                          \
+        B2_D1(st3, 6);                                                                     \
+        B2_D1(st3, 7);                                                                     \
+        B2_PIN();                                                                          \
+        B2_MG(1, 3);                                                                       \
+        B2_PIN();                                                                          \
+        __builtin_amdgcn_s_waitcnt(0x0F78); /* vmcnt(8): all but the newest slab landed */ \
+        __syncthreads();                                                                   \
+        B2_PIN();                                                                          \
     } while (0)
 
-    B2_D(0);
-    B2_D(1);
-    B2_D(2);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+        B2_DBASE();
+#pragma unroll
+        for (int w = 0; w < 8; ++w) B2_D1(q, w);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8): slabs 0 and 1 have landed
     __syncthreads();
-    B2_R(0, 0, 0);
-    for (int s = 0; s < niter; ++s) {
-        const int st0 = s & 3, st1 = (s + 1) & 3, st3 = (s + 3) & 3;
-        // The scheduling barriers pin this order: each batch of LDS reads is issued a whole batch
-        // of 16 MFMAs (512 cycles) before its data is needed; without them the compiler sinks the
-        // reads to just in front of their use and, with one wave per SIMD, nothing hides the latency.
-        B2_D(st3);
-        B2_R(st0, 1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        B2_M(0);
-        __builtin_amdgcn_sched_barrier(0);
-        B2_R(st1, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        B2_M(1);
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(0x0F78);  // everything but the newest slab (8 loads) has landed
-        __syncthreads();
+    B2_RA(0, 0, 0);
+    B2_RB(0, 0, 0);
+    int s = 0;
+    for (; s + 4 <= niter; s += 4) {
+        B2_ITER(0, 1, 3);
+        B2_ITER(1, 2, 0);
+        B2_ITER(2, 3, 1);
+        B2_ITER(3, 0, 2);
     }
+    const int rest = niter - s;  // s is a multiple of four: the stages continue at 0
+    if (rest > 0) B2_ITER(0, 1, 3);
+    if (rest > 1) B2_ITER(1, 2, 0);
+    if (rest > 2) B2_ITER(2, 3, 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing may still be writing LDS
-#undef B2_D
-#undef B2_R
-#undef B2_M
+#undef B2_DBASE
+#undef B2_D1
+#undef B2_RA
+#undef B2_RB
+#undef B2_MG
+#undef B2_PIN
+#undef B2_ITER
 
     // accumulator register r of lane (li, lh) in block (bi, bj): row 32 bi + 8 (r/4) + 4 lh + r%4, column 32 bj + li
     float *__restrict__ C = pr.factor;

@@ -324,6 +324,9 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         if ((reinterpret_cast<uintptr_t>(it.x) & (dtype == KFAC_BF16 ? 1 : 3)) || (reinterpret_cast<uintptr_t>(it.factor) & 3))
             return KFAC_ERR_ARG;
     }
+    if (dtype == KFAC_BF16)
+        for (int64_t i = 0; i < count; ++i)
+            if (items[i].d > (1 << 26)) return KFAC_ERR_UNSUPPORTED;  // packed rows are addressed with 32-bit byte offsets
     CurvPlan pl;
     if (!curvature_plan(items, count, dtype, pl)) return KFAC_ERR_ARG;
     if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;

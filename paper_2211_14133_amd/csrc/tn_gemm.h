@@ -885,7 +885,7 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const PackLaunch pl)
 // column count, pr.K = padded token count.  Same pipeline as the direct fp32
 // loop with the operand registers double-buffered per slab (a single fp32
 // accumulation level: the tolerance of the bfloat16 variant does not need two):
-//   iteration s:  D(s+3)  R(s+1)  M(s)  wait D(s+2)  barrier
+//   iteration s:  M(s) with R(s+1) and D(s+3) between its two k steps  wait D(s+2)  barrier
 __device__ inline void tn_mainloop_bf16_packed(const TnProblem &pr, const TnTile &tl,
                                                float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                                floatx16 (&sum)[2][2])
@@ -896,8 +896,6 @@ __device__ inline void tn_mainloop_bf16_packed(const TnProblem &pr, const TnTile
     const int li = lane & 31, lh = lane >> 5;
     const size_t row_bytes = (size_t)pr.lda * 16;  // one k-group of all columns
     const int groups = pr.K / BF_KG;
-    const char *ga = reinterpret_cast<const char *>(pr.A) + ((size_t)tl.m0 + lane) * 16;
-    const char *gb = reinterpret_cast<const char *>(pr.B) + ((size_t)tl.n0 + lane) * 16;
     const char *la = reinterpret_cast<const char *>(&As[0][0][0]);
     const char *lb = reinterpret_cast<const char *>(&Bs[0][0][0]);
     constexpr int STAGE_BYTES = BK * BM * 4;  // 8 KB
@@ -915,64 +913,101 @@ __device__ inline void tn_mainloop_bf16_packed(const TnProblem &pr, const TnTile
     int gd = (tl.kbase + tl.kt0 * BK) / BF_KG;  // first k-group of the next slab to request
     uint4 fa[2][2][2], fb[2][2][2];              // [register set][k step][block]
 
-    // wave w fetches k-group gd + w: columns 0..63 and 64..127 of the tile, for both operands
-#define BF_D(st)                                                                                            \
+    // Wave w fetches k-group gd + w: columns 0..63 and 64..127 of the tile, for both operands.  The
+    // address is a scalar base (the k-group row) plus a loop-invariant per-lane offset: no vector
+    // arithmetic in the loop (see tn_mainloop_direct).
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const char *xa = reinterpret_cast<const char *>(pr.A), *xb = reinterpret_cast<const char *>(pr.B);
+    const unsigned va = (unsigned)(((size_t)tl.m0 + lane) * 16), vb = (unsigned)(((size_t)tl.n0 + lane) * 16);
+    const unsigned la0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(const __attribute__((address_space(3))) char *)la) + wave_s * 2048;
+    const unsigned lb0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(const __attribute__((address_space(3))) char *)lb) + wave_s * 2048;
+    size_t soff = 0;  // byte offset of the k-group row being requested (wave-uniform)
+#define BF_DBASE()                                                                                          \
     do {                                                                                                    \
-        const size_t off_ = (size_t)min(gd + wave, groups - 1) * row_bytes;                                 \
-        const int ld_ = (st) * STAGE_BYTES + wave * 2048;                                                   \
-        tn_dma16(reinterpret_cast<const float *>(ga + off_), reinterpret_cast<const float *>(la + ld_));    \
-        tn_dma16(reinterpret_cast<const float *>(ga + off_ + 1024), reinterpret_cast<const float *>(la + ld_ + 1024)); \
-        tn_dma16(reinterpret_cast<const float *>(gb + off_), reinterpret_cast<const float *>(lb + ld_));    \
-        tn_dma16(reinterpret_cast<const float *>(gb + off_ + 1024), reinterpret_cast<const float *>(lb + ld_ + 1024)); \
+        soff = (size_t)min(gd + wave_s, groups - 1) * row_bytes;                                            \
         gd += BF_SLAB_GROUPS;                                                                               \
     } while (0)
+#define BF_D1(st, w)                                                                                                              \
+    do {                                                                                                                          \
+        if ((w) == 0) tn_dma16_s(reinterpret_cast<const float *>(xa + soff), va, la0 + (st) * STAGE_BYTES);                       \
+        if ((w) == 1) tn_dma16_s(reinterpret_cast<const float *>(xa + soff + 1024), va, la0 + (st) * STAGE_BYTES + 1024);         \
+        if ((w) == 2) tn_dma16_s(reinterpret_cast<const float *>(xb + soff), vb, lb0 + (st) * STAGE_BYTES);                       \
+        if ((w) == 3) tn_dma16_s(reinterpret_cast<const float *>(xb + soff + 1024), vb, lb0 + (st) * STAGE_BYTES + 1024);         \
+    } while (0)
     // lane (li, lh) feeds columns 2*li, 2*li+1 of the wave tile with k-group 2t + lh
+#define BF_RT(st, set, t)                                                                                   \
+    do {                                                                                                    \
+        const int u_ = (st) * STAGE_BYTES + ((2 * (t) + lh) * 128 + 2 * li) * 16;                           \
+        fa[set][t][0] = *reinterpret_cast<const uint4 *>(la + u_ + wm * 16);                                \
+        fa[set][t][1] = *reinterpret_cast<const uint4 *>(la + u_ + wm * 16 + 16);                           \
+        fb[set][t][0] = *reinterpret_cast<const uint4 *>(lb + u_ + wn * 16);                                \
+        fb[set][t][1] = *reinterpret_cast<const uint4 *>(lb + u_ + wn * 16 + 16);                           \
+    } while (0)
 #define BF_R(st, set)                                                                                       \
     do {                                                                                                    \
-        _Pragma("unroll") for (int t = 0; t < 2; ++t) {                                                     \
-            const int u_ = (st) * STAGE_BYTES + ((2 * t + lh) * 128 + 2 * li) * 16;                         \
-            fa[set][t][0] = *reinterpret_cast<const uint4 *>(la + u_ + wm * 16);                            \
-            fa[set][t][1] = *reinterpret_cast<const uint4 *>(la + u_ + wm * 16 + 16);                       \
-            fb[set][t][0] = *reinterpret_cast<const uint4 *>(lb + u_ + wn * 16);                            \
-            fb[set][t][1] = *reinterpret_cast<const uint4 *>(lb + u_ + wn * 16 + 16);                       \
-        }                                                                                                   \
+        BF_RT(st, set, 0);                                                                                  \
+        BF_RT(st, set, 1);                                                                                  \
     } while (0)
-#define BF_M(set)                                                                                           \
+#define BF_MT(set, t)                                                                                       \
     do {                                                                                                    \
-        _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                       \
-            _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                                \
-                _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                            \
-                    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                  \
-                        __builtin_bit_cast(bf16x8, fa[set][t][bi]), __builtin_bit_cast(bf16x8, fb[set][t][bj]), \
-                        acc[bi][bj], 0, 0, 0);                                                              \
+        _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                                    \
+            _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                                \
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                      \
+                    __builtin_bit_cast(bf16x8, fa[set][t][bi]), __builtin_bit_cast(bf16x8, fb[set][t][bj]), \
+                    acc[bi][bj], 0, 0, 0);                                                                  \
     } while (0)
-#define BF_ITER(s_, cur, nxt)                                                                               \
+#define BF_PIN() __builtin_amdgcn_sched_barrier(0)
+    // slab in stage st (register set cur); reads slab st+1 into set nxt, requests into stage st+3
+#define BF_ITER(st, cur, nxt)                                                                               \
     do {                                                                                                    \
-        BF_D(((s_) + 3) & 3);                                                                               \
-        BF_R(((s_) + 1) & 3, nxt);                                                                          \
-        __builtin_amdgcn_sched_barrier(0); /* keep the reads of the next slab ahead of these MFMAs */       \
-        BF_M(cur);                                                                                          \
-        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        BF_DBASE();                                                                                         \
+        BF_PIN();                                                                                           \
+        BF_MT(cur, 0);                                                                                      \
+        BF_PIN();                                                                                           \
+        BF_RT(((st) + 1) & 3, nxt, 0);                                                                      \
+        BF_D1(((st) + 3) & 3, 0);                                                                           \
+        BF_D1(((st) + 3) & 3, 1);                                                                           \
+        BF_PIN();                                                                                           \
+        BF_MT(cur, 1);                                                                                      \
+        BF_PIN();                                                                                           \
+        BF_RT(((st) + 1) & 3, nxt, 1);                                                                      \
+        BF_D1(((st) + 3) & 3, 2);                                                                           \
+        BF_D1(((st) + 3) & 3, 3);                                                                           \
+        BF_PIN();                                                                                           \
         __builtin_amdgcn_s_waitcnt(0x0F74); /* vmcnt(4): all but the newest slab has landed */              \
         __syncthreads();                                                                                    \
+        BF_PIN();                                                                                           \
     } while (0)
 
-    BF_D(0);
-    BF_D(1);
-    BF_D(2);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+        BF_DBASE();
+        BF_D1(q, 0);
+        BF_D1(q, 1);
+        BF_D1(q, 2);
+        BF_D1(q, 3);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F74);
     __syncthreads();
     BF_R(0, 0);
     int s = 0;
-    for (; s + 1 < niter; s += 2) {
-        BF_ITER(s, 0, 1);
-        BF_ITER(s + 1, 1, 0);
+    for (; s + 4 <= niter; s += 4) {
+        BF_ITER(0, 0, 1);
+        BF_ITER(1, 1, 0);
+        BF_ITER(2, 0, 1);
+        BF_ITER(3, 1, 0);
     }
-    if (s < niter) BF_ITER(s, 0, 1);
+    const int rest = niter - s;  // s is a multiple of four: stages and register sets continue at 0
+    if (rest > 0) BF_ITER(0, 0, 1);
+    if (rest > 1) BF_ITER(1, 1, 0);
+    if (rest > 2) BF_ITER(2, 0, 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-#undef BF_D
+#undef BF_DBASE
+#undef BF_D1
+#undef BF_RT
+#undef BF_MT
+#undef BF_PIN
 #undef BF_R
-#undef BF_M
 #undef BF_ITER
 #pragma unroll
     for (int i = 0; i < 2; ++i)
