@@ -21,9 +21,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_F32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 # HBM traffic of one curvature launch of the default workload, from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (None = not measured).
-CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 11.17e9  # profiles/curvature_syrk_pmc.txt: 10.08 GB fetched + 1.09 GB written
+CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 15.05e9  # profiles/curvature_syrk_pmc.txt: 13.96 GB fetched + 1.09 GB written
 
 
 def parse():
@@ -64,8 +65,8 @@ def main():
         print(json.dumps({"copy_calibration_bytes": src.numel() * 4, "copies": 3}))
         return
     cfg = synth.CONFIGS[args.config]
-    if cfg["bf16"]:
-        raise SystemExit("the bf16-input workload is not a benchmark configuration")
+    bf16 = bool(cfg["bf16"])  # activations / errors in bfloat16 (the stress workload); everything else fp32
+    in_dtype = binding.KFAC_BF16 if bf16 else binding.KFAC_F32
     tokens, n_micro, blocks = cfg["tokens"], cfg["n_micro"], cfg["blocks"]
     damping = synth.DAMPING
     gen = torch.Generator(device=dev)
@@ -84,9 +85,11 @@ def main():
                 if gelu:
                     x = torch.nn.functional.gelu(x)
                 e = torch.randn(tokens, d_out, device=dev, generator=gen) * 1e-3
+                if bf16:
+                    x, e = x.to(torch.bfloat16), e.to(torch.bfloat16)
                 xs[m].append(x)
                 xs[m].append(e)
-                g.addmm_(e.t(), x, alpha=1.0 / (tokens * n_micro))
+                g.addmm_(e.float().t(), x.float(), alpha=1.0 / (tokens * n_micro))
             grads.append(g)
             outs.append(torch.empty_like(g))
             facs.append(torch.empty(d_in, d_in, device=dev))
@@ -101,7 +104,7 @@ def main():
     inv_items = binding._inv_items(facs, invs, infos)
     prec_items = binding._prec_items(b_invs, a_invs, grads, outs)
     nfac, nlay = len(facs), len(grads)
-    ws_bytes = max(lib.kfac_curvature_grouped_workspace(curv_items[0], nfac, binding.KFAC_F32),
+    ws_bytes = max(lib.kfac_curvature_grouped_workspace(curv_items[0], nfac, in_dtype),
                    lib.kfac_invert_batched_workspace(inv_items, nfac),
                    lib.kfac_precondition_grouped_workspace(prec_items, nlay))
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
@@ -123,7 +126,7 @@ def main():
         for m in range(n_micro):
             if events is not None:
                 events["c0"][m].record(stream)
-            check(lib.kfac_curvature_grouped(curv_items[m], nfac, binding.KFAC_F32, alpha,
+            check(lib.kfac_curvature_grouped(curv_items[m], nfac, in_dtype, alpha,
                                              0.0 if m == 0 else 1.0, wsp, ws_bytes, sp))
             if events is not None:
                 events["c1"][m].record(stream)
@@ -171,6 +174,7 @@ def main():
     f_prec = sum(2 * do * di * (di + do) for (di, do) in layers)
     f_total = f_curv + f_inv + f_prec
     achieved = f_curv_launch / (launch_ms * 1e-3) / 1e12
+    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_F32_MFMA_TFLOPS
 
     # what the matrix cores sustain on this chip with nothing else in the way (register-only MFMA loop)
     sink = torch.zeros(64, dtype=torch.float32, device=dev)
@@ -179,7 +183,7 @@ def main():
     for _ in range(4):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        check(lib.kfac_mfma_probe(binding.KFAC_F32, 4000, ctypes.c_void_p(sink.data_ptr()),
+        check(lib.kfac_mfma_probe(in_dtype, 4000, ctypes.c_void_p(sink.data_ptr()),
                                   ctypes.byref(probe_flops), sp))
         e1.record(stream)
         torch.cuda.synchronize()
@@ -187,7 +191,7 @@ def main():
     measured_peak = probe_flops.value / (min(probe_ms[1:]) * 1e-3) / 1e12
 
     result = {
-        "metric": "kfac_step_ms_bert_large_stage (curvature + inversion + precondition)",
+        "metric": "kfac_step_ms_%s (curvature + inversion + precondition)" % cfg["name"].replace("-", "_"),
         "value": round(ms_per_step, 3),
         "unit": "ms",
         "n_gpus": 1,
@@ -197,11 +201,12 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
         "config": {
-            "workload": "%s: %d blocks x %d linears, %d micro-batches x %d tokens, fp32, damping %g"
-                        % (cfg["name"], blocks, len(cfg["layers"]), n_micro, tokens, damping),
+            "workload": "%s: %d blocks x %d linears, %d micro-batches x %d tokens, %s, damping %g"
+                        % (cfg["name"], blocks, len(cfg["layers"]), n_micro, tokens,
+                           "bf16 activations and errors, fp32 factors / inverses / gradients" if bf16 else "fp32", damping),
             "factors": nfac,
             "layers": nlay,
         },
@@ -213,13 +218,14 @@ def main():
             "precondition": round(f_prec / (prec_ms * 1e-3) / 1e12, 2),
         },
         "roofline": {
-            "kernel": "curvature_syrk_kernel (one launch = all %d factors of the stage for one micro-batch)" % nfac,
+            "kernel": "%s (one launch = all %d factors of the stage for one micro-batch)"
+                      % ("pack_bf16_kernel + curvature_syrk_bf16_256_kernel" if bf16 else "curvature_syrk_kernel", nfac),
             "bound": "mfma",
             "achieved": round(achieved, 2),
-            "peak": PEAK_F32_MFMA_TFLOPS,
+            "peak": peak,
             "unit": "TFLOP/s",
-            "frac": round(achieved / PEAK_F32_MFMA_TFLOPS, 4),
-            "traffic": CURVATURE_TRAFFIC_BYTES_PER_LAUNCH,
+            "frac": round(achieved / peak, 4),
+            "traffic": CURVATURE_TRAFFIC_BYTES_PER_LAUNCH if args.config == 4 else None,
             "measured_mfma_peak": round(measured_peak, 1),
             "frac_of_measured_peak": round(achieved / measured_peak, 4),
             "launch_ms": round(launch_ms, 4),
@@ -239,8 +245,10 @@ def cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping, f_curv, f_inv
 
     # sample: every linear of the first two encoder blocks (or of the only one), micro-batch 0
     nl = len(cfg["layers"]) * min(2, cfg["blocks"])
-    hx = [xs[0][2 * i].cpu().numpy() for i in range(nl)]
-    he = [xs[0][2 * i + 1].cpu().numpy() for i in range(nl)]
+    if cfg["bf16"]:
+        nl = 4  # the attention linears only: the oracle needs minutes for one 8192-dimensional factor
+    hx = [xs[0][2 * i].float().cpu().numpy() for i in range(nl)]
+    he = [xs[0][2 * i + 1].float().cpu().numpy() for i in range(nl)]
     hg = [grads[i].cpu().numpy() for i in range(nl)]
     t0 = time.perf_counter()
     fa = [oracle.curvature_update(x, 1.0 / tokens, 0.0) for x in hx]
