@@ -32,7 +32,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4, help="workload id (4 = BERT-Large stage, the headline)")
+    ap.add_argument("--config", type=int, default=4, help="workload id (4 = BERT-Large stage, the headline; 2, 3: one block; 5: bf16 stress block; "
+                         "6, 7: BERT-Large-shaped block with 16384 / 65536 tokens)")
     ap.add_argument("--seed", type=int, default=221114133)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -231,6 +232,24 @@ def main():
             "launch_ms": round(launch_ms, 4),
             "flops_per_launch": f_curv_launch,
         },
+    }
+
+    # Section 3.3 of the paper with the measured K-FAC times.  T_f and T_b are NOT measured (no model is
+    # run here): they are the stage's forward GEMM flops at the rate this engine reaches on the
+    # precondition products, and twice that.
+    f_fwd = sum(2 * tokens * di * do for (di, do) in layers)
+    t_f = f_fwd / (f_prec / (prec_ms * 1e-3)) * 1e3
+    t_b = 2.0 * t_f
+    depth = 4
+    c = n_micro + depth - 1
+    model = binding.kfac_perf_model(c, c, t_f, t_b, n_micro, curv_ms / n_micro, inv_ms, prec_ms)
+    result["pipefisher_model"] = {
+        "assumed": "GPipe, depth %d, %d micro-batches (C_f = C_b = %d); T_f = forward GEMM flops of the stage / "
+                   "measured precondition rate, T_b = 2 T_f (not measured)" % (depth, n_micro, c),
+        "t_f_ms": round(t_f, 3), "t_b_ms": round(t_b, 3),
+        "t_pipe_ms": round(model["t_pipe"], 3), "t_bubble_ms": round(model["t_bubble"], 3),
+        "t_kfac_ms": round(model["t_kfac"], 3),
+        "curvature_plus_inversion_over_bubble": round(model["ratio"], 3),
     }
 
     if not args.no_cpu_baseline:

@@ -105,6 +105,10 @@ CONFIGS = {
     3: dict(name="bert-large-block", layers=block_layers(1024, 4096), blocks=1, tokens=4096, n_micro=1, bf16=False),
     4: dict(name="bert-large-stage", layers=block_layers(1024, 4096), blocks=6, tokens=4096, n_micro=8, bf16=False),
     5: dict(name="stress-2048-8192", layers=block_layers(2048, 8192), blocks=1, tokens=8192, n_micro=1, bf16=True),
+    # the longer sequences of the paper's table of performance-model figures (appendix): same layer
+    # shapes as BERT-Large, 32 sequences of 512 (T5-Large) and of 2048 (OPT-350M) tokens per micro-batch
+    6: dict(name="t5-large-block-s512", layers=block_layers(1024, 4096), blocks=1, tokens=16384, n_micro=1, bf16=False),
+    7: dict(name="opt-350m-block-s2048", layers=block_layers(1024, 4096), blocks=1, tokens=65536, n_micro=1, bf16=False),
 }
 
 

@@ -111,3 +111,45 @@ def test_stage_full_size(oracle):
         ep = oracle.rel_fro(outs[li].cpu().numpy(), op)
         print("  A %.2e  B %.2e  A^-1 %.2e  P %.2e" % (ea, eb, eai, ep), flush=True)
         assert ea <= 1e-4 and eb <= 1e-4 and ep <= 5e-3
+
+
+def test_curvature_long_sequence(oracle):
+    """The longest micro-batch of the paper's performance-model table (32 x 2048 = 65,536 tokens) at the
+    BERT-Large factor sizes: the whole 1024-dimensional factor against the oracle, sampled entries
+    of the 4096-dimensional one, and the split into two halves of the tokens."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2211_14133_amd as k
+
+    cfg = synth.CONFIGS[7]
+    n = cfg["tokens"]
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.SEED + 7)
+    xs = [torch.randn(n, 1024, device=dev, generator=gen),
+          torch.nn.functional.gelu(torch.randn(n, 4096, device=dev, generator=gen))]
+    facs = [torch.empty(1024, 1024, device=dev), torch.empty(4096, 4096, device=dev)]
+    k.kfac_curvature_grouped(xs, facs, 1.0 / n, 0.0)
+    torch.cuda.synchronize()
+    want = oracle.curvature(xs[0].cpu().numpy())
+    err = oracle.rel_fro(facs[0].cpu().numpy(), want)
+    print("  d=1024, 65536 tokens: %.2e" % err, flush=True)
+    assert err <= 1e-6
+    rng = np.random.default_rng(11)
+    scale = float(facs[1].diagonal().abs().max())
+    worst = 0.0
+    for _ in range(6):
+        i, j = int(rng.integers(4096)), int(rng.integers(4096))
+        cols = xs[1][:, [i, j]].cpu().numpy()
+        w = oracle.curvature_entry(cols, 0, 1, 1.0 / n)
+        got = float(facs[1][i, j])
+        assert got == float(facs[1][j, i])
+        worst = max(worst, abs(got - w) / scale)
+    print("  d=4096 sampled entries: %.2e" % worst, flush=True)
+    assert worst <= 1e-5
+    # the same factor from two calls on halves of the tokens (a work item cut to a bubble's length)
+    f2 = torch.empty_like(facs[0])
+    k.kfac_curvature(xs[0][: n // 2], f2, 1.0 / n, 0.0)
+    k.kfac_curvature(xs[0][n // 2:], f2, 1.0 / n, 1.0)
+    torch.cuda.synchronize()
+    assert oracle.rel_fro(f2.cpu().numpy(), want) <= 1e-6
