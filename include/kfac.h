@@ -70,7 +70,11 @@ typedef enum {
  * alpha   1 / (tokens in the whole mini-batch); beta = 0 for the first
  *         micro-batch of a refresh, 1 for the following ones.
  * The sum over tokens is accumulated in fp32 in short chunks that are then
- * added up, so the rounding error does not grow with n_tokens.
+ * added up, so the rounding error does not grow with n_tokens (float32 input;
+ * the bfloat16 variant keeps one fp32 accumulation level per call).
+ * bfloat16 input is first repacked into the workspace (its size is part of
+ * what the workspace query returns).  Limits: sizes must fit in 31 bits;
+ * d <= 2^26 for bfloat16 input (KFAC_ERR_UNSUPPORTED beyond).
  */
 kfac_status kfac_curvature(const void *x, kfac_dtype dtype, int64_t n_tokens, int64_t d, int64_t ldx,
                            float alpha, float beta, float *factor, int64_t ldf,
@@ -110,6 +114,7 @@ size_t kfac_curvature_grouped_workspace(const kfac_curvature_item *items, int64_
  *           of the decomposition was not positive (matrix not positive
  *           definite); -1 the input held a non-finite value.  When it is not 0
  *           `inv` is left untouched.
+ * Limit: d <= 32640 (255 panels of 128; KFAC_ERR_UNSUPPORTED beyond).
  */
 kfac_status kfac_invert(const float *factor, int64_t d, int64_t ldf, float damping,
                         float *inv, int64_t ldi, int32_t *info_dev,
