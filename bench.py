@@ -30,8 +30,8 @@ CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 15.05e9  # profiles/curvature_syrk_pmc.txt:
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload id (4 = BERT-Large stage, the headline; 2, 3: one block; 5: bf16 stress block; "
                          "6, 7: BERT-Large-shaped block with 16384 / 65536 tokens)")
     ap.add_argument("--seed", type=int, default=221114133)
@@ -156,16 +156,22 @@ def main():
     if int(infos.abs().max().item()) != 0:
         raise RuntimeError("an inversion reported failure: %s" % infos.tolist())
 
-    curv_launch_ms, curv_ms, inv_ms, prec_ms = [], 0.0, 0.0, 0.0
+    curv_launch_ms, per_step = [], {"curvature": [], "inversion": [], "precondition": [], "step": []}
     for ev in all_events:
         for m in range(n_micro):
             curv_launch_ms.append(ev["c0"][m].elapsed_time(ev["c1"][m]))
-        curv_ms += ev["t0"].elapsed_time(ev["c1"][n_micro - 1])
-        inv_ms += ev["c1"][n_micro - 1].elapsed_time(ev["t2"])
-        prec_ms += ev["t2"].elapsed_time(ev["t3"])
-    curv_ms /= args.steps
-    inv_ms /= args.steps
-    prec_ms /= args.steps
+        per_step["curvature"].append(ev["t0"].elapsed_time(ev["c1"][n_micro - 1]))
+        per_step["inversion"].append(ev["c1"][n_micro - 1].elapsed_time(ev["t2"]))
+        per_step["precondition"].append(ev["t2"].elapsed_time(ev["t3"]))
+        per_step["step"].append(ev["t0"].elapsed_time(ev["t3"]))
+    curv_ms = sum(per_step["curvature"]) / args.steps
+    inv_ms = sum(per_step["inversion"]) / args.steps
+    prec_ms = sum(per_step["precondition"]) / args.steps
+
+    def median(v):
+        v = sorted(v)
+        return 0.5 * (v[(len(v) - 1) // 2] + v[len(v) // 2])
+
     launch_ms = sum(curv_launch_ms) / len(curv_launch_ms)
 
     # ------------------------------------------------- algorithmic work (useful flops)
@@ -174,6 +180,10 @@ def main():
     f_inv = sum(d ** 3 for (di, do) in layers for d in (di, do))
     f_prec = sum(2 * do * di * (di + do) for (di, do) in layers)
     f_total = f_curv + f_inv + f_prec
+    in_bytes = 2 if bf16 else 4
+    b_curv = sum(n_micro * tokens * d * in_bytes + (2 * n_micro - 1) * 4 * d * d for (di, do) in layers for d in (di, do))
+    b_inv = sum(2 * 4 * d * d for (di, do) in layers for d in (di, do))
+    b_prec = sum(4 * (do * do + di * di + 2 * do * di) for (di, do) in layers)
     achieved = f_curv_launch / (launch_ms * 1e-3) / 1e12
     peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_F32_MFMA_TFLOPS
 
@@ -213,6 +223,14 @@ def main():
         },
         "useful_tflops": round(f_total / (ms_per_step * 1e-3) / 1e12, 2),
         "phases_ms": {"curvature": round(curv_ms, 3), "inversion": round(inv_ms, 3), "precondition": round(prec_ms, 3)},
+        "phases_ms_median": {k2: round(median(v), 3) for k2, v in per_step.items()},
+        "phases_ms_min": {k2: round(min(v), 3) for k2, v in per_step.items()},
+        # minimum bytes each phase has to move (inputs once, factors / inverses / gradients read and written once)
+        "phases_min_traffic_gbps": {
+            "curvature": round(b_curv / (curv_ms * 1e-3) / 1e9, 1),
+            "inversion": round(b_inv / (inv_ms * 1e-3) / 1e9, 1),
+            "precondition": round(b_prec / (prec_ms * 1e-3) / 1e9, 1),
+        },
         "phases_useful_tflops": {
             "curvature": round(f_curv / (curv_ms * 1e-3) / 1e12, 2),
             "inversion": round(f_inv / (inv_ms * 1e-3) / 1e12, 2),

@@ -609,22 +609,10 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
         for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
 }
 
-// 16 bytes per lane from global memory straight into LDS: lane l's data lands
-// at lds_row + 16 * l (lds_row must be the same for the whole wave).
-__device__ inline void tn_dma16(const float *gptr, const float *lds_row)
-{
-    // byte offset in LDS; the same for every lane of the wave, so it can live in a scalar register
-    const unsigned lds_addr = __builtin_amdgcn_readfirstlane(
-        (unsigned)(size_t)(const __attribute__((address_space(3))) float *)lds_row);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(gptr), "s"(lds_addr)
-                 : "memory", "m0");
-}
-
-// Same with the address split into a wave-uniform base (scalar registers) and a 32-bit
-// per-lane byte offset: the K loop then advances the base with scalar arithmetic and needs no
-// vector instruction per load.
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at
+// lds_addr + 16 * l (lds_addr, a byte address in LDS, is the same for the whole wave).  The global
+// address is a wave-uniform base (scalar registers) plus a 32-bit per-lane byte offset: a K loop
+// advances the base with scalar arithmetic and needs no vector instruction per load.
 __device__ inline void tn_dma16_s(const float *sbase, unsigned voff, unsigned lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
