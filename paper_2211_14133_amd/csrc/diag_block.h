@@ -95,6 +95,7 @@ __device__ inline void sb_store(diag_floatx16 acc, float (*C)[LDT], int cm0, int
 // Ss and its mirror below); nothing is read back and there is no barrier inside.  Returns the 1-based local index of the first bad pivot, or 0.
 __device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o, int lane)
 {
+    __shared__ float dump[2 * SB];  // where the lanes that do not hold row j put their (meaningless) stores
     const int c = lane & 31, h = lane >> 5;
     diag_floatx16 T, V;
 #pragma unroll
@@ -103,36 +104,50 @@ __device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o
         T[r] = (i <= c) ? Fs[o + i][o + c] : Fs[o + c][o + i];
         V[r] = (i == c) ? 1.f : 0.f;
     }
-    int bad = 0;
+    // Row j lives in the lanes of half hj = (j / 4) % 2.  Everything that depends on "is this my row"
+    // is prepared here for both parities, so that a step has no address or mask arithmetic: store
+    // addresses are a base plus an immediate, and the other half's values are multiplied by zero.
+    float *uF[2], *wS[2], *vS[2];
+    float keep[2];
+#pragma unroll
+    for (int hp = 0; hp < 2; ++hp) {
+        const bool mine = (h == hp);
+        uF[hp] = mine ? &Fs[o][o + c] : &Fs[o][NB];      // + j rows:     U[j][c]
+        wS[hp] = mine ? &Ss[o + c][o] : &dump[c];        // + j elements: W[c][j] (the mirror)
+        vS[hp] = mine ? &Ss[o][o + c] : &Ss[o][NB + 1];  // + j rows:     W^T[j][c]
+        keep[hp] = mine ? 1.f : 0.f;
+    }
+    // The 32 steps are one dependent chain (MFMA on T -> pivot -> scale -> MFMA on T), so the order
+    // is pinned: first what the next MFMA on T needs, then the update of V, which runs in the shadow
+    // of the chain.  Pivots are not checked inside the loop; a pivot that is not positive makes its
+    // U[j][j] (= sqrt of the pivot) a NaN, and so everything after it, which is tested at the end
+    // (the caller discards the result of a failed matrix).
 #pragma unroll
     for (int j = 0; j < SB; ++j) {
         const int hj = (j >> 2) & 1, rj = 4 * (j >> 3) + (j & 3);  // row j lives in half hj, register rj
-        float piv = diag_bcast(T[rj], j + 32 * hj);
-        if (!(piv > 0.f) || !(piv <= 3.0e38f)) {
-            if (bad == 0) bad = j + 1;
-            piv = 1.f;
-        }
-        float rinv = __builtin_amdgcn_rsqf(piv);
-        rinv = rinv * (1.5f - 0.5f * piv * rinv * rinv);  // one Newton step: full fp32 accuracy
-        const bool mine = (h == hj);
-        const float u = T[rj] * rinv;     // U[j][c] in the lanes of half hj
-        const float vrow = V[rj] * rinv;  // row j of U^-T = column j of W, final
-        // The lanes of the other half write to the padding columns instead of branching.
-        // All 32 columns are stored: the entries on the wrong side of the diagonal are
+        const float piv = diag_bcast(T[rj], j + 32 * hj);
+        const float rinv = __builtin_amdgcn_rsqf(piv) * keep[hj];  // v_rsq_f32 is accurate to one ulp
+        const float u = T[rj] * rinv;            // U[j][c] in the lanes of half hj, 0 in the others
+        const float au = (c > j) ? -u : 0.f;     // rows below j are eliminated
+        __builtin_amdgcn_sched_barrier(0);
+        T = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, T, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        const float vrow = V[rj] * rinv;         // row j of U^-T = column j of W, final
+        // All 32 columns of the row are stored: the entries on the wrong side of the diagonal are
         // either unused (Fs) or exact zeros that a later step overwrites (Ss).
-        float *ud = mine ? &Fs[o + j][o + c] : &Fs[o + j][NB];
-        float *wd = mine ? &Ss[o + c][o + j] : &Ss[o + j][NB];
-        float *vd = mine ? &Ss[o + j][o + c] : &Ss[o + j][NB + 1];
-        *ud = u;
-        *wd = vrow;
-        *vd = vrow;
-        const float au = (mine && c > j) ? -u : 0.f;  // rows below j are eliminated
-        const float bt = mine ? u : 0.f;
-        const float bv = mine ? vrow : 0.f;
-        T = __builtin_amdgcn_mfma_f32_32x32x2f32(au, bt, T, 0, 0, 0);
-        V = __builtin_amdgcn_mfma_f32_32x32x2f32(au, bv, V, 0, 0, 0);
+        uF[hj][j * LDT] = u;
+        wS[hj][j] = vrow;
+        vS[hj][j * LDT] = vrow;
+        __builtin_amdgcn_sched_barrier(0);
+        V = __builtin_amdgcn_mfma_f32_32x32x2f32(au, vrow, V, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
         // row j of V stays unscaled in the accumulator; it is never read again
     }
+    // first pivot whose square root is not a positive finite number
+    const float ujj = Fs[o + c][o + c];
+    const unsigned long long ok = __ballot(ujj > 0.f && ujj <= 3.0e38f);
+    const unsigned fail = ~(unsigned)ok;
+    const int bad = fail ? __builtin_ctz(fail) + 1 : 0;
     return bad;
 }
 
@@ -144,13 +159,13 @@ __device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o
 // sub-block, MFMA products for the panel solve, the trailing update and the
 // pairwise merges of the triangular inverse.  A block smaller than NB is padded
 // with the identity.  A pivot that is not positive (or not finite) is recorded
-// in *info as its 1-based index in the whole matrix (first failure wins) and
-// replaced by 1 so that the arithmetic stays finite; the caller discards the
+// in *info as its 1-based index in the whole matrix (first failure wins); what
+// follows it in that matrix is not meaningful (NaNs) and the caller discards the
 // result.
 __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaunch dl)
 {
-    __shared__ float Fs[NB][LDT];  // U above the diagonal, its mirror below
-    __shared__ float Ss[NB][LDT];  // W = U^-1 above the diagonal, its mirror below
+    __shared__ __attribute__((aligned(16))) float Fs[NB][LDT];  // U above the diagonal, its mirror below
+    __shared__ __attribute__((aligned(16))) float Ss[NB][LDT];  // W = U^-1 above the diagonal, its mirror below
 
     const DiagItem &it = dl.it[blockIdx.x];
     const int n = it.n;
@@ -180,9 +195,11 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int c = c4 + t;
-                Fs[r][c] = (r <= c || r >= n || c >= n) ? e[t] : 0.f;
-                Ss[r][c] = 0.f;
+                e[t] = (r <= c || r >= n || c >= n) ? e[t] : 0.f;
             }
+            // rows of Fs / Ss are 16-byte aligned (LDT * 4 = 528 bytes)
+            *reinterpret_cast<float4 *>(&Fs[r][c4]) = make_float4(e[0], e[1], e[2], e[3]);
+            *reinterpret_cast<float4 *>(&Ss[r][c4]) = make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
     __syncthreads();
@@ -216,9 +233,9 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
 #pragma unroll
         for (int q = 0; q < NB / 8; ++q) {
             const int r = r0 + 8 * q;
-            if (n == NB && c4 >= r) {  // whole float4 on or above the diagonal
-                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) =
-                    make_float4(Fs[r][c4], Fs[r][c4 + 1], Fs[r][c4 + 2], Fs[r][c4 + 3]);
+            if (n == NB) {
+                // whole rows: what lands below the diagonal of this block (mirrors, zeros) is never read
+                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) = *reinterpret_cast<const float4 *>(&Fs[r][c4]);
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
@@ -228,7 +245,10 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
             }
         }
     }
-    __syncthreads();
+    // LDS-only barrier: the merges below overwrite Fs, so every wave must have read what it stores, but
+    // nobody has to wait for the global stores themselves (__syncthreads would drain them: 3 us)
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
     // Phase 2: W = U^-1 by pairwise merges, [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
     for (int b = SB; b < NB; b *= 2) {
         const int nodes = NB / (2 * b), sub = b / SB;       // sub x sub output sub-blocks per node
@@ -256,8 +276,7 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
         for (int q = 0; q < NB / 8; ++q) {
             const int r = r0 + 8 * q;
             if (n == NB) {
-                *reinterpret_cast<float4 *>(&it.S[(size_t)r * it.lds + c4]) =
-                    make_float4(Ss[r][c4], Ss[r][c4 + 1], Ss[r][c4 + 2], Ss[r][c4 + 3]);
+                *reinterpret_cast<float4 *>(&it.S[(size_t)r * it.lds + c4]) = *reinterpret_cast<const float4 *>(&Ss[r][c4]);
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
