@@ -13,9 +13,11 @@
 //
 // Tiling: a 256-thread workgroup (4 wave64) owns a 128 x 128 tile of C; each
 // wave owns 64 x 64 as 2 x 2 MFMA 32x32x2 blocks (64 accumulator registers).
-// K advances in slabs of 16 through double-buffered LDS with register prefetch.
-// The token sum is folded into a second accumulator every CHUNK slabs, so the
-// fp32 rounding error grows with the chunk length, not with K.
+// K advances in slabs of 16 through a ring of LDS stages: straight from global
+// memory into LDS for aligned unmasked tiles (tn_mainloop_direct), through staging
+// registers with a fix-up for ragged or masked ones (tn_mainloop).
+// The token sum is folded into a second accumulator every TN_CHUNK_SLABS slabs, so
+// the fp32 rounding error grows with the chunk length, not with K.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
