@@ -119,3 +119,13 @@ def test_plan_and_host_functions_reject_bad_arguments():
     assert lib.kfac_invert_plan_run(None, 1, None) == 1
     assert lib.kfac_perf_model(1.0, 1.0, 1.0, 1.0, 0, 1.0, 1.0, 1.0, None) == 1
     assert lib.kfac_assign_work(0, None, None, 1.0, 0, None, None, None, None, None, None, None, None, None) == 1
+
+
+def test_mfma_probe_rejects_bad_arguments():
+    lib = binding.load()
+    flops = ctypes.c_double(0.0)
+    fake = ctypes.c_void_p(256)  # never dereferenced: every call below fails before a launch
+    assert lib.kfac_mfma_probe(binding.KFAC_F32, 10, None, ctypes.byref(flops), None) == 1
+    assert lib.kfac_mfma_probe(binding.KFAC_F32, 10, fake, None, None) == 1
+    assert lib.kfac_mfma_probe(binding.KFAC_F32, 0, fake, ctypes.byref(flops), None) == 1
+    assert lib.kfac_mfma_probe(7, 10, fake, ctypes.byref(flops), None) == 1

@@ -542,3 +542,13 @@ def test_curvature_bf16_large_tiles(k, oracle):
     print("bf16 large tiles rel_fro %.3g" % err, flush=True)
     assert err <= BF16_FACTOR_TOL and err <= 2e-6
     assert np.array_equal(host(f), host(f).T)
+
+
+def test_mfma_probe_reports_its_work(k):
+    """The measurement aid runs, leaves its sink alone and reports 4096 / 32768 flops per MFMA."""
+    sink = torch.zeros(64, device="cuda")
+    for code, per_mfma in ((0, 4096.0), (1, 32768.0)):
+        flops = k.kfac_mfma_probe(code, 50, sink)
+        torch.cuda.synchronize()
+        assert flops == 256 * 2 * 8 * 4 * 50 * 8 * per_mfma
+    assert float(sink.abs().max()) == 0.0
