@@ -238,7 +238,7 @@ def main():
         },
         "roofline": {
             "kernel": "%s (one launch = all %d factors of the stage for one micro-batch)"
-                      % ("pack_bf16_kernel + curvature_syrk_bf16_256_kernel" if bf16 else "curvature_syrk_kernel", nfac),
+                      % ("curvature_syrk_bf16_256_rowmajor_kernel" if bf16 else "curvature_syrk_kernel", nfac),
             "bound": "mfma",
             "achieved": round(achieved, 2),
             "peak": peak,

@@ -41,6 +41,78 @@ __host__ __device__ inline int b2_tiles(int d)
     return nt * (nt + 1) / 2;
 }
 
+// Which problem and which 256 x 256 tile of its lower tile set a workgroup owns.
+struct B2Tile {
+    int pi, m0, n0;
+    bool diag;
+};
+
+__device__ inline B2Tile b2_locate(const Syrk256Launch &lp)
+{
+    const int t = tn_logical_tile(blockIdx.x, gridDim.x);
+    int pi = 0, hi = lp.count;
+    while (hi - pi > 1) {
+        const int mid = (pi + hi) >> 1;
+        if (lp.p[mid].tile_begin <= t)
+            pi = mid;
+        else
+            hi = mid;
+    }
+    int ti, tj;
+    tn_decode_lower(t - lp.p[pi].tile_begin, (lp.p[pi].d + B2_TILE - 1) / B2_TILE, ti, tj);
+    B2Tile r;
+    r.pi = pi;
+    r.m0 = ti * B2_TILE;
+    r.n0 = tj * B2_TILE;
+    r.diag = (ti == tj);
+    return r;
+}
+
+// Epilogue of a wave's 128 x 128 quarter: factor = beta * factor + alpha * acc on the lower tile set,
+// mirrored into the upper one (bitwise symmetric result).
+__device__ inline void b2_store(const floatx16 (&acc)[4][4], const SyrkProblem &pr, float alpha, float beta,
+                                int m0, int n0, int wm, int wn, int li, int lh, bool diag)
+{
+    const int d = pr.d;
+    // accumulator register r of lane (li, lh) in block (bi, bj): row 32 bi + 8 (r/4) + 4 lh + r%4, column 32 bj + li
+    float *__restrict__ C = pr.factor;
+    const size_t ldf = (size_t)pr.ldf;
+    const bool vec_t = ((pr.ldf & 3) == 0) && ((reinterpret_cast<uintptr_t>(C) & 15) == 0);
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 4; ++bj) {
+            const int n = n0 + wn + 32 * bj + li;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int mq = m0 + wm + 32 * bi + 8 * q + 4 * lh;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int m = mq + e;
+                    v[e] = alpha * acc[bi][bj][4 * q + e];
+                    if (m < d && n < d && (!diag || n <= m)) {
+                        float *dst = C + (size_t)m * ldf + n;
+                        if (beta != 0.f) v[e] += beta * (*dst);
+                        *dst = v[e];
+                    }
+                }
+                // mirror: four consecutive rows of C are four consecutive columns of the transposed tile
+                if (n < d) {
+                    if (!diag && mq + 3 < d && vec_t) {
+                        *reinterpret_cast<float4 *>(C + (size_t)n * ldf + mq) = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int m = mq + e;
+                            if (m < d && (!diag || n < m)) C[(size_t)n * ldf + m] = v[e];
+                        }
+                    }
+                }
+            }
+        }
+}
+
 __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const Syrk256Launch lp)
 {
     __shared__ __attribute__((aligned(16))) char lds_a[B2_STAGES * B2_STAGE_BYTES];
@@ -51,23 +123,9 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const S
     const int li = lane & 31, lh = lane >> 5;
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
 
-    // which tile
-    const int t = tn_logical_tile(blockIdx.x, gridDim.x);
-    int pi = 0, hi = lp.count;
-    while (hi - pi > 1) {
-        const int mid = (pi + hi) >> 1;
-        if (lp.p[mid].tile_begin <= t)
-            pi = mid;
-        else
-            hi = mid;
-    }
-    const SyrkProblem &pr = lp.p[pi];
-    const int d = pr.d;
-    int ti, tj;
-    tn_decode_lower(t - pr.tile_begin, (d + B2_TILE - 1) / B2_TILE, ti, tj);
-    const int m0 = ti * B2_TILE, n0 = tj * B2_TILE;
-    const bool diag = (ti == tj);
-
+    const B2Tile bt = b2_locate(lp);
+    const SyrkProblem &pr = lp.p[bt.pi];
+    const int m0 = bt.m0, n0 = bt.n0;
     const size_t row_bytes = (size_t)pr.ldx * 16;  // one k-group of all columns
     const int groups = pr.n / BF_KG;
     const int niter = groups / BF_SLAB_GROUPS;
@@ -209,44 +267,190 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const S
 #undef B2_PIN
 #undef B2_ITER
 
-    // accumulator register r of lane (li, lh) in block (bi, bj): row 32 bi + 8 (r/4) + 4 lh + r%4, column 32 bj + li
-    float *__restrict__ C = pr.factor;
-    const size_t ldf = (size_t)pr.ldf;
-    const float alpha = lp.alpha, beta = lp.beta;
-    const bool vec_t = ((pr.ldf & 3) == 0) && ((reinterpret_cast<uintptr_t>(C) & 15) == 0);
+    b2_store(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
+}
+
+// ---------------------------------------------------------------------------
+// The same tile without the repacking pre-pass, for inputs that need no padding
+// (d a multiple of 256, tokens a multiple of 32, rows 16-byte aligned).
+//
+// Slabs of the row-major input go straight into LDS as they are: one
+// global_load_lds_dwordx4 per token row, lanes 0..31 fetching the 256 columns of
+// the A panel and lanes 32..63 those of the B panel (the per-lane global address is
+// free, the LDS destination is base + 16 * lane), so an LDS row is
+// [A: 256 columns | B: 256 columns] of one token.  The k-contiguous operand
+// layout of the MFMA is produced on the way out of LDS by ds_read_b64_tr_b16
+// (gfx950): in each group of 16 lanes, lane 4s+q supplies the address of 4
+// consecutive columns of token row kb+s, and lane i receives tokens kb .. kb+3 of
+// column c0 + i (lane layout probed on the hardware).  Two such reads give a lane
+// the 8 consecutive tokens of its column that MFMA 32x32x16 wants.  LDS rows are
+// padded by 32 bytes so that the 4 rows of a read fall into different banks.
+constexpr int B2R_ROW_BYTES = 2 * B2_TILE * 2 + 32;          // 1056
+constexpr int B2R_SLAB_ROWS = 32;                             // tokens per slab = two k steps of 16
+constexpr int B2R_STAGE_BYTES = B2R_SLAB_ROWS * B2R_ROW_BYTES;  // 33792
+
+typedef short b2_short4 __attribute__((ext_vector_type(4)));
+typedef short b2_short8 __attribute__((ext_vector_type(8)));
+
+__device__ inline b2_short4 b2_read_tr(const char *lds_ptr)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) b2_short4 *)lds_ptr);
+}
+
+__global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_rowmajor_kernel(const Syrk256Launch lp)
+{
+    __shared__ __attribute__((aligned(16))) char lds[B2_STAGES * B2R_STAGE_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+    const B2Tile bt = b2_locate(lp);
+    const SyrkProblem &pr = lp.p[bt.pi];
+    const int m0 = bt.m0, n0 = bt.n0;
+    const int K = pr.n;
+    const int niter = K / B2R_SLAB_ROWS;
+    const size_t row_pitch = (size_t)pr.ldx * 2;  // bytes per token row of x
+    const char *xp = static_cast<const char *>(pr.x);
+    // this lane's 8 columns of a token row: A panel in the lower half of the wave, B panel in the upper
+    const unsigned vcol = (unsigned)(((lane < 32) ? (m0 + 8 * lane) : (n0 + 8 * (lane - 32))) * 2);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned l0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(const __attribute__((address_space(3))) char *)lds) +
+                        wave_s * (8 * B2R_ROW_BYTES);  // wave w fetches rows 8w .. 8w+7 of a slab
+
+    floatx16 acc[4][4];
 #pragma unroll
-    for (int bi = 0; bi < 4; ++bi)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int bj = 0; bj < 4; ++bj) {
-            const int n = n0 + wn + 32 * bj + li;
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int mq = m0 + wm + 32 * bi + 8 * q + 4 * lh;
-                float v[4];
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // transposing reads: group g = lane / 16 covers k half g / 2 and column half g % 2 of a 32-column block
+    const int g = lane >> 4, s4 = (lane >> 2) & 3, q4 = lane & 3;
+    const int rd = (8 * (g >> 1) + s4) * B2R_ROW_BYTES + (16 * (g & 1) + 4 * q4) * 2;
+    // one address register per stage and operand: what is added per read (k step, block, upper four
+    // rows) then fits the 16-bit offset field of the LDS instruction, and the loop has no address arithmetic
+    const char *ra[B2_STAGES], *rb[B2_STAGES];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int m = mq + e;
-                    v[e] = alpha * acc[bi][bj][4 * q + e];
-                    if (m < d && n < d && (!diag || n <= m)) {
-                        float *dst = C + (size_t)m * ldf + n;
-                        if (beta != 0.f) v[e] += beta * (*dst);
-                        *dst = v[e];
-                    }
-                }
-                // mirror: four consecutive rows of C are four consecutive columns of the transposed tile
-                if (n < d) {
-                    if (!diag && mq + 3 < d && vec_t) {
-                        *reinterpret_cast<float4 *>(C + (size_t)n * ldf + mq) = make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
+    for (int st = 0; st < B2_STAGES; ++st) {
+        ra[st] = lds + st * B2R_STAGE_BYTES + rd + wm * 2;
+        rb[st] = lds + st * B2R_STAGE_BYTES + rd + B2_TILE * 2 + wn * 2;
+    }
+
+    b2_short8 fa[2][4], fb[2][4];  // [k step parity][block]
+    int kd = 0;                    // first token of the next slab to request
+    const char *sbase = xp;
+
+#define R2_DBASE()                                                                         \
+    do {                                                                                   \
+        sbase = xp + (size_t)(min(kd, K - B2R_SLAB_ROWS) + 8 * wave_s) * row_pitch;        \
+        kd += B2R_SLAB_ROWS;                                                               \
+    } while (0)
+    // row w of this wave's eight rows of the slab
+#define R2_D1(st, w)                                                                       \
+    tn_dma16_s(reinterpret_cast<const float *>(sbase + (size_t)(w) * row_pitch), vcol,     \
+               l0 + (st) * B2R_STAGE_BYTES + (w) * B2R_ROW_BYTES)
+#define R2_R(dst, base, st, t, b)                                                                       \
+    do {                                                                                                \
+        const char *p_ = (base)[st] + (t) * 16 * B2R_ROW_BYTES + (b) * 64;                              \
+        const b2_short4 lo_ = b2_read_tr(p_), hi_ = b2_read_tr(p_ + 4 * B2R_ROW_BYTES);                 \
+        dst = __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7);                                \
+    } while (0)
+#define R2_RA(st, t, set)                                                                  \
+    do {                                                                                   \
+        _Pragma("unroll") for (int b = 0; b < 4; ++b) R2_R(fa[set][b], ra, st, t, b);      \
+    } while (0)
+#define R2_RB(st, t, set)                                                                  \
+    do {                                                                                   \
+        _Pragma("unroll") for (int b = 0; b < 4; ++b) R2_R(fb[set][b], rb, st, t, b);      \
+    } while (0)
+#define R2_MG(set, bi)                                                                                        \
+    do {                                                                                                      \
+        _Pragma("unroll") for (int bj = 0; bj < 4; ++bj)                                                      \
+            acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                            \
+                __builtin_bit_cast(bf16x8, fa[set][bi]), __builtin_bit_cast(bf16x8, fb[set][bj]),             \
+                acc[bi][bj], 0, 0, 0);                                                                        \
+    } while (0)
+#define R2_PIN() __builtin_amdgcn_sched_barrier(0)
+    // One slab; same order as the packed kernel: reads and loads in pieces between groups of four MFMAs.
+#define R2_ITER(st0, st1, st3)                                                             \
+    do {                                                                                   \
+        R2_DBASE();                                                                        \
+        R2_PIN();                                                                          \
+        R2_MG(0, 0);                                                                       \
+        R2_PIN();                                                                          \
+        R2_RA(st0, 1, 1);                                                                  \
+        R2_D1(st3, 0);                                                                     \
+        R2_PIN();                                                                          \
+        R2_MG(0, 1);                                                                       \
+        R2_PIN();                                                                          \
+        R2_RB(st0, 1, 1);                                                                  \
+        R2_D1(st3, 1);                                                                     \
+        R2_PIN();                                                                          \
+        R2_MG(0, 2);                                                                       \
+        R2_PIN();                                                                          \
+        R2_D1(st3, 2);                                                                     \
+        R2_PIN();                                                                          \
+        R2_MG(0, 3);                                                                       \
+        R2_PIN();                                                                          \
+        R2_D1(st3, 3);                                                                     \
+        R2_PIN();                                                                          \
+        R2_MG(1, 0);                                                                       \
+        R2_PIN();                                                                          \
+        R2_RA(st1, 0, 0);                                                                  \
+        R2_D1(st3, 4);                                                                     \
+        R2_PIN();                                                                          \
+        R2_MG(1, 1);                                                                       \
+        R2_PIN();                                                                          \
+        R2_RB(st1, 0, 0);                                                                  \
+        R2_D1(st3, 5);                                                                     \
+        R2_PIN();                                                                          \
+        R2_MG(1, 2);                                                                       \
+        R2_PIN();                                                                          \
+        R2_D1(st3, 6);                                                                     \
+        R2_D1(st3, 7);                                                                     \
+        R2_PIN();                                                                          \
+        R2_MG(1, 3);                                                                       \
+        R2_PIN();                                                                          \
+        __builtin_amdgcn_s_waitcnt(0x0F78); /* vmcnt(8): all but the newest slab landed */ \
+        __syncthreads();                                                                   \
+        R2_PIN();                                                                          \
+    } while (0)
+
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int m = mq + e;
-                            if (m < d && (!diag || n < m)) C[(size_t)n * ldf + m] = v[e];
-                        }
-                    }
-                }
-            }
-        }
+    for (int q = 0; q < 3; ++q) {
+        R2_DBASE();
+#pragma unroll
+        for (int w = 0; w < 8; ++w) R2_D1(q, w);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8): slabs 0 and 1 have landed
+    __syncthreads();
+    R2_RA(0, 0, 0);
+    R2_RB(0, 0, 0);
+    int s = 0;
+    for (; s + 4 <= niter; s += 4) {
+        R2_ITER(0, 1, 3);
+        R2_ITER(1, 2, 0);
+        R2_ITER(2, 3, 1);
+        R2_ITER(3, 0, 2);
+    }
+    const int rest = niter - s;  // s is a multiple of four: the stages continue at 0
+    if (rest > 0) R2_ITER(0, 1, 3);
+    if (rest > 1) R2_ITER(1, 2, 0);
+    if (rest > 2) R2_ITER(2, 3, 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing may still be writing LDS
+#undef R2_DBASE
+#undef R2_D1
+#undef R2_R
+#undef R2_RA
+#undef R2_RB
+#undef R2_MG
+#undef R2_PIN
+#undef R2_ITER
+
+    b2_store(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
 }
 
 }  // namespace kfac

@@ -395,8 +395,25 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
             l2.count = (int)n;
             l2.alpha = alpha;
             l2.beta = beta;
-            hipLaunchKernelGGL(pack_bf16_kernel, dim3((cmax + PACK_COLS - 1) / PACK_COLS, gmax / BF_SLAB_GROUPS, (unsigned)n), dim3(256), 0, st, pk);
-            hipLaunchKernelGGL(curvature_syrk_bf16_256_kernel, dim3(tb), dim3(256), 0, st, l2);
+            // inputs that need no padding are read as they are (transposing LDS reads), without the pre-pass
+            bool rowmajor = true;
+            for (int64_t i = 0; i < n; ++i) {
+                const kfac_curvature_item &it = items[done + i];
+                rowmajor = rowmajor && it.d % B2_TILE == 0 && it.n_tokens % B2R_SLAB_ROWS == 0 && it.ldx % 8 == 0 &&
+                           (reinterpret_cast<uintptr_t>(it.x) & 15) == 0;
+            }
+            if (rowmajor) {
+                for (int64_t i = 0; i < n; ++i) {
+                    const kfac_curvature_item &it = items[done + i];
+                    l2.p[i].x = it.x;
+                    l2.p[i].n = (int)it.n_tokens;
+                    l2.p[i].ldx = (int)it.ldx;
+                }
+                hipLaunchKernelGGL(curvature_syrk_bf16_256_rowmajor_kernel, dim3(tb), dim3(256), 0, st, l2);
+            } else {
+                hipLaunchKernelGGL(pack_bf16_kernel, dim3((cmax + PACK_COLS - 1) / PACK_COLS, gmax / BF_SLAB_GROUPS, (unsigned)n), dim3(256), 0, st, pk);
+                hipLaunchKernelGGL(curvature_syrk_bf16_256_kernel, dim3(tb), dim3(256), 0, st, l2);
+            }
         } else if (dtype == KFAC_BF16) {
             SyrkLaunchPacked lb;
             static_assert(sizeof(lb) == sizeof(lp), "the curvature launch types share one layout");

@@ -544,6 +544,23 @@ def test_curvature_bf16_large_tiles(k, oracle):
     assert np.array_equal(host(f), host(f).T)
 
 
+@pytest.mark.parametrize("n", [32, 96, 160, 288])
+def test_curvature_bf16_rowmajor_tiles(k, oracle, n):
+    """Sizes that need no padding take the kernel that reads the row-major input directly (transposing
+    LDS reads): 1, 3, 5 and 9 slabs of 32 tokens, a row pitch larger than d, two micro-batches."""
+    d = 5120  # 20 x 21 / 2 = 210 tiles of 256 x 256
+    xs = [synth.activations(5, 2, m, 0, n, d, bf16=True) for m in range(2)]
+    f = torch.empty(d, d, device="cuda")
+    for m, x in enumerate(xs):
+        buf = torch.zeros(n, d + 64, device="cuda", dtype=torch.bfloat16)
+        buf[:, :d] = dev(x).to(torch.bfloat16)
+        k.kfac_curvature(buf[:, :d], f, 1.0 / (2 * n), 0.0 if m == 0 else 1.0)
+    err = oracle.rel_fro(host(f), oracle.curvature(xs))
+    print("bf16 row-major tiles n=%d rel_fro %.3g" % (n, err), flush=True)
+    assert err <= BF16_FACTOR_TOL and err <= 2e-6
+    assert np.array_equal(host(f), host(f).T)
+
+
 def test_mfma_probe_reports_its_work(k):
     """The measurement aid runs, leaves its sink alone and reports 4096 / 32768 flops per MFMA."""
     sink = torch.zeros(64, device="cuda")
