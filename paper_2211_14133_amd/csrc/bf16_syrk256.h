@@ -284,10 +284,11 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const S
 // consecutive columns of token row kb+s, and lane i receives tokens kb .. kb+3 of
 // column c0 + i (lane layout probed on the hardware).  Two such reads give a lane
 // the 8 consecutive tokens of its column that MFMA 32x32x16 wants.  LDS rows are
-// padded by 32 bytes so that the 4 rows of a read fall into different banks.
-constexpr int B2R_ROW_BYTES = 2 * B2_TILE * 2 + 32;          // 1056
+// padded by 64 bytes: the 4 rows that half a wave reads (64 bytes of each) then fall
+// into different banks.
+constexpr int B2R_ROW_BYTES = 2 * B2_TILE * 2 + 64;            // 1088
 constexpr int B2R_SLAB_ROWS = 32;                             // tokens per slab = two k steps of 16
-constexpr int B2R_STAGE_BYTES = B2R_SLAB_ROWS * B2R_ROW_BYTES;  // 33792
+constexpr int B2R_STAGE_BYTES = B2R_SLAB_ROWS * B2R_ROW_BYTES;  // 34816
 
 typedef short b2_short4 __attribute__((ext_vector_type(4)));
 typedef short b2_short8 __attribute__((ext_vector_type(8)));
