@@ -561,6 +561,38 @@ def test_curvature_bf16_rowmajor_tiles(k, oracle, n):
     assert np.array_equal(host(f), host(f).T)
 
 
+def test_work_items_follow_the_callers_stream(k, oracle):
+    """Everything is enqueued on the stream the caller names: a chain issued on a side stream (default
+    priority), with its inputs produced on that stream just before, equals the default-stream result."""
+    n, d_in, d_out = 512, 384, 256
+    x = dev(synth.activations(2, 0, 0, 0, n, d_in))
+    e = dev(synth.errors(2, 0, 0, 0, n, d_out))
+    g = dev(synth.weight_gradient([host(e)], [host(x)]))
+
+    def chain(stream, xin, ein):
+        a = torch.empty(d_in, d_in, device="cuda")
+        b = torch.empty(d_out, d_out, device="cuda")
+        k.kfac_curvature(xin, a, 1.0 / n, 0.0, stream=stream)
+        k.kfac_curvature(ein, b, 1.0 / n, 0.0, stream=stream)
+        ai, bi = torch.empty_like(a), torch.empty_like(b)
+        infos = k.kfac_invert_batched([a, b], synth.DAMPING, [ai, bi], stream=stream)
+        p = torch.empty_like(g)
+        k.kfac_precondition(bi, ai, g, p, stream=stream)
+        return a, b, ai, bi, p, infos
+
+    ref = chain(None, x, e)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        x2 = x * 1.0  # produced on the side stream: only stream order makes it visible to the kernels
+        e2 = e * 1.0
+        got = chain(side, x2, e2)
+    side.synchronize()
+    for r, o in zip(ref, got):
+        assert torch.equal(r, o)
+    assert int(got[5].abs().max()) == 0
+
+
 def test_mfma_probe_reports_its_work(k):
     """The measurement aid runs, leaves its sink alone and reports 4096 / 32768 flops per MFMA."""
     sink = torch.zeros(64, device="cuda")
