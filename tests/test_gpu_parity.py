@@ -593,6 +593,56 @@ def test_work_items_follow_the_callers_stream(k, oracle):
     assert int(got[5].abs().max()) == 0
 
 
+def test_chain_can_be_captured_in_a_graph(k, oracle):
+    """The library allocates nothing and enqueues only kernels, so a whole chain (two curvature work
+    items, the batched inversion with its chain of launches, the precondition) can be captured in a HIP
+    graph.  Every replay, with eager work and synchronisation in between and fresh inputs written into
+    the captured buffers, must equal the eager result bit for bit."""
+    n, d_in, d_out = 512, 640, 384
+    x = torch.empty(n, d_in, device="cuda")
+    e = torch.empty(n, d_out, device="cuda")
+    g = torch.empty(d_out, d_in, device="cuda")
+    a, b = torch.empty(d_in, d_in, device="cuda"), torch.empty(d_out, d_out, device="cuda")
+    ai, bi, p = torch.empty_like(a), torch.empty_like(b), torch.empty_like(g)
+    infos = torch.zeros(2, dtype=torch.int32, device="cuda")
+    need = max(k.kfac_curvature_grouped_workspace([x, e], [a, b]), k.kfac_invert_batched_workspace([a, b], [ai, bi]),
+               k.kfac_precondition_grouped_workspace([bi], [ai], [g], [p]))
+    ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+
+    def chain(stream):
+        k.kfac_curvature_grouped([x, e], [a, b], 1.0 / n, 0.0, workspace=ws, stream=stream)
+        k.kfac_invert_batched([a, b], synth.DAMPING, [ai, bi], infos=infos, workspace=ws, stream=stream)
+        k.kfac_precondition(bi, ai, g, p, workspace=ws, stream=stream)
+
+    def fill(mb):
+        hx, he = synth.activations(2, 1, 0, mb, n, d_in), synth.errors(2, 1, 0, mb, n, d_out)
+        x.copy_(dev(hx))
+        e.copy_(dev(he))
+        g.copy_(dev(synth.weight_gradient([he], [hx])))
+
+    fill(0)
+    chain(None)  # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain(torch.cuda.current_stream())
+    for mb in range(3):
+        fill(mb)
+        chain(None)
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (a, b, ai, bi, p)]
+        for t in (a, b, ai, bi, p):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for w, t in zip(want, (a, b, ai, bi, p)):
+            assert torch.equal(w, t)
+        assert int(infos.abs().max()) == 0
+    op = oracle.kfac_chain([host(x)], [host(e)], host(g), synth.DAMPING)[4]
+    assert oracle.rel_fro(host(p), op) <= PRECOND_TOL
+
+
 def test_mfma_probe_reports_its_work(k):
     """The measurement aid runs, leaves its sink alone and reports 4096 / 32768 flops per MFMA."""
     sink = torch.zeros(64, device="cuda")
