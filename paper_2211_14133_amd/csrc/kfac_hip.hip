@@ -199,7 +199,7 @@ struct InvBatch {
     PlanSteps *rec = nullptr;
     const std::vector<InvMat> &mats;
     std::vector<TriNode> nodes;
-    int op = 0, tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE;
+    int op = 0, tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE, reverse_cols = 0;
     float alpha = 1.f, beta = 0.f;
 
     explicit InvBatch(const std::vector<InvMat> &m) : mats(m) {}
@@ -239,6 +239,7 @@ struct InvBatch {
             lp.c.splits = 1;
             lp.c.alpha = alpha;
             lp.c.beta = beta;
+            lp.c.reverse_cols = reverse_cols;
             lp.op = op;
             const int grid = tn_balance_xcds(lp, tiles);
             if (rec != nullptr) {
@@ -625,6 +626,7 @@ kfac_status invert_record(const kfac_invert_item *items, int64_t count, float da
     s1.rec = s2.rec = &steps;
     s1.op = INV_MERGE_Y;
     s1.mask_b = MASK_KEEP_K_LE;  // W22 upper triangular
+    s1.reverse_cols = 1;         // K grows with the tile column: last columns first
     s2.op = INV_MERGE_W;
     s2.mask_a = MASK_KEEP_K_GE;  // W11 read through its mirror below the diagonal
     s2.alpha = -1.f;

@@ -59,6 +59,8 @@ struct TnCommon {
     float beta;
     float *partial;  // [total logical tiles][BM * BN]
     int slab_align;  // K ranges of split tiles are multiples of this many slabs (0 or 1: any)
+    int reverse_cols;  // TILE_FULL only: walk the tile columns from the last to the first (set when K grows
+                       // with the column, so that the long tiles of a range run first, not last)
     int xcd_balanced;  // 0: each XCD takes a contiguous eighth of the tiles; 1: the ranges xcd_begin[]
     int xcd_begin[9];  // XCD x works on logical tiles xcd_begin[x] .. xcd_begin[x+1]-1 (equal cost, see tn_balance_xcds)
 };
@@ -324,6 +326,7 @@ __device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
     const int tm = (pr.M + BM - 1) / BM, tn = (pr.N + BN - 1) / BN;
     if (lp.tile_mode == TILE_FULL) {
         tn_decode_full(tile, tm, tn, tl.ti, tl.tj);
+        if (lp.reverse_cols) tl.tj = tn - 1 - tl.tj;
     } else {
         tn_decode_lower(tile, tm, tl.ti, tl.tj);
         if (lp.tile_mode == TILE_UPPER) {
@@ -365,6 +368,7 @@ inline int tn_balance_xcds(L &ll, int total_tiles)
                 int ti, tj;
                 if (c.tile_mode == TILE_FULL) {
                     tn_decode_full(tile, tm, tn, ti, tj);
+                    if (c.reverse_cols) tj = tn - 1 - tj;
                 } else {
                     tn_decode_lower(tile, tm, ti, tj);
                     if (c.tile_mode == TILE_UPPER) { const int sw = ti; ti = tj; tj = sw; }
