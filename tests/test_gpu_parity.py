@@ -561,6 +561,33 @@ def test_curvature_bf16_rowmajor_tiles(k, oracle, n):
     assert np.array_equal(host(f), host(f).T)
 
 
+def test_chain_with_order_one_errors_and_few_tokens(k, oracle):
+    """In the configurations B = E^T E / N is tiny against the damping, so B's inverse is almost I / damping
+    and the chain hardly exercises it.  Here the errors are O(1) and there are fewer tokens than output
+    features, so B is rank-deficient: its inverse spans six orders of magnitude and carries the result."""
+    n, d_in, d_out = 384, 320, 640
+    x = synth.activations(3, 7, 0, 0, n, d_in, gelu=True)
+    e = synth.errors(3, 7, 0, 0, n, d_out, scale=1.0)
+    g = synth.weight_gradient([e], [x])
+    a, b = torch.empty(d_in, d_in, device="cuda"), torch.empty(d_out, d_out, device="cuda")
+    k.kfac_curvature(dev(x), a, 1.0 / n, 0.0)
+    k.kfac_curvature(dev(e), b, 1.0 / n, 0.0)
+    ai, bi = torch.empty_like(a), torch.empty_like(b)
+    infos = k.kfac_invert_batched([a, b], synth.DAMPING, [ai, bi])
+    p = torch.empty(d_out, d_in, device="cuda")
+    k.kfac_precondition(bi, ai, dev(g), p)
+    assert int(infos.abs().max()) == 0
+    oa, ob, oai, obi, op = oracle.kfac_chain([x], [e], g, synth.DAMPING)
+    errs = [oracle.rel_fro(host(t), o) for t, o in ((a, oa), (b, ob), (ai, oai), (bi, obi), (p, op))]
+    print("O(1) errors: A %.2e B %.2e A^-1 %.2e B^-1 %.2e P %.2e" % tuple(errs), flush=True)
+    assert errs[0] <= FACTOR_TOL and errs[1] <= FACTOR_TOL and errs[4] <= PRECOND_TOL
+    # the Kronecker identity of section 2.3.1 on the GPU's own result: (B + lam I) P (A + lam I) = G
+    at = oa + synth.DAMPING * np.eye(d_in)
+    bt = ob + synth.DAMPING * np.eye(d_out)
+    back = bt @ host(p).astype(np.float64) @ at
+    assert oracle.rel_fro(back, g) <= PRECOND_TOL
+
+
 def test_work_items_follow_the_callers_stream(k, oracle):
     """Everything is enqueued on the stream the caller names: a chain issued on a side stream (default
     priority), with its inputs produced on that stream just before, equals the default-stream result."""
