@@ -642,23 +642,11 @@ __device__ inline void tn_dma16_s(const float *sbase, unsigned voff, unsigned ld
 // whatever is not an MFMA must be little and sit between MFMAs.  The loop is unrolled over
 // the four stages (LDS addresses become immediates), the loads take a scalar base that is
 // advanced with scalar arithmetic, and scheduling barriers pin the order written here.
-//
-// ROLE: on a diagonal tile of a triangular tile set one 64 x 64 quarter lies wholly on the side
-// that is not stored (its mirror is), so only 12 of the 16 MFMA blocks of the tile are needed.
-// Instead of letting one wave idle (the tile would take as long as before: its waves move in step)
-// the 12 blocks are dealt three to a wave: the waves of the three useful quarters skip their block
-// (1,1) (TN_ROLE_MAIN3) and the fourth wave computes those three blocks (TN_ROLE_HELPER_*; it returns
-// them in sum[0][0], sum[0][1], sum[1][0], for the quarters (0,0), the off-diagonal one and (64,64)).
-// The diagonal tile then costs three quarters of a full one.
-enum TnRole : int { TN_ROLE_FULL = 0, TN_ROLE_MAIN3 = 1, TN_ROLE_HELPER_LOWER = 2, TN_ROLE_HELPER_UPPER = 3 };
-
-template <int ROLE>
 __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
                                           float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                           floatx16 (&sum)[2][2])
 {
     static_assert(TN_LDS_STAGES == 4, "the loop below is unrolled over four stages");
-    constexpr bool HELPER = (ROLE == TN_ROLE_HELPER_LOWER || ROLE == TN_ROLE_HELPER_UPPER);
     const int tid = threadIdx.x;
     const int K = pr.K;
     const float *__restrict__ A = pr.A;
@@ -679,8 +667,7 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
 
     const int nslab = tl.kt1 - tl.kt0;
     if (nslab <= 0) return;
-    float2 fa[2][4], fb[2][4];                        // own quarter (helper: the quarter rows / columns 0..63)
-    float2 fah[HELPER ? 2 : 1][4], fbh[HELPER ? 2 : 1][4];  // helper only: rows / columns 64..127
+    float2 fa[2][4], fb[2][4];
     int kd = tl.kbase + tl.kt0 * BK;  // first K row of the next slab to request (wave-uniform)
 
     // per-lane byte offsets of the four loads of a slab, relative to the slab's first row
@@ -717,34 +704,16 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
 #define TN_R(st, half)                                                                                            \
     do {                                                                                                          \
         _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                           \
-            if constexpr (HELPER) {                                                                               \
-                fa[half][q] = *reinterpret_cast<const float2 *>(&As[st][8 * (half) + 2 * q + lh][2 * li]);        \
-                fb[half][q] = *reinterpret_cast<const float2 *>(&Bs[st][8 * (half) + 2 * q + lh][2 * li]);        \
-                fah[half][q] = *reinterpret_cast<const float2 *>(&As[st][8 * (half) + 2 * q + lh][64 + 2 * li]);  \
-                fbh[half][q] = *reinterpret_cast<const float2 *>(&Bs[st][8 * (half) + 2 * q + lh][64 + 2 * li]);  \
-            } else {                                                                                              \
-                fa[half][q] = *reinterpret_cast<const float2 *>(&As[st][8 * (half) + 2 * q + lh][wm + 2 * li]);   \
-                fb[half][q] = *reinterpret_cast<const float2 *>(&Bs[st][8 * (half) + 2 * q + lh][wn + 2 * li]);   \
-            }                                                                                                     \
+            fa[half][q] = *reinterpret_cast<const float2 *>(&As[st][8 * (half) + 2 * q + lh][wm + 2 * li]);       \
+            fb[half][q] = *reinterpret_cast<const float2 *>(&Bs[st][8 * (half) + 2 * q + lh][wn + 2 * li]);       \
         }                                                                                                         \
     } while (0)
-    // (helper: block (1,1) of the quarters (0,0), (64,0) [lower sets] or (0,64) [upper sets], (64,64))
-#define TN_MQ(half, q)                                                                                            \
-    do {                                                                                                          \
-        if constexpr (HELPER) {                                                                                   \
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[0][0], 0, 0, 0);   \
-            if constexpr (ROLE == TN_ROLE_HELPER_LOWER)                                                           \
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fah[half][q].y, fb[half][q].y, acc[0][1], 0, 0, 0); \
-            else                                                                                                  \
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fbh[half][q].y, acc[0][1], 0, 0, 0); \
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fah[half][q].y, fbh[half][q].y, acc[1][0], 0, 0, 0); \
-        } else {                                                                                                  \
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].x, acc[0][0], 0, 0, 0);   \
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].y, acc[0][1], 0, 0, 0);   \
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].x, acc[1][0], 0, 0, 0);   \
-            if constexpr (ROLE == TN_ROLE_FULL)                                                                   \
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[1][1], 0, 0, 0); \
-        }                                                                                                         \
+#define TN_MQ(half, q)                                                                                        \
+    do {                                                                                                      \
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].x, acc[0][0], 0, 0, 0);   \
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].y, acc[0][1], 0, 0, 0);   \
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].x, acc[1][0], 0, 0, 0);   \
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[1][1], 0, 0, 0);   \
     } while (0)
 #define TN_PIN() __builtin_amdgcn_sched_barrier(0)
     // s_waitcnt vmcnt(4): everything but the four newest loads has landed (gfx9 encoding:
@@ -1076,44 +1045,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
     // (the direct loop addresses a slab with 32-bit byte offsets from its first row)
     const bool direct_ok = (pr.K % BK) == 0 && pr.lda < (1 << 25) && pr.ldb < (1 << 25);
     if (!done && fast_a && fast_b && !masked && direct_ok) {
-        if (tl.diag && lp.splits == 1) {
-            // 12 useful MFMA blocks dealt three to a wave (see TnRole); the helper is the wave whose own
-            // quarter is not stored: upper right (wave 1) for lower tile sets, lower left (wave 2) for upper
-            const bool lower = (lp.tile_mode == TILE_LOWER);
-            const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-            const int helper = lower ? 1 : 2, mid_owner = lower ? 2 : 1;
-            if (wave_u == helper) {
-                if (lower)
-                    tn_mainloop_direct<TN_ROLE_HELPER_LOWER>(pr, tl, As, Bs, sum);
-                else
-                    tn_mainloop_direct<TN_ROLE_HELPER_UPPER>(pr, tl, As, Bs, sum);
-            } else {
-                tn_mainloop_direct<TN_ROLE_MAIN3>(pr, tl, As, Bs, sum);
-            }
-            // hand the helper's blocks to their owners through LDS (the ring is free now: every wave has
-            // waited for its own loads, the barrier makes that true for all of them)
-            float(*xbuf)[16][64] = reinterpret_cast<float(*)[16][64]>(&As[0][0][0]);  // [block][register][lane]: 12 KB
-            __syncthreads();
-            if (wave_u == helper) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    xbuf[0][r][lane] = sum[0][0][r];
-                    xbuf[1][r][lane] = sum[0][1][r];
-                    xbuf[2][r][lane] = sum[1][0][r];
-                    sum[0][0][r] = 0.f;
-                    sum[0][1][r] = 0.f;
-                    sum[1][0][r] = 0.f;
-                }
-            }
-            __syncthreads();
-            if (wave_u != helper) {
-                const int blk = (wave_u == 0) ? 0 : (wave_u == mid_owner ? 1 : 2);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sum[1][1][r] = xbuf[blk][r][lane];
-            }
-        } else {
-            tn_mainloop_direct<TN_ROLE_FULL>(pr, tl, As, Bs, sum);
-        }
+        tn_mainloop_direct(pr, tl, As, Bs, sum);
         done = true;
     }
     if (!done) {
@@ -1135,7 +1067,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
                     TnTile seg = tl;
                     if (s0 > tl.kt0) {
                         seg.kt0 = tl.kt0; seg.kt1 = s0;
-                        tn_mainloop_direct<TN_ROLE_FULL>(pr, seg, As, Bs, sum);
+                        tn_mainloop_direct(pr, seg, As, Bs, sum);
                         __syncthreads();
                     }
                     seg.kt0 = s0; seg.kt1 = s1;
@@ -1143,7 +1075,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
                     if (s1 < tl.kt1) {
                         __syncthreads();
                         seg.kt0 = s1; seg.kt1 = tl.kt1;
-                        tn_mainloop_direct<TN_ROLE_FULL>(pr, seg, As, Bs, sum);
+                        tn_mainloop_direct(pr, seg, As, Bs, sum);
                     }
                 } else {
                     tn_mainloop<false, true>(lp, pr, tl, As, Bs, sum);
