@@ -129,3 +129,17 @@ def test_mfma_probe_rejects_bad_arguments():
     assert lib.kfac_mfma_probe(binding.KFAC_F32, 10, fake, None, None) == 1
     assert lib.kfac_mfma_probe(binding.KFAC_F32, 0, fake, ctypes.byref(flops), None) == 1
     assert lib.kfac_mfma_probe(7, 10, fake, ctypes.byref(flops), None) == 1
+
+
+def test_header_is_plain_c_and_cxx():
+    """The boundary is a C ABI: the header must compile on its own as C99 and as C++11."""
+    import shutil
+    import subprocess
+
+    header = os.path.join(ROOT, "include", "kfac.h")
+    for cc, flags in (("gcc", ["-std=c99", "-x", "c"]), ("g++", ["-std=c++11", "-x", "c++"])):
+        if shutil.which(cc) is None:
+            pytest.skip(cc + " not available")
+        r = subprocess.run([cc, *flags, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", header],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
