@@ -131,8 +131,8 @@ def test_curvature_grouped_matches_single_and_oracle(k, oracle):
         want = oracle.curvature_update(x, 1.0 / 512, 0.0)
         assert oracle.rel_fro(host(f), want) <= 5e-7
         assert np.array_equal(host(f), host(f).T)
-    # 60 items: more than one launch
-    many = [dev(synth.activations(1, 1, i, 0, 128, 96)) for i in range(60)]
+    # 100 items: more than the 80 problems one launch describes
+    many = [dev(synth.activations(1, 1, i, 0, 128, 96)) for i in range(100)]
     fm = [torch.empty(96, 96, device="cuda") for _ in many]
     k.kfac_curvature_grouped(many, fm, 1.0 / 128, 0.0)
     for x, f in zip(many, fm):
@@ -586,6 +586,33 @@ def test_chain_with_order_one_errors_and_few_tokens(k, oracle):
     bt = ob + synth.DAMPING * np.eye(d_out)
     back = bt @ host(p).astype(np.float64) @ at
     assert oracle.rel_fro(back, g) <= PRECOND_TOL
+
+
+def test_more_items_than_one_launch_describes(k, oracle):
+    """90 inversions (a launch describes 72 matrices) and 60 preconditions (48 problems per launch):
+    the calls cut themselves into several launches; every item still equals its single-item result."""
+    ds = [96 + 32 * (i % 5) for i in range(90)]
+    fs = [oracle.curvature(synth.activations(2, 5, i, 0, d + 40, d)).astype(np.float32) for i, d in enumerate(ds)]
+    fd = [dev(f) for f in fs]
+    invs = [torch.empty(d, d, device="cuda") for d in ds]
+    infos = k.kfac_invert_batched(fd, 1e-2, invs)
+    assert np.all(host(infos) == 0)
+    for i in (0, 44, 71, 72, 89):
+        want, _ = oracle.invert(fs[i].astype(np.float64), 1e-2)
+        assert oracle.rel_fro(host(invs[i]), want) <= 1e-4
+        single, _ = gpu_invert(k, fs[i], 1e-2)
+        assert np.array_equal(single, host(invs[i]))
+    # 60 layers: B^-1 = inverses 0..59 padded to a common pairing with A^-1 = inverses 30..89
+    b_invs, a_invs = invs[:60], invs[30:90]
+    grads = [dev(synth.errors(2, 6, i, 0, b.shape[0], a.shape[0], scale=1.0)) for i, (b, a) in enumerate(zip(b_invs, a_invs))]
+    outs = [torch.empty_like(g) for g in grads]
+    k.kfac_precondition_grouped(b_invs, a_invs, grads, outs)
+    for i in (0, 47, 48, 59):
+        want = oracle.precondition(host(b_invs[i]), host(grads[i]), host(a_invs[i]))
+        assert oracle.rel_fro(host(outs[i]), want) <= 2e-6
+        one = torch.empty_like(outs[i])
+        k.kfac_precondition(b_invs[i], a_invs[i], grads[i], one)
+        assert torch.equal(one, outs[i])
 
 
 def test_work_items_follow_the_callers_stream(k, oracle):
