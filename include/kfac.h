@@ -246,7 +246,6 @@ kfac_status kfac_perf_model(double c_f, double c_b, double t_f, double t_b, int6
 /* ------------------------------------------------------------------- misc */
 const char *kfac_status_string(kfac_status status);
 
-/* Library version as major * 10000 + minor * 100 + patch. */
 /* Measurement aid (not a step of the method): enqueues a kernel whose waves do nothing but
  * matrix-core instructions on registers, so that a caller can time what the matrix cores of this
  * chip sustain and report a kernel against that ceiling as well as against the published peak.
@@ -258,6 +257,7 @@ const char *kfac_status_string(kfac_status status);
  * unknown dtype; KFAC_ERR_HIP if the launch fails. */
 kfac_status kfac_mfma_probe(kfac_dtype dtype, int64_t iters, void *sink, double *flops, void *stream);
 
+/* Library version as major * 10000 + minor * 100 + patch. */
 int kfac_version(void);
 
 #ifdef __cplusplus
