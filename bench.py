@@ -36,6 +36,12 @@ def parse():
                          "6, 7: BERT-Large-shaped block with 16384 / 65536 tokens)")
     ap.add_argument("--seed", type=int, default=221114133)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline", choices=["sample", "full"], default="sample",
+                    help="sample: time the oracle on a bounded part of the workload (default, seconds); "
+                         "full: run the oracle over the whole step (minutes)")
+    ap.add_argument("--phase", choices=["all", "curvature", "inversion", "precondition"], default="all",
+                    help="for profiling: after one full untimed step, time only this phase (prints a short JSON "
+                         "line that is not the benchmark line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain 1 GiB device copies (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
@@ -138,6 +144,31 @@ def main():
         if events is not None:
             events["t3"].record(stream)
 
+    def phase_only(which):
+        if which == "curvature":
+            for m in range(n_micro):
+                check(lib.kfac_curvature_grouped(curv_items[m], nfac, in_dtype, alpha,
+                                                 0.0 if m == 0 else 1.0, wsp, ws_bytes, sp))
+        elif which == "inversion":
+            check(lib.kfac_invert_batched(inv_items, nfac, damping, wsp, ws_bytes, sp))
+        else:
+            check(lib.kfac_precondition_grouped(prec_items, nlay, wsp, ws_bytes, sp))
+
+    if args.phase != "all":
+        step()  # every buffer the phase reads holds real data
+        for _ in range(args.warmup):
+            phase_only(args.phase)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            phase_only(args.phase)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"phase": args.phase, "workload": cfg["name"], "repetitions": args.steps,
+                          "ms": round(e0.elapsed_time(e1) / args.steps, 4)}))
+        return
+
     def new_events():
         ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
         return {"t0": ev(), "t2": ev(), "t3": ev(), "c0": [ev() for _ in range(n_micro)],
@@ -236,6 +267,9 @@ def main():
             "inversion": round(f_inv / (inv_ms * 1e-3) / 1e12, 2),
             "precondition": round(f_prec / (prec_ms * 1e-3) / 1e12, 2),
         },
+        # the curvature counted as a dense product (2 N d^2 per factor) instead of its triangle (N d (d+1))
+        "curvature_dense_equivalent_tflops": round(
+            sum(2 * tokens * d * d for (di, do) in layers for d in (di, do)) * n_micro / (curv_ms * 1e-3) / 1e12, 2),
         "roofline": {
             "kernel": "%s (one launch = all %d factors of the stage for one micro-batch)"
                       % ("curvature_syrk_bf16_256_rowmajor_kernel" if bf16 else "curvature_syrk_kernel", nfac),
@@ -271,8 +305,11 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping,
-                                              f_curv, f_inv, f_prec)
+        if args.cpu_baseline == "full":
+            result["cpu_baseline"] = cpu_baseline_full(xs, grads, layers, tokens, n_micro, damping)
+        else:
+            result["cpu_baseline"] = cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping,
+                                                  f_curv, f_inv, f_prec)
     print(json.dumps(result))
 
 
@@ -309,6 +346,38 @@ def cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping, f_curv, f_inv
         "sample": "fp64 oracle on the first %d linears of the stage, one micro-batch of %d tokens: curvature "
                   "%.2f s, inversion %.2f s, precondition %.2f s; each phase scaled by the step's useful flops "
                   "over the sample's" % (nl, tokens, t1 - t0, t2 - t1, t3 - t2),
+    }
+
+
+def cpu_baseline_full(xs, grads, layers, tokens, n_micro, damping):
+    """The fp64 oracle, as it stands, over the whole step: every factor from all micro-batches, every inverse,
+    every preconditioned gradient (minutes; copies from the device are not counted)."""
+    from oracle import kfac_oracle as oracle
+
+    t_curv = t_inv = t_prec = 0.0
+    for li in range(len(layers)):
+        hx = [xs[m][2 * li].float().cpu().numpy() for m in range(n_micro)]
+        he = [xs[m][2 * li + 1].float().cpu().numpy() for m in range(n_micro)]
+        hg = grads[li].cpu().numpy()
+        t0 = time.perf_counter()
+        fa = fb = None
+        for m in range(n_micro):
+            fa = oracle.curvature_update(hx[m], 1.0 / (tokens * n_micro), 0.0 if m == 0 else 1.0, fa)
+            fb = oracle.curvature_update(he[m], 1.0 / (tokens * n_micro), 0.0 if m == 0 else 1.0, fb)
+        t1 = time.perf_counter()
+        ia, ib = oracle.invert(fa, damping)[0], oracle.invert(fb, damping)[0]
+        t2 = time.perf_counter()
+        oracle.precondition(ib, hg, ia)
+        t3 = time.perf_counter()
+        t_curv, t_inv, t_prec = t_curv + (t1 - t0), t_inv + (t2 - t1), t_prec + (t3 - t2)
+        print("cpu baseline: layer %d of %d done" % (li + 1, len(layers)), file=sys.stderr, flush=True)
+    return {
+        "value": round((t_curv + t_inv + t_prec) * 1e3, 1),
+        "unit": "ms",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "the whole step, not a sample: fp64 oracle on all %d layers and %d micro-batches: curvature "
+                  "%.1f s, inversion %.1f s, precondition %.1f s" % (len(layers), n_micro, t_curv, t_inv, t_prec),
     }
 
 

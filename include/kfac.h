@@ -215,7 +215,12 @@ size_t kfac_precondition_grouped_workspace(const kfac_precondition_item *items, 
  * (time in step 0, e.g. the end of the forward pass of its micro-batch: rule 1)
  * and after every work listed in dep_ids[dep_begin[w] .. dep_begin[w+1])
  * (rule 2: an inversion after all its curvature work; ids must be smaller
- * than w).  Works are placed in index order, chunk by chunk, first fit.
+ * than w).  Works are placed in index order, chunk by chunk, first fit along
+ * the time line: a chunk goes into the first idle interval that starts no
+ * earlier than the chunk may and can hold it.  Idle intervals are the bubbles
+ * minus what has been placed, so a hole that a later-released chunk left in
+ * front of itself is used by a later chunk of the queue that fits (the paper
+ * says nothing about such holes; this reading uses the bubbles best).
  *
  * Outputs, one entry per chunk in the same order as chunk_time: the pipeline
  * step (0, 1, ...) and bubble index it went to and its start time relative to

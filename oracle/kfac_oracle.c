@@ -64,15 +64,6 @@ void oracle_curvature(const double *x, int64_t n, int64_t d, int64_t ldx,
     }
 }
 
-/* One entry of the same quantity: alpha * sum_t x[t][i]*x[t][j]. */
-double oracle_curvature_entry(const double *x, int64_t n, int64_t ldx,
-                              int64_t i, int64_t j, double alpha)
-{
-    double s = 0.0;
-    for (int64_t t = 0; t < n; ++t) s += x[t * ldx + i] * x[t * ldx + j];
-    return alpha * s;
-}
-
 /* Cholesky decomposition m = l l^T, l lower triangular, column by column
  * (Cholesky-Crout).  m and l are d x d row-major; only the lower triangle of
  * m is read; the strict upper triangle of l is set to zero.

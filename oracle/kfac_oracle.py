@@ -43,8 +43,6 @@ def _load():
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_curvature.argtypes = [p, i64, i64, i64, f64, f64, p, i64]
         lib.oracle_curvature.restype = None
-        lib.oracle_curvature_entry.argtypes = [p, i64, i64, i64, i64, f64]
-        lib.oracle_curvature_entry.restype = f64
         lib.oracle_cholesky.argtypes = [p, i64, i64, p, i64]
         lib.oracle_cholesky.restype = i64
         lib.oracle_cholesky_inverse.argtypes = [p, i64, i64, p, i64]

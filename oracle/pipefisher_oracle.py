@@ -7,7 +7,7 @@ TEST INFRASTRUCTURE ONLY (same rules as kfac_oracle.py: never imported by the pr
   the piece has to wait for (rule 1: the forward / backward pass of its micro-batch; rule 2: all
   curvature work of the factor for an inversion) and is long enough; when the bubbles of a pipeline
   step are used up the bubbles of the following steps are taken.  It is written as a walk along the
-  time line, bubble instance by bubble instance, not as a table of cursors.
+  time line over the idle intervals of every bubble instance (see the reading stated in its docstring).
 * ``perf_model`` is section 3.3: T_pipe = C_f T_f + C_b T_b, T_bubble = T_pipe - N_micro (T_f + T_b),
   T_kfac = N_micro T_curv + T_inv + T_prec, and the (curvature + inversion) / bubble ratio.
 * ``gpipe_stage_timeline`` lays out one GPipe step of one stage (all forward passes, then all backward
@@ -16,9 +16,16 @@ TEST INFRASTRUCTURE ONLY (same rules as kfac_oracle.py: never imported by the pr
 
 
 def assign_work(bubble_start, bubble_length, step_period, chunk_times, release, deps, max_steps=100000):
-    """Returns (placements, steps_needed); placements[w] = [(step, bubble, start_in_step), ...]."""
-    # occupied[(step, bubble)] = list of (start, end) already given away, kept sorted by start
-    occupied = {}
+    """Returns (placements, steps_needed); placements[w] = [(step, bubble, start_in_step), ...].
+
+    Reading of "assign it to a bubble if its duration is shorter than the bubble duration, otherwise
+    subsequent bubbles are utilized" (section 3.1; the paper does not say what happens to idle time that
+    is left in FRONT of a piece which had to wait for its release): a bubble is whatever part of it
+    is still idle.  The time line is walked from the moment the piece may start; the piece goes into the
+    first idle interval that can hold it, be it the rest of a bubble behind earlier pieces or a hole an
+    earlier, later-released piece left in front of itself.
+    """
+    idle = {}  # (step, bubble) -> idle intervals [begin, end) of that bubble instance, in time order
     finish = []
     placements = []
     last_step = -1
@@ -38,13 +45,15 @@ def assign_work(bubble_start, bubble_length, step_period, chunk_times, release, 
                     raise ValueError("no room")
                 base = step * step_period
                 for b, (s0, length) in enumerate(zip(bubble_start, bubble_length)):
-                    taken = occupied.get((step, b), [])
-                    # pieces are appended left to right, so the free part starts after the last one
-                    free_from = taken[-1][1] if taken else s0
-                    t = max(free_from, ready - base)
-                    if t + dur <= s0 + length:
-                        found = (step, b, t)
-                        occupied.setdefault((step, b), []).append((t, t + dur))
+                    holes = idle.setdefault((step, b), [(s0, s0 + length)])
+                    for h, (begin, end) in enumerate(holes):
+                        t = max(begin, ready - base)
+                        if t + dur <= end:
+                            found = (step, b, t)
+                            # what stays idle: the part in front of the piece and the part behind it
+                            holes[h:h + 1] = [(begin, t), (t + dur, end)]
+                            break
+                    if found is not None:
                         break
                 step += 1
             spots.append(found)

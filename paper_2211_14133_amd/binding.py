@@ -116,11 +116,16 @@ def _need_f32_matrix(t, name):
         raise KfacError("%s must be a 2-D float32 device tensor with unit column stride" % name)
 
 
-def _workspace(nbytes, like, workspace):
+def _workspace(nbytes, like, workspace, stream=None):
     if nbytes == 0:
         return None, 0, None
     if workspace is None:
+        # A temporary buffer comes from torch's caching allocator, which only knows about the stream that is
+        # current now: tell it which stream the kernels will run on, so the memory is not handed out again
+        # while they are still queued there.
         workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=like.device)
+        if stream is not None:
+            workspace.record_stream(stream)
     ptr = (workspace.data_ptr() + 255) // 256 * 256
     avail = workspace.numel() - (ptr - workspace.data_ptr())
     return ctypes.c_void_p(ptr), avail, workspace
@@ -134,6 +139,9 @@ def _curv_items(xs, factors):
         _need_f32_matrix(f, "factor")
         if f.shape[0] != x.shape[1] or f.shape[1] != x.shape[1]:
             raise KfacError("factor must be [d, d] for x [tokens, d]")
+        if x.dtype != xs[0].dtype:
+            raise KfacError("all inputs of a grouped curvature call must have the same dtype (got %s and %s)"
+                            % (xs[0].dtype, x.dtype))
         arr[i] = CurvatureItem(x.data_ptr(), x.shape[0], x.shape[1], x.stride(0), f.data_ptr(), f.stride(0))
     return arr
 
@@ -144,7 +152,7 @@ def kfac_curvature(x, factor, alpha, beta, workspace=None, stream=None):
     _curv_items([x], [factor])
     dt = _dtype_code(x)
     need = lib.kfac_curvature_workspace(x.shape[0], x.shape[1], dt)
-    ws, nbytes, keep = _workspace(need, x, workspace)
+    ws, nbytes, keep = _workspace(need, x, workspace, stream)
     _check(lib.kfac_curvature(ctypes.c_void_p(x.data_ptr()), dt, x.shape[0], x.shape[1], x.stride(0),
                               alpha, beta, ctypes.c_void_p(factor.data_ptr()), factor.stride(0),
                               ws, nbytes, _stream(stream)))
@@ -162,7 +170,7 @@ def kfac_curvature_grouped(xs, factors, alpha, beta, workspace=None, stream=None
     arr = _curv_items(xs, factors)
     dt = _dtype_code(xs[0])
     need = lib.kfac_curvature_grouped_workspace(arr, len(xs), dt)
-    ws, nbytes, keep = _workspace(need, xs[0], workspace)
+    ws, nbytes, keep = _workspace(need, xs[0], workspace, stream)
     _check(lib.kfac_curvature_grouped(arr, len(xs), dt, alpha, beta, ws, nbytes, _stream(stream)))
     return factors
 
@@ -186,7 +194,7 @@ def kfac_invert(factor, damping, inv, info=None, workspace=None, stream=None):
         info = torch.zeros(1, dtype=torch.int32, device=factor.device)
     _inv_items([factor], [inv], info)
     need = lib.kfac_invert_workspace(factor.shape[0])
-    ws, nbytes, keep = _workspace(need, factor, workspace)
+    ws, nbytes, keep = _workspace(need, factor, workspace, stream)
     _check(lib.kfac_invert(ctypes.c_void_p(factor.data_ptr()), factor.shape[0], factor.stride(0), damping,
                            ctypes.c_void_p(inv.data_ptr()), inv.stride(0), ctypes.c_void_p(info.data_ptr()),
                            ws, nbytes, _stream(stream)))
@@ -206,7 +214,7 @@ def kfac_invert_batched(factors, damping, invs, infos=None, workspace=None, stre
         infos = torch.zeros(len(factors), dtype=torch.int32, device=factors[0].device)
     arr = _inv_items(factors, invs, infos)
     need = lib.kfac_invert_batched_workspace(arr, len(factors))
-    ws, nbytes, keep = _workspace(need, factors[0], workspace)
+    ws, nbytes, keep = _workspace(need, factors[0], workspace, stream)
     _check(lib.kfac_invert_batched(arr, len(factors), damping, ws, nbytes, _stream(stream)))
     return infos
 
@@ -230,7 +238,7 @@ def kfac_precondition(b_inv, a_inv, grad, out, workspace=None, stream=None):
     _prec_items([b_inv], [a_inv], [grad], [out])
     d_out, d_in = grad.shape
     need = lib.kfac_precondition_workspace(d_out, d_in)
-    ws, nbytes, keep = _workspace(need, grad, workspace)
+    ws, nbytes, keep = _workspace(need, grad, workspace, stream)
     _check(lib.kfac_precondition(ctypes.c_void_p(b_inv.data_ptr()), d_out, b_inv.stride(0),
                                  ctypes.c_void_p(a_inv.data_ptr()), d_in, a_inv.stride(0),
                                  ctypes.c_void_p(grad.data_ptr()), grad.stride(0),
@@ -248,7 +256,7 @@ def kfac_precondition_grouped(b_invs, a_invs, grads, outs, workspace=None, strea
     lib = load()
     arr = _prec_items(b_invs, a_invs, grads, outs)
     need = lib.kfac_precondition_grouped_workspace(arr, len(grads))
-    ws, nbytes, keep = _workspace(need, grads[0], workspace)
+    ws, nbytes, keep = _workspace(need, grads[0], workspace, stream)
     _check(lib.kfac_precondition_grouped(arr, len(grads), ws, nbytes, _stream(stream)))
     return outs
 
@@ -264,7 +272,7 @@ class InvertPlan:
         self._keep = (list(factors), list(invs), infos)
         arr = _inv_items(factors, invs, infos)
         need = lib.kfac_invert_batched_workspace(arr, len(factors))
-        ws, nbytes, self._ws = _workspace(need, factors[0], workspace)
+        ws, nbytes, self._ws = _workspace(need, factors[0], workspace)  # kept for the plan's lifetime
         handle = ctypes.c_void_p()
         _check(lib.kfac_invert_plan_create(arr, len(factors), damping, ws, nbytes, ctypes.byref(handle)))
         self._h = handle

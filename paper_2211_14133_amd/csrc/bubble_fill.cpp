@@ -2,7 +2,9 @@
 // pipeline bubbles (section 3.1 of the paper) and the closed forms of its
 // performance model (section 3.3).  No device code here.
 #include <cstdint>
+#include <cstddef>
 #include <limits>
+#include <utility>
 #include <vector>
 
 #include "../../include/kfac.h"
@@ -31,8 +33,11 @@ kfac_status kfac_assign_work(int64_t n_bubbles, const double *bubble_start, cons
         prev_end = bubble_start[b] + bubble_length[b];
         if (bubble_length[b] > longest) longest = bubble_length[b];
     }
-    // cursor[s][b]: first free time of bubble b in pipeline step s, relative to that step's start
-    std::vector<std::vector<double>> cursor;
+    // busy[s][b]: the pieces already placed in bubble b of pipeline step s as (start, end) relative to
+    // that step's start, sorted by start.  A piece may go behind them or into a hole in front of one
+    // that had to wait for its release: a bubble is whatever part of it is still idle.
+    typedef std::vector<std::pair<double, double>> Pieces;
+    std::vector<std::vector<Pieces>> busy;
     std::vector<double> finish((size_t)n_works, 0.0);  // absolute completion time of each work
     int64_t chunk = 0, last_step = -1;
     for (int64_t w = 0; w < n_works; ++w) {
@@ -51,20 +56,28 @@ kfac_status kfac_assign_work(int64_t n_bubbles, const double *bubble_start, cons
             int64_t s = (int64_t)(ready / step_period);
             if (s < 0) s = 0;
             for (; s < MAX_PIPELINE_STEPS && !placed; ++s) {
-                while ((int64_t)cursor.size() <= s) cursor.emplace_back(bubble_start, bubble_start + n_bubbles);
+                while ((int64_t)busy.size() <= s) busy.emplace_back((size_t)n_bubbles);
                 const double base = (double)s * step_period;
-                for (int64_t b = 0; b < n_bubbles; ++b) {
-                    double t = cursor[(size_t)s][(size_t)b];
-                    if (ready - base > t) t = ready - base;
-                    if (t + dur <= bubble_start[b] + bubble_length[b]) {
-                        cursor[(size_t)s][(size_t)b] = t + dur;
-                        out_step[chunk] = s;
-                        out_bubble[chunk] = b;
-                        out_start[chunk] = t;
-                        ready = base + t + dur;
-                        if (s > last_step) last_step = s;
-                        placed = true;
-                        break;
+                for (int64_t b = 0; b < n_bubbles && !placed; ++b) {
+                    Pieces &pc = busy[(size_t)s][(size_t)b];
+                    const double bubble_end = bubble_start[b] + bubble_length[b];
+                    // holes in time order: in front of piece 0, between pieces, behind the last one
+                    double hole_begin = bubble_start[b];
+                    for (size_t h = 0; h <= pc.size(); ++h) {
+                        const double hole_end = h < pc.size() ? pc[h].first : bubble_end;
+                        double t = hole_begin;
+                        if (ready - base > t) t = ready - base;
+                        if (t + dur <= hole_end) {
+                            pc.insert(pc.begin() + (std::ptrdiff_t)h, std::make_pair(t, t + dur));
+                            out_step[chunk] = s;
+                            out_bubble[chunk] = b;
+                            out_start[chunk] = t;
+                            ready = base + t + dur;
+                            if (s > last_step) last_step = s;
+                            placed = true;
+                            break;
+                        }
+                        if (h < pc.size()) hole_begin = pc[h].second;
                     }
                 }
             }

@@ -308,7 +308,7 @@ __global__ void invert_clear_info_kernel(const PrepLaunch pl, int count)
     if (i < count) *pl.it[i].info = 0;
 }
 
-// dst = src + damping * I (full copy); a non-finite source element sets info = -1.
+// dst = src + damping * I (full copy); a non-finite element of the upper triangle sets info = -1.
 __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl)
 {
     const PrepItem &it = pl.it[blockIdx.y];
@@ -329,8 +329,9 @@ __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl
                     v.z = (c + 2 < d) ? src[c + 2] : 0.f;
                     v.w = 0.f;
                 }
-                if (!(fabsf(v.x) <= 3.0e38f) || !(fabsf(v.y) <= 3.0e38f) || !(fabsf(v.z) <= 3.0e38f) ||
-                    !(fabsf(v.w) <= 3.0e38f))
+                // only the upper triangle (column >= row) is input; what lies below it is copied but never used
+                if ((c + 0 >= r && !(fabsf(v.x) <= 3.0e38f)) || (c + 1 >= r && !(fabsf(v.y) <= 3.0e38f)) ||
+                    (c + 2 >= r && !(fabsf(v.z) <= 3.0e38f)) || (c + 3 >= r && !(fabsf(v.w) <= 3.0e38f)))
                     bad = true;
                 if (r >= c && r < c + 4) {
                     if (r == c) v.x += pl.damping;
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl
         } else {
             for (int c = threadIdx.x; c < d; c += blockDim.x) {
                 float v = src[c];
-                if (!(fabsf(v) <= 3.0e38f)) bad = true;
+                if (c >= r && !(fabsf(v) <= 3.0e38f)) bad = true;
                 if (r == c) v += pl.damping;
                 dst[c] = v;
             }

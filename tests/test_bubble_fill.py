@@ -44,11 +44,37 @@ def test_assign_work_by_hand():
                                        [[], [0], [1]])
     assert placements == [[(0, 0, 1.0)], [(0, 0, 1.5), (0, 1, 5.0)], [(1, 0, 1.0)]]
     assert steps == 2
-    # release time inside a bubble: the piece starts at its release, not at the bubble start
+    # release time inside a bubble: the piece starts at its release, not at the bubble start; the idle
+    # time it leaves in front of itself is still part of the bubble, and the next piece of the queue
+    # (free from the start, too long for the 0.5 behind the first piece) goes there
     placements, steps = po.assign_work([0.0], [4.0], 5.0, [[1.0], [1.0]], [2.5, 0.0], [[], []])
-    assert placements == [[(0, 0, 2.5)], [(1, 0, 0.0)]]  # the second piece no longer fits behind the first
+    assert placements == [[(0, 0, 2.5)], [(0, 0, 0.0)]] and steps == 1
     with pytest.raises(ValueError):
         po.assign_work([0.0], [1.0], 5.0, [[2.0]], [0.0], [[]])
+
+
+def test_assign_work_holes_by_hand():
+    """Worked on paper.  One bubble [0, 10) per step, period 12.
+    w0: released at 6, 2 long            -> [6, 8)                       idle: [0, 6) [8, 10)
+    w1: released at 0, 5 long            -> the hole in front: [0, 5)    idle: [5, 6) [8, 10)
+    w2: released at 0, chunks 1.5, 1.5   -> 1.5 does not fit [5, 6): [8, 9.5); the second chunk must follow
+                                            the first (>= 9.5) and 0.5 is left in this step -> next step [0, 1.5)
+    w3: after w1, 1 long                 -> [5, 6) exactly
+    w4: released at 9, 0.5 long          -> [9.5, 10)
+    w5: released at 0, 0.25 long         -> step 0 is full -> step 1 behind w2's second chunk: [1.5, 1.75)
+    """
+    chunk_times = [[2.0], [5.0], [1.5, 1.5], [1.0], [0.5], [0.25]]
+    release = [6.0, 0.0, 0.0, 0.0, 9.0, 0.0]
+    deps = [[], [], [], [1], [], []]
+    want = [[(0, 0, 6.0)], [(0, 0, 0.0)], [(0, 0, 8.0), (1, 0, 0.0)], [(0, 0, 5.0)], [(0, 0, 9.5)], [(1, 0, 1.5)]]
+    placements, steps = po.assign_work([0.0], [10.0], 12.0, chunk_times, release, deps)
+    assert placements == want and steps == 2
+    got, got_steps = k.kfac_assign_work([0.0], [10.0], 12.0, chunk_times, release, deps)
+    assert got == want and got_steps == 2
+    # two bubbles [0, 2) and [5, 7), period 8.  w0 (released 5.5) -> [5.5, 6.5).  w1 is released at 1.5: it never
+    # starts before that, so [1.5, 2) is too short, as are [5, 5.5) and [6.5, 7) -> first bubble of the next step
+    placements, steps = po.assign_work([0.0, 5.0], [2.0, 2.0], 8.0, [[1.0], [1.0]], [5.5, 1.5], [[], []])
+    assert placements == [[(0, 1, 5.5)], [(1, 0, 0.0)]] and steps == 2
 
 
 def _kfac_queue(depth, stage, n_micro, t_f, t_b, layers, t_curv_a, t_curv_b, inv_chunks):
@@ -112,8 +138,20 @@ def test_product_perf_model_matches_oracle():
             assert got[key] == pytest.approx(want[key], rel=1e-15, abs=0)
 
 
+def _holes_used(placements):
+    """Chunks that start in front of a chunk placed earlier in the same bubble instance."""
+    seen, n = {}, 0
+    for spots in placements:
+        for (step, b, t) in spots:
+            if any(t < t2 for t2 in seen.get((step, b), [])):
+                n += 1
+            seen.setdefault((step, b), []).append(t)
+    return n
+
+
 def test_product_assign_work_matches_oracle_exactly():
     rng = np.random.default_rng(1)
+    holes = 0
     for case in range(30):
         depth = int(rng.integers(2, 9))
         n_micro = int(rng.integers(1, 9))
@@ -139,6 +177,32 @@ def test_product_assign_work_matches_oracle_exactly():
         assert got_steps == want_steps
         assert got == want  # same arithmetic on the same doubles: exact
         _check_schedule(tl, period, chunk_times, release, deps, got)
+        holes += _holes_used(got)
+    assert holes == 0  # in a GPipe step every release time lies at or before the start of the next bubble
+
+
+def test_product_assign_work_matches_oracle_with_holes():
+    """Arbitrary bubbles and release times anywhere in the first steps: pieces that have to wait leave idle
+    time in front of themselves, which later pieces of the queue take."""
+    rng = np.random.default_rng(5)
+    holes = 0
+    for case in range(40):
+        nb = int(rng.integers(1, 5))
+        cuts = np.sort(rng.uniform(0.0, 10.0, 2 * nb))
+        bstart = [float(cuts[2 * i]) for i in range(nb)]
+        blen = [float(cuts[2 * i + 1] - cuts[2 * i]) for i in range(nb)]
+        period = 10.0 + float(rng.uniform(0, 1))
+        longest = max(blen)
+        n_works = int(rng.integers(10, 40))
+        chunk_times = [[float(x) for x in rng.uniform(0.0, 0.3 * longest, int(rng.integers(1, 4)))] for _ in range(n_works)]
+        release = [float(rng.uniform(0.0, 1.5 * period)) if rng.random() < 0.6 else 0.0 for _ in range(n_works)]
+        deps = [sorted(set(int(x) for x in rng.integers(0, w, int(rng.integers(0, 3))))) if w else [] for w in range(n_works)]
+        want, want_steps = po.assign_work(bstart, blen, period, chunk_times, release, deps)
+        got, got_steps = k.kfac_assign_work(bstart, blen, period, chunk_times, release, deps)
+        assert got == want and got_steps == want_steps
+        _check_schedule({"bubbles": list(zip(bstart, blen))}, period, chunk_times, release, deps, got)
+        holes += _holes_used(got)
+    assert holes >= 30
 
 
 def test_product_assign_work_rejects_bad_input():
