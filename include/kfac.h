@@ -19,9 +19,11 @@
  *    (the paper computes everything in fp32) unless a dtype argument says
  *    otherwise.  Leading dimensions (ld*) count elements between rows.
  *  - Ownership: every buffer, the workspace included, belongs to the caller.
- *    The library allocates no device memory, has no global state and keeps no
- *    pointer after a call returns (the one exception, the host-side plan of
- *    the chunked inversion, is described with it).
+ *    The library allocates no device memory and keeps no pointer after a call
+ *    returns (the one exception, the host-side plan of the chunked inversion,
+ *    is described with it).  On the host, the inversion and precondition calls
+ *    use a few KB to a few hundred KB of C++ heap for their bookkeeping while
+ *    they run (lists of launches and tasks), freed before they return.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Work is only enqueued; no call synchronises with the host.
  *  - `workspace` is device scratch of at least the size the matching
@@ -144,8 +146,8 @@ size_t kfac_invert_batched_workspace(const kfac_invert_item *items, int64_t coun
  * order, on any stream, between other work.  Running all steps is exactly
  * kfac_invert_batched.  `inv` buffers are written by the last steps only.
  *
- * The plan lives in host memory obtained from the C++ heap (this is the only
- * allocation the library makes; it never allocates device memory).  It keeps
+ * The plan lives in host memory obtained from the C++ heap (about 4 KB per
+ * step: the launch descriptors; the library never allocates device memory).  It keeps
  * the device pointers of `items` and of `workspace`: those must stay valid,
  * and the workspace must not be used by anything else, until the plan has
  * run to its end.  A plan can be reset and run again (next refresh).

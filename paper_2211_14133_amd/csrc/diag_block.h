@@ -8,12 +8,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "tn_gemm.h"
+
 namespace kfac {
 
-constexpr int NB = 128;  // panel width of the blocked factorisation (= tile size of the engine)
-static_assert(NB == 128, "must equal INV_NB of the contraction engine");
-constexpr int DIAG_THREADS = 256;
-constexpr int DIAG_MAX_ITEMS = 80;
+constexpr int NB = INV_NB;  // panel width of the blocked factorisation (= tile size of the engine)
+static_assert(NB == 128, "the sub-block structure below is written for 128");
+constexpr int DIAG_THREADS = TN_THREADS;
 constexpr int PREP_MAX_ITEMS = 80;
 
 struct DiagItem {
@@ -24,10 +25,6 @@ struct DiagItem {
     int ldf;
     int lds;
     int pivot_base;  // index of the block's first row in the whole matrix
-};
-
-struct DiagLaunch {
-    DiagItem it[DIAG_MAX_ITEMS];
 };
 
 constexpr int SB = 32;        // sub-block handled by one wave
@@ -162,12 +159,9 @@ __device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o
 // in *info as its 1-based index in the whole matrix (first failure wins); what
 // follows it in that matrix is not meaningful (NaNs) and the caller discards the
 // result.
-__global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaunch dl)
+// Fs: U above the diagonal, its mirror below;  Ss: W = U^-1 above the diagonal, its mirror below (LDS, NB x LDT each)
+__device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*Fs)[LDT], float (*Ss)[LDT])
 {
-    __shared__ __attribute__((aligned(16))) float Fs[NB][LDT];  // U above the diagonal, its mirror below
-    __shared__ __attribute__((aligned(16))) float Ss[NB][LDT];  // W = U^-1 above the diagonal, its mirror below
-
-    const DiagItem &it = dl.it[blockIdx.x];
     const int n = it.n;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -286,6 +280,40 @@ __global__ __launch_bounds__(DIAG_THREADS) void diag_block_kernel(const DiagLaun
             }
         }
     }
+}
+
+// The launches of the blocked inversion that contain diagonal blocks: a workgroup either factors one
+// diagonal block (INV_DIAG node) or computes one tile of a contraction node, exactly as in
+// invert_gemm_kernel.  The diagonal-block algorithm needs 132 KB of LDS, so one workgroup runs per CU;
+// the few workgroups with diagonal blocks are on the critical path of the factorisation while the
+// tiles of independent work keep the other CUs busy.
+__global__ __launch_bounds__(TN_THREADS, 1) void invert_diag_gemm_kernel(const InvLaunch lp)
+{
+    __shared__ __attribute__((aligned(16))) float lds[2 * NB * LDT];
+    static_assert(2 * NB * LDT >= TN_LDS_STAGES * BK * (BM + BN), "the engine's slab ring fits into the same LDS");
+    const int logical = tn_logical_tile(blockIdx.x, gridDim.x, lp.c);
+    if (logical < 0) return;  // whole workgroup
+    TnProblem pr;
+    TnAttr at;
+    const TnTile tl = tn_locate(lp, logical, pr, at);
+    const InvNode &nd = lp.n[tl.prob];
+    if (nd.op == INV_DIAG) {
+        const InvMatDesc &mt = lp.m[nd.mat];
+        const size_t q0 = (size_t)nd.a * NB, off = q0 * mt.ld + q0;
+        DiagItem it;
+        it.F = lp.mat_f(nd.mat) + off;
+        it.S = lp.mat_s(nd.mat) + off;
+        it.info = mt.info;
+        it.n = min(NB, (int)mt.d - (int)q0);
+        it.ldf = mt.ld;
+        it.lds = mt.ld;
+        it.pivot_base = (int)q0;
+        diag_block_body(it, reinterpret_cast<float (*)[LDT]>(lds), reinterpret_cast<float (*)[LDT]>(lds + NB * LDT));
+        return;
+    }
+    tn_tile_work(lp, pr, at, tl, logical,
+                 *reinterpret_cast<float (*)[TN_LDS_STAGES][BK][BM]>(lds),
+                 *reinterpret_cast<float (*)[TN_LDS_STAGES][BK][BN]>(lds + TN_LDS_STAGES * BK * BM));
 }
 
 struct PrepItem {

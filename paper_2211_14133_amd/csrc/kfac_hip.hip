@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <new>
@@ -34,13 +35,6 @@ inline bool ws_ok(const void *ws, size_t have, size_t need)
     return ws != nullptr && have >= need && (reinterpret_cast<uintptr_t>(ws) % WS_ALIGN) == 0;
 }
 
-// One kernel launch (or a launch with its second pass) of a recorded sequence.
-struct PlanStep {
-    std::function<void(hipStream_t)> run;
-    double flops;  // model cost: multiply-adds x 2 of the launch (0 for copies)
-};
-typedef std::vector<PlanStep> PlanSteps;
-
 inline double tn_problem_flops(int M, int N, int K, int tile_mode, int mask_a, int mask_b)
 {
     double f = 2.0 * M * N * K;
@@ -49,10 +43,69 @@ inline double tn_problem_flops(int M, int N, int K, int tile_mode, int mask_a, i
     return f;
 }
 
+// Where the launches of a work item go: straight to a stream, or into a recorded plan.
+struct Emitter {
+    virtual ~Emitter() {}
+    virtual void prep(const PrepLaunch &pl, int count, int grid_x) = 0;
+    virtual void inv(const InvLaunch &lp, int grid, bool with_diag, double flops) = 0;
+    virtual void tn(const TnLaunch &lp, int grid, int tiles, double flops) = 0;
+};
+
+void launch_prep(hipStream_t s, const PrepLaunch &pl, int count, int grid_x)
+{
+    hipLaunchKernelGGL(invert_clear_info_kernel, dim3(1), dim3(128), 0, s, pl, count);
+    hipLaunchKernelGGL(invert_prepare_kernel, dim3(grid_x, (unsigned)count), dim3(256), 0, s, pl);
+}
+
+void launch_inv(hipStream_t s, const InvLaunch &lp, int grid, bool with_diag)
+{
+    if (with_diag)
+        hipLaunchKernelGGL(invert_diag_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
+    else
+        hipLaunchKernelGGL(invert_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
+}
+
+void launch_tn(hipStream_t s, const TnLaunch &lp, int grid, int tiles)
+{
+    hipLaunchKernelGGL(tn_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
+    if (lp.c.splits > 1) hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / lp.c.splits), dim3(TN_THREADS), 0, s, lp);
+}
+
+struct StreamEmitter : Emitter {
+    hipStream_t s;
+    explicit StreamEmitter(hipStream_t st) : s(st) {}
+    void prep(const PrepLaunch &pl, int count, int grid_x) override { launch_prep(s, pl, count, grid_x); }
+    void inv(const InvLaunch &lp, int grid, bool with_diag, double) override { launch_inv(s, lp, grid, with_diag); }
+    void tn(const TnLaunch &lp, int grid, int tiles, double) override { launch_tn(s, lp, grid, tiles); }
+};
+
+// One step of a recorded sequence: a kernel launch (with its helper launch, if it has one).
+struct PlanStep {
+    std::function<void(hipStream_t)> run;
+    double flops;  // model cost: multiply-adds x 2 of the launch (0 for copies)
+};
+typedef std::vector<PlanStep> PlanSteps;
+
+struct RecordEmitter : Emitter {
+    PlanSteps &steps;
+    explicit RecordEmitter(PlanSteps &st) : steps(st) {}
+    void prep(const PrepLaunch &pl, int count, int grid_x) override
+    {
+        steps.push_back(PlanStep{[pl, count, grid_x](hipStream_t s) { launch_prep(s, pl, count, grid_x); }, 0.0});
+    }
+    void inv(const InvLaunch &lp, int grid, bool with_diag, double flops) override
+    {
+        steps.push_back(PlanStep{[lp, grid, with_diag](hipStream_t s) { launch_inv(s, lp, grid, with_diag); }, flops});
+    }
+    void tn(const TnLaunch &lp, int grid, int tiles, double flops) override
+    {
+        steps.push_back(PlanStep{[lp, grid, tiles](hipStream_t s) { launch_tn(s, lp, grid, tiles); }, flops});
+    }
+};
+
 // Collects problems that share the launch parameters and sends them to the
-// engine in chunks of at most TN_MAX_PROBLEMS (or records the launches).
+// engine in chunks of at most TN_MAX_PROBLEMS.
 struct TnBatch {
-    PlanSteps *rec = nullptr;
     std::vector<TnProblem> probs;
     int tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE, splits = 1;
     float alpha = 1.f, beta = 0.f;
@@ -70,17 +123,19 @@ struct TnBatch {
         probs.push_back(p);
     }
 
-    hipError_t launch(hipStream_t stream)
+    void launch(Emitter &em)
     {
         size_t i = 0;
         while (i < probs.size()) {
             TnLaunch lp;
             std::memset(&lp, 0, sizeof(lp));
             int tiles = 0, cnt = 0;
+            double fl = 0.0;
             while (i < probs.size() && cnt < TN_MAX_PROBLEMS) {
                 lp.p[cnt] = probs[i];
                 lp.p[cnt].tile_begin = tiles;
                 tiles += tn_tiles(probs[i].M, probs[i].N, tile_mode) * splits;
+                fl += tn_problem_flops(probs[i].M, probs[i].N, probs[i].K, tile_mode, mask_a, mask_b);
                 ++cnt;
                 ++i;
             }
@@ -93,26 +148,9 @@ struct TnBatch {
             lp.c.beta = beta;
             lp.c.partial = partial;
             const int grid = tn_balance_xcds(lp, tiles);
-            if (rec != nullptr) {
-                double fl = 0.0;
-                for (int k = 0; k < cnt; ++k) fl += tn_problem_flops(lp.p[k].M, lp.p[k].N, lp.p[k].K, tile_mode, mask_a, mask_b);
-                const int sp = splits;
-                rec->push_back(PlanStep{[lp, tiles, sp, grid](hipStream_t s) {
-                                            hipLaunchKernelGGL(tn_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
-                                            if (sp > 1)
-                                                hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / sp), dim3(TN_THREADS), 0, s, lp);
-                                        },
-                                        fl});
-                continue;
-            }
-            hipLaunchKernelGGL(tn_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, stream, lp);
-            if (splits > 1)
-                hipLaunchKernelGGL(tn_reduce_kernel, dim3(tiles / splits), dim3(TN_THREADS), 0, stream, lp);
-            const hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
+            em.tn(lp, grid, tiles, fl);
         }
         probs.clear();
-        return hipSuccess;
     }
 };
 
@@ -170,100 +208,264 @@ inline size_t invert_item_bytes(int64_t d)
 struct InvMat {
     float *F, *S;
     int d, ld, nblk;
+    unsigned f_off;  // offset of F in the workspace in 256-byte units
     float *inv;
     int ldi;
     int *info;
 };
 
-struct TriNode {
-    int mat, a, b, c;  // matrix, first block, blocks in the first part, blocks in the second part
+// A node of the inversion before it has a place in a launch.
+struct NodeSpec {
+    unsigned char mat, a, b, c, op, r0, rn;
 };
 
-// Balanced splitting of block range [lo, hi): returns the height of the node and
-// files it under that height.  Nodes of equal height are independent.
-int build_tree(int mat, int lo, int hi, std::vector<std::vector<TriNode>> &levels)
-{
-    if (hi - lo <= 1) return 0;
-    const int mid = lo + (hi - lo + 1) / 2;
-    const int hl = build_tree(mat, lo, mid, levels);
-    const int hr = build_tree(mat, mid, hi, levels);
-    const int h = 1 + std::max(hl, hr);
-    if ((int)levels.size() <= h) levels.resize(h + 1);
-    levels[h].push_back(TriNode{mat, lo, mid - lo, hi - mid});
-    return h;
-}
+constexpr int SUPER_PANEL = 4;  // block rows factored between two updates of the rest of the matrix (K = 512)
 
-// Sends the nodes of one phase of the inversion to invert_gemm_kernel, as many per
-// launch as the kernel arguments hold.
-struct InvBatch {
-    PlanSteps *rec = nullptr;
-    const std::vector<InvMat> &mats;
-    std::vector<TriNode> nodes;
-    int op = 0, tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE, reverse_cols = 0;
-    float alpha = 1.f, beta = 0.f;
+// Builds the launch sequence of a batched inversion.
+//
+// The factorisation is a chain of short dependent launches (per block row: update the row, factor
+// the diagonal block, solve the panel) that occupy a fraction of the chip.  Everything else - the
+// update of the part of the matrix that the chain does not need yet, and the products of the
+// triangular inverse, which only need block rows that are already final - is cut into tasks.  A task
+// belongs to a group; a group may depend on other groups, and a task is placed in a launch only if
+// every group it depends on was completed by earlier launches.  Tasks run
+//   * in the launches of the chain that factor diagonal blocks (one workgroup per CU, most CUs free):
+//     short tasks ride along there, as the second list of the engine's tile order;
+//   * in launches of their own when a node of the chain needs a group (the rows a super-panel is about
+//     to factor need every earlier update) or when the chain has ended: such a launch takes every
+//     task that is ready, whatever its operation.
+class InvScheduler {
+public:
+    InvScheduler(const std::vector<InvMat> &mats, float *ws, Emitter &em) : mats_(mats), ws_(ws), em_(em) {}
 
-    explicit InvBatch(const std::vector<InvMat> &m) : mats(m) {}
+    int new_group(const std::vector<int> &deps)
+    {
+        groups_.push_back(Group{0, -1, deps});
+        return (int)groups_.size() - 1;
+    }
 
-    void add(int mat, int a, int b = 0, int c = 0) { nodes.push_back(TriNode{mat, a, b, c}); }
+    // urgent: has a deadline inside the factorisation (deferred row updates); otherwise bulk work
+    void push(const NodeSpec &n, int group, bool urgent)
+    {
+        Task t;
+        t.n = n;
+        t.group = group;
+        shape(n, t.tiles, t.cost, t.flops, &t.longest);
+        if (t.tiles == 0) return;
+        groups_[(size_t)group].pending++;
+        (urgent ? urgent_ : bulk_).push_back(t);
+        (urgent ? urgent_cost_ : bulk_cost_) += t.cost;
+    }
 
-    hipError_t launch(hipStream_t stream)
+    // One launch of the chain: its own nodes `crit` plus tasks that ride along.
+    bool launch(const std::vector<NodeSpec> &crit, bool with_diag)
     {
         size_t i = 0;
-        while (i < nodes.size()) {
-            InvLaunch lp;
-            std::memset(&lp, 0, sizeof(lp));
-            for (size_t k = 0; k < mats.size(); ++k) {
-                lp.m[k].F = mats[k].F;
-                lp.m[k].S = mats[k].S;
-                lp.m[k].d = mats[k].d;
-                lp.m[k].ld = mats[k].ld;
-            }
-            int tiles = 0, cnt = 0;
-            while (i < nodes.size() && cnt < INV_MAX_NODES) {
-                const TriNode &nd = nodes[i++];
-                const InvDims dm = inv_dims(op, mats[(size_t)nd.mat].d, nd.a, nd.b, nd.c);
-                if (dm.M <= 0 || dm.N <= 0) continue;
-                lp.n[cnt].mat = (unsigned char)nd.mat;
-                lp.n[cnt].a = (unsigned char)nd.a;
-                lp.n[cnt].b = (unsigned char)nd.b;
-                lp.n[cnt].c = (unsigned char)nd.c;
-                lp.n[cnt].tile_begin = tiles;
-                tiles += tn_tiles(dm.M, dm.N, tile_mode);
-                ++cnt;
-            }
-            if (cnt == 0) continue;
-            lp.c.count = cnt;
-            lp.c.tile_mode = tile_mode;
-            lp.c.mask_a = mask_a;
-            lp.c.mask_b = mask_b;
-            lp.c.splits = 1;
-            lp.c.alpha = alpha;
-            lp.c.beta = beta;
-            lp.c.reverse_cols = reverse_cols;
-            lp.op = op;
-            const int grid = tn_balance_xcds(lp, tiles);
-            if (rec != nullptr) {
-                double fl = 0.0;
-                for (int k = 0; k < cnt; ++k) {
-                    const InvDims dm = inv_dims(op, lp.m[lp.n[k].mat].d, lp.n[k].a, lp.n[k].b, lp.n[k].c);
-                    fl += tn_problem_flops(dm.M, dm.N, dm.K, tile_mode, mask_a, mask_b);
-                }
-                rec->push_back(PlanStep{[lp, grid](hipStream_t s) {
-                                            hipLaunchKernelGGL(invert_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
-                                        },
-                                        fl});
-                continue;
-            }
-            hipLaunchKernelGGL(invert_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, stream, lp);
-            const hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
-        }
-        nodes.clear();
-        return hipSuccess;
+        do {
+            // leave room for some tasks even when a launch has many nodes of its own
+            const size_t n = std::min(crit.size() - i, (size_t)INV_MAX_NODES - 32);
+            if (!emit(crit.data() + i, n, with_diag, false)) return false;
+            i += n;
+        } while (i < crit.size());
+        return true;
     }
+
+    // Runs tasks until the groups are complete (needed when a node of the chain depends on them).
+    bool finish_groups(const std::vector<int> &gs)
+    {
+        for (;;) {
+            bool open = false;
+            for (int g : gs)
+                if (g >= 0 && groups_[(size_t)g].pending > 0) open = true;
+            if (!open) return true;
+            if (!emit(nullptr, 0, false, true)) return false;
+        }
+    }
+
+    bool finish_all()
+    {
+        while (head_u_ < urgent_.size() || head_b_ < bulk_.size())
+            if (!emit(nullptr, 0, false, true)) return false;
+        return true;
+    }
+
+    int launches() const { return launch_idx_; }
+
+private:
+    struct Task {
+        NodeSpec n;
+        int group, tiles, cost, longest = 0;  // longest: cost of its longest tile
+        double flops;
+        bool done = false;
+    };
+    struct Group {
+        int pending, last_launch;
+        std::vector<int> deps;
+    };
+
+    void shape(const NodeSpec &n, int &tiles, int &cost, double &flops, int *longest = nullptr) const
+    {
+        if (longest) *longest = 0;
+        const InvMat &m = mats_[n.mat];
+        const InvDims dm = inv_dims(n.op, m.d, n.a, n.b, n.c, n.r0, n.rn);
+        tiles = cost = 0;
+        flops = 0.0;
+        if (dm.M <= 0 || dm.N <= 0) return;
+        if (n.op == INV_DIAG) {
+            tiles = 1;
+            cost = INV_DIAG_COST;
+            flops = 2.0 / 3.0 * dm.M * (double)dm.M * dm.M;
+            return;
+        }
+        const TnAttr at = InvLaunch::op_attr(n.op);
+        const int tm = (dm.M + BM - 1) / BM, tn = (dm.N + BN - 1) / BN;
+        for (int ti = 0; ti < tm; ++ti)
+            for (int tj = 0; tj < tn; ++tj) {
+                int kb, nslab;
+                tn_k_range(at, dm.K, ti * BM, tj * BN, kb, nslab);
+                cost += nslab + 4;
+                if (longest) *longest = std::max(*longest, nslab + 4);
+            }
+        tiles = tm * tn;
+        flops = tn_problem_flops(dm.M, dm.N, dm.K, at.tile_mode, at.mask_a, at.mask_b);
+    }
+
+    bool ready(const Task &t) const
+    {
+        for (int g : groups_[(size_t)t.group].deps) {
+            if (g < 0) continue;
+            const Group &d = groups_[(size_t)g];
+            if (d.pending > 0 || d.last_launch >= launch_idx_) return false;
+        }
+        return true;
+    }
+
+    // Takes ready tasks from a queue, in order, while they fit the budget.
+    void take(std::vector<Task> &q, size_t &head, long long &queue_cost, long long &budget, int longest_allowed,
+              InvLaunch &lp, int &cnt, int &tiles, double &flops)
+    {
+        constexpr size_t WINDOW = 2048;  // tasks looked at behind the first one that cannot go yet
+        for (size_t i = head; i < q.size() && i < head + WINDOW && cnt < INV_MAX_NODES && budget > 0; ++i) {
+            Task &t = q[i];
+            if (t.done || t.longest > longest_allowed || !ready(t)) continue;
+            add_node(lp, cnt, tiles, t.n, t.tiles);
+            flops += t.flops;
+            budget -= t.tiles;
+            queue_cost -= t.cost;
+            t.done = true;
+            Group &g = groups_[(size_t)t.group];
+            g.pending--;
+            g.last_launch = launch_idx_;
+        }
+        while (head < q.size() && q[head].done) ++head;
+    }
+
+    static void add_node(InvLaunch &lp, int &cnt, int &tiles, const NodeSpec &n, int ntiles)
+    {
+        InvNode &o = lp.n[cnt++];
+        o.mat = n.mat; o.a = n.a; o.b = n.b; o.c = n.c; o.op = n.op; o.r0 = n.r0; o.rn = n.rn; o.pad_ = 0;
+        o.tile_begin = tiles;
+        tiles += ntiles;
+    }
+
+    bool emit(const NodeSpec *crit, size_t ncrit, bool with_diag, bool drain)
+    {
+        InvLaunch lp;
+        std::memset(&lp, 0, sizeof(lp));
+        for (size_t k = 0; k < mats_.size(); ++k) {
+            lp.m[k].info = mats_[k].info;
+            lp.m[k].f_off = mats_[k].f_off;
+            lp.m[k].d = (unsigned short)mats_[k].d;
+            lp.m[k].ld = (unsigned short)mats_[k].ld;
+        }
+        lp.ws = ws_;
+        int cnt = 0, tiles = 0;
+        double flops = 0.0;
+        int own_longest = 0;
+        for (size_t i = 0; i < ncrit; ++i) {
+            int t, c;
+            double f;
+            shape(crit[i], t, c, f);
+            if (t == 0) continue;
+            add_node(lp, cnt, tiles, crit[i], t);
+            flops += f;
+            own_longest = std::max(own_longest, c / t);
+        }
+        const int first_tiles = tiles;
+        // Which tasks ride along.  A launch that only drains the queues takes everything that is ready.  A
+        // launch with diagonal blocks keeps a dozen to 72 CUs busy for about 40 us: tiles of up to that
+        // length on three quarters of the other CUs leave it 17 us longer and are done at twice the rate
+        // they reach in a launch of their own.  The panel solves and row updates of the chain take nothing
+        // along: they are shorter than any task, and measured with riders they lost as much time as the
+        // riders would have taken alone (12.4 - 12.6 against 12.2 ms for the BERT-Large stage).
+        const int slots = 256;  // one workgroup per CU in a launch with diagonal blocks
+        long long budget = drain ? (1 << 20) : (with_diag ? std::max(0, slots * 3 / 4 - first_tiles) : 0);
+        const int longest_allowed = drain ? (1 << 30) : std::max(own_longest, INV_DIAG_COST);
+        take(urgent_, head_u_, urgent_cost_, budget, longest_allowed, lp, cnt, tiles, flops);
+        take(bulk_, head_b_, bulk_cost_, budget, longest_allowed, lp, cnt, tiles, flops);
+        if (cnt == 0) return !drain;  // draining with nothing that can run: a dependency cycle (cannot happen)
+        lp.c.count = cnt;
+        lp.c.splits = 1;
+        if (!in_bounds(lp, cnt)) return false;
+        const int grid = tn_balance_xcds(lp, tiles, first_tiles);
+        em_.inv(lp, grid, with_diag, flops);
+        ++launch_idx_;
+        return true;
+    }
+
+    // Every operand of every node must lie inside the working arrays of its matrix: checked on the
+    // host, with the same descriptor arithmetic the kernel uses, before anything is launched.
+    bool in_bounds(const InvLaunch &lp, int cnt) const
+    {
+        for (int i = 0; i < cnt; ++i) {
+            const InvNode &nd = lp.n[i];
+            if (nd.mat >= mats_.size()) return false;
+            const InvMat &m = mats_[nd.mat];
+            if (lp.mat_f(nd.mat) != m.F || lp.mat_s(nd.mat) != m.S) return false;
+            const TnProblem pr = lp.problem(i);
+            auto inside = [&](const float *p, int rows, int cols) {
+                if (p == nullptr) return true;
+                const float *base = p >= m.S ? m.S : m.F;
+                if (p < base) return false;
+                const size_t off = (size_t)(p - base), r = off / (size_t)m.ld, c = off % (size_t)m.ld;
+                return r + (size_t)rows <= (size_t)m.d && c + (size_t)cols <= (size_t)m.d;
+            };
+            bool ok;
+            if (nd.op == INV_DIAG)
+                ok = (int)nd.a < m.nblk;
+            else
+                ok = inside(pr.A, pr.K, pr.M) && inside(pr.B, pr.K, pr.N) && inside(pr.C, pr.M, pr.N) && inside(pr.Ct, pr.N, pr.M);
+            if (!ok) return false;
+        }
+        return true;
+    }
+
+    const std::vector<InvMat> &mats_;
+    float *ws_;
+    Emitter &em_;
+    std::vector<Group> groups_;
+    std::vector<Task> urgent_, bulk_;
+    size_t head_u_ = 0, head_b_ = 0;
+    long long urgent_cost_ = 0, bulk_cost_ = 0;
+    int launch_idx_ = 0;
 };
 
-constexpr int SUPER_PANEL = 4;  // block rows factored before one trailing update (K = 512)
+// Balanced splitting of the block range [lo, hi) for the triangular inverse.
+struct TriNode {
+    int lo, mid, hi;
+    int left, right;   // children (-1: a single block, inverted by the diagonal-block node)
+    int g_y = -1, g_w = -1;  // groups of its two products
+};
+
+int build_tree(int lo, int hi, std::vector<TriNode> &nodes)
+{
+    if (hi - lo <= 1) return -1;
+    const int mid = lo + (hi - lo + 1) / 2;
+    const int l = build_tree(lo, mid, nodes);
+    const int r = build_tree(mid, hi, nodes);
+    nodes.push_back(TriNode{lo, mid, hi, l, r});
+    return (int)nodes.size() - 1;  // children come before their parent
+}
 
 }  // namespace
 
@@ -481,9 +683,9 @@ size_t kfac_invert_workspace(int64_t d)
 
 namespace {
 
-// Validates the arguments and records the launch sequence of a batched inversion.
-kfac_status invert_record(const kfac_invert_item *items, int64_t count, float damping,
-                          void *workspace, size_t workspace_bytes, PlanSteps &steps)
+// Validates the arguments and sends the launch sequence of a batched inversion to `em`.
+kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damping,
+                        void *workspace, size_t workspace_bytes, Emitter &em)
 {
     if (count == 0) return KFAC_OK;
     if (items == nullptr || count < 0) return KFAC_ERR_ARG;
@@ -507,13 +709,12 @@ kfac_status invert_record(const kfac_invert_item *items, int64_t count, float da
         for (int64_t i0 = 0; i0 < count; i0 += INV_MAX_MATS) {
             const int64_t n = std::min<int64_t>(INV_MAX_MATS, count - i0);
             const size_t bytes = kfac_invert_batched_workspace(items + i0, n);
-            const kfac_status stt = invert_record(items + i0, n, damping, base, bytes, steps);
+            const kfac_status stt = invert_emit(items + i0, n, damping, base, bytes, em);
             if (stt != KFAC_OK) return stt;
             base += bytes;
         }
         return KFAC_OK;
     }
-    hipStream_t st = nullptr;  // launches are recorded, not issued
 
     std::vector<InvMat> mats((size_t)count);
     char *cur = static_cast<char *>(workspace);
@@ -525,6 +726,7 @@ kfac_status invert_record(const kfac_invert_item *items, int64_t count, float da
         const size_t one = align_up((size_t)m.d * m.ld * sizeof(float), WS_ALIGN);
         m.F = reinterpret_cast<float *>(cur);
         m.S = reinterpret_cast<float *>(cur + one);
+        m.f_off = (unsigned)((size_t)(cur - static_cast<char *>(workspace)) / WS_ALIGN);
         cur += 2 * one;
         m.nblk = (m.d + NB - 1) / NB;
         m.inv = items[i].inv;
@@ -532,6 +734,7 @@ kfac_status invert_record(const kfac_invert_item *items, int64_t count, float da
         m.info = items[i].info_dev;
         max_blk = std::max(max_blk, m.nblk);
     }
+    if ((size_t)(cur - static_cast<char *>(workspace)) / WS_ALIGN > 0xFFFFFFFFull) return KFAC_ERR_UNSUPPORTED;
 
     // 1. info = 0; working copy F = factor + damping I.
     for (size_t i0 = 0; i0 < mats.size(); i0 += PREP_MAX_ITEMS) {
@@ -550,101 +753,107 @@ kfac_status invert_record(const kfac_invert_item *items, int64_t count, float da
             dmax = std::max(dmax, m.d);
         }
         pl.damping = damping;
-        const int nn = (int)n, gx = std::min(dmax, 512);
-        steps.push_back(PlanStep{[pl, nn, gx](hipStream_t s) {
-                                     hipLaunchKernelGGL(invert_clear_info_kernel, dim3(1), dim3(128), 0, s, pl, nn);
-                                     hipLaunchKernelGGL(invert_prepare_kernel, dim3(gx, (unsigned)nn), dim3(256), 0, s, pl);
-                                 },
-                                 0.0});
+        em.prep(pl, (int)n, std::min(dmax, 512));
     }
 
-    // 2. Blocked upper Cholesky M = U^T U with panel width NB, all matrices advanced together.
-    //    Inside a super-panel of SUPER_PANEL block rows the factorisation is left-looking (a block
-    //    row is brought up to date just before it is factored); the rest of the matrix is updated
-    //    once per super-panel, so that it is read and written SUPER_PANEL times less often.
-    InvBatch solve(mats), rowup(mats), trail(mats);
-    solve.rec = rowup.rec = trail.rec = &steps;
-    solve.op = INV_PANEL_SOLVE;
-    solve.mask_a = MASK_KEEP_K_LE;  // U_jj^-1 is upper triangular: rows k <= column
-    rowup.op = INV_ROW_UPDATE;
-    rowup.alpha = -1.f;
-    rowup.beta = 1.f;
-    trail.op = INV_TRAIL_UPDATE;
-    trail.tile_mode = TILE_UPPER;
-    trail.alpha = -1.f;
-    trail.beta = 1.f;
+    // 2. Blocked upper Cholesky M = U^T U with panel width NB, all matrices advanced together, and
+    //    W = U^-1 by pairwise merging of inverted diagonal ranges,
+    //        [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22],
+    //    interleaved: see InvScheduler.
+    //    Chain, per super-panel of SUPER_PANEL block rows [s0, e): for each row j, bring it up to date
+    //    with the rows s0..j-1 of the super-panel, factor its diagonal block, solve its panel.  After
+    //    the super-panel the next SUPER_PANEL block rows are updated with it at once (they are
+    //    factored next); the rows below are updated by tasks that ride along in later launches.
+    //    A product of the triangular inverse becomes a task as soon as the block rows it reads are
+    //    final: Y^T = (W11 U12)^T when the rows of the first part are, W12 = -Y W22 when all are.
+    InvScheduler sch(mats, static_cast<float *>(workspace), em);
+    std::vector<std::vector<TriNode>> trees(mats.size());
+    for (size_t mi = 0; mi < mats.size(); ++mi) build_tree(0, mats[mi].nblk, trees[mi]);
+    // group of the latest deferred update of block row i of matrix mi (-1: none)
+    std::vector<std::vector<int>> row_group(mats.size());
+    for (size_t mi = 0; mi < mats.size(); ++mi) row_group[mi].assign((size_t)mats[mi].nblk, -1);
+    constexpr int MERGE_TASK_TILES = 64;  // a product is cut into tasks of about this many tiles
+
+    auto push_product = [&](size_t mi, TriNode &t, int op) {
+        const InvMat &m = mats[mi];
+        const int b1 = (t.mid - t.lo) * NB, c1 = t.mid * NB, b2 = std::min((t.hi - t.mid) * NB, m.d - c1);
+        std::vector<int> deps;
+        int rows, cols;
+        if (op == INV_MERGE_YT) {
+            deps.push_back(t.left >= 0 ? trees[mi][(size_t)t.left].g_w : -1);
+            rows = b2; cols = b1;
+        } else {
+            deps.push_back(t.g_y);
+            deps.push_back(t.right >= 0 ? trees[mi][(size_t)t.right].g_w : -1);
+            rows = b1; cols = b2;
+        }
+        const int g = sch.new_group(deps);
+        (op == INV_MERGE_YT ? t.g_y : t.g_w) = g;
+        const int tr = (rows + NB - 1) / NB, tc = (cols + NB - 1) / NB;
+        const int step = std::max(1, MERGE_TASK_TILES / std::max(1, tc));
+        for (int r0 = 0; r0 < tr; r0 += step) {
+            NodeSpec n{(unsigned char)mi, (unsigned char)t.lo, (unsigned char)(t.mid - t.lo), (unsigned char)(t.hi - t.mid),
+                       (unsigned char)op, (unsigned char)r0, (unsigned char)std::min(step, tr - r0)};
+            sch.push(n, g, false);
+        }
+    };
+
+    std::vector<NodeSpec> crit;
+    std::vector<int> wait;
     for (int s0 = 0; s0 < max_blk; s0 += SUPER_PANEL) {
-        for (int j = s0; j < std::min(s0 + SUPER_PANEL, max_blk); ++j) {
-            std::vector<DiagItem> ditems;
-            for (size_t mi = 0; mi < mats.size(); ++mi) {
-                const InvMat &m = mats[mi];
-                if (j >= m.nblk) continue;
-                const int r0 = j * NB;
-                const int n = std::min(NB, m.d - r0);
-                DiagItem di;
-                di.F = m.F + (size_t)r0 * m.ld + r0;
-                di.S = m.S + (size_t)r0 * m.ld + r0;
-                di.info = m.info;
-                di.n = n;
-                di.ldf = m.ld;
-                di.lds = m.ld;
-                di.pivot_base = r0;
-                ditems.push_back(di);
-                if (j > s0) rowup.add((int)mi, s0, j);
-                if (m.d - r0 - n > 0) solve.add((int)mi, j);
+        const int e = std::min(s0 + SUPER_PANEL, max_blk);
+        for (int j = s0; j < e; ++j) {
+            if (j > s0) {
+                crit.clear();
+                for (size_t mi = 0; mi < mats.size(); ++mi)
+                    if (j < mats[mi].nblk)
+                        crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)s0, (unsigned char)j, (unsigned char)j, INV_ROW_UPDATE, 0, 0});
+                if (!crit.empty() && !sch.launch(crit, false)) return KFAC_ERR_HIP;
             }
-            if (rowup.launch(st) != hipSuccess) return KFAC_ERR_HIP;
-            for (size_t i0 = 0; i0 < ditems.size(); i0 += DIAG_MAX_ITEMS) {
-                const size_t n = std::min<size_t>(DIAG_MAX_ITEMS, ditems.size() - i0);
-                DiagLaunch dl;
-                std::memset(&dl, 0, sizeof(dl));
-                for (size_t i = 0; i < n; ++i) dl.it[i] = ditems[i0 + i];
-                const unsigned nb = (unsigned)n;
-                double fl = 0.0;
-                for (size_t i = 0; i < n; ++i) fl += 2.0 / 3.0 * dl.it[i].n * (double)dl.it[i].n * dl.it[i].n;
-                steps.push_back(PlanStep{[dl, nb](hipStream_t s) {
-                                             hipLaunchKernelGGL(diag_block_kernel, dim3(nb), dim3(DIAG_THREADS), 0, s, dl);
-                                         },
-                                         fl});
+            crit.clear();
+            for (size_t mi = 0; mi < mats.size(); ++mi)
+                if (j < mats[mi].nblk) crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)j, 0, 0, INV_DIAG, 0, 0});
+            if (!crit.empty() && !sch.launch(crit, true)) return KFAC_ERR_HIP;
+            // W_jj is there: second products of the tree nodes that end with block j, smallest first
+            for (size_t mi = 0; mi < mats.size(); ++mi)
+                for (TriNode &t : trees[mi])
+                    if (t.hi - 1 == j) push_product(mi, t, INV_MERGE_W);
+            crit.clear();
+            for (size_t mi = 0; mi < mats.size(); ++mi)
+                if (j + 1 < mats[mi].nblk) crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)j, 0, 0, INV_PANEL_SOLVE, 0, 0});
+            if (!crit.empty() && !sch.launch(crit, false)) return KFAC_ERR_HIP;
+            // block row j of U is final: first products of the tree nodes whose first part ends with it
+            for (size_t mi = 0; mi < mats.size(); ++mi)
+                for (TriNode &t : trees[mi])
+                    if (t.mid - 1 == j) push_product(mi, t, INV_MERGE_YT);
+        }
+        // the rows factored next take the update with this super-panel now ...
+        crit.clear();
+        wait.clear();
+        for (size_t mi = 0; mi < mats.size(); ++mi)
+            for (int i = e; i < std::min(e + SUPER_PANEL, mats[mi].nblk); ++i) {
+                crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)s0, (unsigned char)i, (unsigned char)e, INV_ROW_UPDATE, 0, 0});
+                wait.push_back(row_group[mi][(size_t)i]);  // after their earlier deferred updates
             }
-            if (solve.launch(st) != hipSuccess) return KFAC_ERR_HIP;
-        }
-        for (size_t mi = 0; mi < mats.size(); ++mi) {
-            const int e = std::min(s0 + SUPER_PANEL, mats[mi].nblk);
-            if (s0 < mats[mi].nblk && e < mats[mi].nblk) trail.add((int)mi, s0, e);
-        }
-        if (trail.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+        if (!sch.finish_groups(wait)) return KFAC_ERR_HIP;
+        if (!crit.empty() && !sch.launch(crit, false)) return KFAC_ERR_HIP;
+        // ... the rows below as tasks, each after the previous update of the same row
+        for (size_t mi = 0; mi < mats.size(); ++mi)
+            for (int i = e + SUPER_PANEL; i < mats[mi].nblk; ++i) {
+                const int g = sch.new_group(std::vector<int>{row_group[mi][(size_t)i]});
+                sch.push(NodeSpec{(unsigned char)mi, (unsigned char)s0, (unsigned char)i, (unsigned char)e, INV_ROW_UPDATE, 0, 0}, g, true);
+                row_group[mi][(size_t)i] = g;
+            }
     }
+    if (!sch.finish_all()) return KFAC_ERR_HIP;
 
-    // 3. W = U^-1 by pairwise merging of already inverted diagonal ranges:
-    //    [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
-    //    Y = U12 W22 goes where U12 was (the factor's upper blocks are no longer needed:
-    //    later merges read the mirrored copy below the diagonal).
-    std::vector<std::vector<TriNode>> levels;
-    for (size_t i = 0; i < mats.size(); ++i) build_tree((int)i, 0, mats[i].nblk, levels);
-    InvBatch s1(mats), s2(mats);
-    s1.rec = s2.rec = &steps;
-    s1.op = INV_MERGE_Y;
-    s1.mask_b = MASK_KEEP_K_LE;  // W22 upper triangular
-    s1.reverse_cols = 1;         // K grows with the tile column: last columns first
-    s2.op = INV_MERGE_W;
-    s2.mask_a = MASK_KEEP_K_GE;  // W11 read through its mirror below the diagonal
-    s2.alpha = -1.f;
-    for (size_t h = 1; h < levels.size(); ++h) {
-        s1.nodes = levels[h];
-        s2.nodes = levels[h];
-        if (s1.launch(st) != hipSuccess) return KFAC_ERR_HIP;
-        if (s2.launch(st) != hipSuccess) return KFAC_ERR_HIP;
-    }
-
-    // 4. inv = W W^T, read through the mirror: inv[i][j] = sum_{k >= max(i,j)} S[k][i] S[k][j].
+    // 3. inv = W W^T, read through the mirror: inv[i][j] = sum_{k >= max(i,j)} S[k][i] S[k][j].
     TnBatch lu;
-    lu.rec = &steps;
     lu.tile_mode = TILE_LOWER;
     lu.mask_a = MASK_KEEP_K_GE;
     lu.mask_b = MASK_KEEP_K_GE;
     for (const InvMat &m : mats) lu.add(m.S, m.ld, m.S, m.ld, m.inv, m.ldi, m.d, m.d, m.d, m.inv, m.ldi, m.info);
-    if (lu.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+    lu.launch(em);
     return KFAC_OK;
 }
 
@@ -661,12 +870,10 @@ extern "C" {
 kfac_status kfac_invert_batched(const kfac_invert_item *items, int64_t count, float damping,
                                 void *workspace, size_t workspace_bytes, void *stream)
 {
-    PlanSteps steps;
-    const kfac_status st = invert_record(items, count, damping, workspace, workspace_bytes, steps);
+    if (count == 0) return KFAC_OK;
+    StreamEmitter em(static_cast<hipStream_t>(stream));
+    const kfac_status st = invert_emit(items, count, damping, workspace, workspace_bytes, em);
     if (st != KFAC_OK) return st;
-    if (steps.empty()) return KFAC_OK;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    for (PlanStep &p : steps) p.run(hs);
     return hipGetLastError() == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
 }
 
@@ -677,7 +884,8 @@ kfac_status kfac_invert_plan_create(const kfac_invert_item *items, int64_t count
     *plan = nullptr;
     kfac_invert_plan *p = new (std::nothrow) kfac_invert_plan();
     if (p == nullptr) return KFAC_ERR_ARG;
-    const kfac_status st = invert_record(items, count, damping, workspace, workspace_bytes, p->steps);
+    RecordEmitter em(p->steps);
+    const kfac_status st = invert_emit(items, count, damping, workspace, workspace_bytes, em);
     if (st != KFAC_OK) {
         delete p;
         return st;
@@ -797,7 +1005,7 @@ kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64
     PrecPlan pl;
     if (!precondition_plan(items, count, pl)) return KFAC_ERR_ARG;
     if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    StreamEmitter em(static_cast<hipStream_t>(stream));
     char *tbase = static_cast<char *>(workspace);
     float *partial = reinterpret_cast<float *>(tbase + pl.t_bytes);
 
@@ -821,7 +1029,8 @@ kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64
                 else
                     b.add(tt, dout, it.a_inv, (int)it.lda, it.out, (int)it.ldo, dout, din, din);
             }
-            if (b.launch(st) != hipSuccess) return KFAC_ERR_HIP;
+            b.launch(em);
+            if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
             done += n;
         }
     }

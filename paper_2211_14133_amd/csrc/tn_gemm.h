@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 namespace kfac {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -49,9 +51,20 @@ struct TnProblem {
     int tile_begin;    // first logical tile (tile * splits + split) of this problem
 };
 
+// What may differ from problem to problem inside one launch.
+struct TnAttr {
+    int tile_mode;     // TILE_LOWER / TILE_UPPER need M == N
+    int mask_a;
+    int mask_b;
+    int reverse_cols;  // TILE_FULL only: walk the tile columns from the last to the first (set when K grows
+                       // with the column, so that the long tiles of a range run first, not last)
+    float alpha;
+    float beta;
+};
+
 struct TnCommon {
     int count;
-    int tile_mode;  // TILE_LOWER / TILE_UPPER need M == N
+    int tile_mode;  // the attributes of every problem of a general or curvature launch (see TnAttr)
     int mask_a;
     int mask_b;
     int splits;     // > 1: partial tiles go to `partial`, the reduce kernel finishes
@@ -59,10 +72,20 @@ struct TnCommon {
     float beta;
     float *partial;  // [total logical tiles][BM * BN]
     int slab_align;  // K ranges of split tiles are multiples of this many slabs (0 or 1: any)
-    int reverse_cols;  // TILE_FULL only: walk the tile columns from the last to the first (set when K grows
-                       // with the column, so that the long tiles of a range run first, not last)
-    int xcd_balanced;  // 0: each XCD takes a contiguous eighth of the tiles; 1: the ranges xcd_begin[]
-    int xcd_begin[9];  // XCD x works on logical tiles xcd_begin[x] .. xcd_begin[x+1]-1 (equal cost, see tn_balance_xcds)
+    int reverse_cols;
+    int xcd_balanced;  // 0: each XCD takes a contiguous eighth of the tiles; 1: the ranges below
+    // XCD x works on logical tiles xcd_begin[x] .. xcd_begin[x+1]-1 and then on xcd_begin2[x] .. xcd_begin2[x+1]-1
+    // (two lists of tiles, each dealt to all eight XCDs: work that the next launch waits for, then work that
+    // only fills the chip; see tn_balance_xcds)
+    int xcd_begin[9];
+    int xcd_begin2[9];
+    __host__ __device__ TnAttr attr() const
+    {
+        TnAttr a;
+        a.tile_mode = tile_mode; a.mask_a = mask_a; a.mask_b = mask_b; a.reverse_cols = reverse_cols;
+        a.alpha = alpha; a.beta = beta;
+        return a;
+    }
 };
 
 // General launch: up to TN_MAX_PROBLEMS arbitrary problems.
@@ -71,8 +94,11 @@ struct TnLaunch {
     static constexpr bool kAllowMask = true;
     TnProblem p[TN_MAX_PROBLEMS];
     TnCommon c;
+    static constexpr bool kHasDiag = false;
     __host__ __device__ int tile_begin(int i) const { return p[i].tile_begin; }
     __host__ __device__ TnProblem problem(int i) const { return p[i]; }
+    __host__ __device__ TnAttr attr(int) const { return c.attr(); }
+    __host__ __device__ int fixed_cost(int) const { return 0; }
 };
 
 // Curvature launch: factor = beta * factor + alpha * x^T x.  Both operands are x
@@ -93,8 +119,11 @@ template <bool PACKED>
 struct SyrkLaunchT {
     static constexpr bool kPackedBf16 = PACKED;
     static constexpr bool kAllowMask = false;
+    static constexpr bool kHasDiag = false;
     SyrkProblem p[SYRK_MAX_PROBLEMS];
     TnCommon c;
+    __host__ __device__ TnAttr attr(int) const { return c.attr(); }
+    __host__ __device__ int fixed_cost(int) const { return 0; }
     __host__ __device__ int tile_begin(int i) const { return p[i].tile_begin; }
     __host__ __device__ TnProblem problem(int i) const
     {
@@ -110,31 +139,42 @@ struct SyrkLaunchT {
 typedef SyrkLaunchT<false> SyrkLaunch;       // float32 activations / errors
 typedef SyrkLaunchT<true> SyrkLaunchPacked;  // bfloat16 in k-interleaved layout, bf16 MFMA
 
-// Inversion launch: the problems of one phase of the blocked inversion are
-// described by (matrix, up to three block indices); pointers and sizes follow
-// from the matrix table, so a whole stage's worth of matrices (and a few hundred
-// merge nodes) fits into the kernel arguments of a single launch.
+// Inversion launch: every problem of the blocked inversion is a node (operation, matrix, up to three
+// block indices, optionally a range of tile rows); pointers and sizes follow from the matrix table, so
+// a whole stage's worth of matrices and a couple of hundred nodes fit into the kernel arguments of a
+// single launch.  Nodes of different operations can share a launch: the host puts the nodes the next
+// launch waits for first and fills the rest of the chip with independent work (see tn_balance_xcds).
 constexpr int INV_NB = 128;  // panel width of the blocked factorisation (= BM = BN)
 constexpr int INV_MAX_MATS = 72;
-constexpr int INV_MAX_NODES = 224;
+constexpr int INV_MAX_NODES = 216;
+constexpr int INV_DIAG_COST = 40;  // a diagonal-block node takes about as long as a tile of 36 slabs
 
+// Working storage of matrix `mat`: F = working copy, then the factor U above the diagonal (the blocks
+// below the diagonal are scratch of the triangular inverse); S = W = U^-1 above the diagonal and its
+// mirror W^T below.
 enum InvOp : int {
-    INV_PANEL_SOLVE = 0,  // a = block row j:            U[j, j+1:] = W_jj^T M[j, j+1:]     (mirrored below)
-    INV_ROW_UPDATE = 1,   // a = first row s, b = row j:  M[j, j:] -= U[s:j, j]^T U[s:j, j:]
-    INV_TRAIL_UPDATE = 2, // a = s, b = e:                M[e:, e:] -= U[s:e, e:]^T U[s:e, e:] (upper tiles)
-    INV_MERGE_Y = 3,      // a = r0, b = b1, c = b2 (blocks): Y = U12 W22, stored over U12
-    INV_MERGE_W = 4       // same node:                  W12 = -W11 Y               (mirrored)
+    INV_PANEL_SOLVE = 0,  // a = block row j:                  U[j, j+1:] = W_jj^T M[j, j+1:]
+    INV_ROW_UPDATE = 1,   // a = s, b = block row j, c = e:    M[j, j:] -= U[s:e, j]^T U[s:e, j:]
+    // Triangular inverse of the block range [a, a+b+c) from its two inverted parts (b blocks, then c):
+    //   [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
+    INV_MERGE_YT = 2,     // Y^T = (W11 U12)^T, kept where the mirror of U12 would be (below the diagonal of F)
+    INV_MERGE_W = 3,      // W12 = -Y W22, written to S together with its mirror
+    INV_DIAG = 4          // a = block row j: factor the diagonal block and invert its factor (diag_block.h);
+                          // only in launches of invert_diag_gemm_kernel
 };
 
 struct InvMatDesc {
-    float *F;  // working copy / factor U above the diagonal, U^T below
-    float *S;  // W = U^-1 above the diagonal, W^T below
-    int d;
-    int ld;
+    int *info;            // status word of the matrix
+    unsigned f_off;       // F starts this many 256-byte units into the workspace; S follows F
+    unsigned short d;
+    unsigned short ld;
 };
 
 struct InvNode {
     unsigned char mat, a, b, c;
+    unsigned char op;
+    unsigned char r0, rn;  // merges only: tile rows r0 .. r0+rn-1 of the output (rn = 0: all)
+    unsigned char pad_;
     int tile_begin;
 };
 
@@ -142,21 +182,39 @@ struct InvDims {
     int M, N, K;
 };
 
-__host__ __device__ inline InvDims inv_dims(int op, int d, int a, int b, int c)
+// Rows of the output that a merge node covers: [first, first + count)
+__host__ __device__ inline void inv_row_range(int rows, int r0, int rn, int &first, int &count)
+{
+    first = 0;
+    count = rows;
+    if (rn != 0) {
+        first = min(rows, r0 * INV_NB);
+        count = min(rows - first, rn * INV_NB);
+    }
+}
+
+__host__ __device__ inline InvDims inv_dims(int op, int d, int a, int b, int c, int r0 = 0, int rn = 0)
 {
     InvDims r;
     if (op == INV_PANEL_SOLVE) {
-        const int r0 = a * INV_NB, n = min(INV_NB, d - r0);
-        r.M = n; r.N = d - r0 - n; r.K = n;
+        const int q0 = a * INV_NB, n = min(INV_NB, d - q0);
+        r.M = n; r.N = d - q0 - n; r.K = n;
     } else if (op == INV_ROW_UPDATE) {
-        const int r0 = b * INV_NB, n = min(INV_NB, d - r0);
-        r.M = n; r.N = d - r0; r.K = r0 - a * INV_NB;
-    } else if (op == INV_TRAIL_UPDATE) {
-        const int r0 = b * INV_NB;
-        r.M = d - r0; r.N = d - r0; r.K = r0 - a * INV_NB;
+        const int q0 = b * INV_NB, n = min(INV_NB, d - q0);
+        r.M = n; r.N = d - q0; r.K = (c - a) * INV_NB;
+    } else if (op == INV_DIAG) {
+        const int q0 = a * INV_NB, n = min(INV_NB, d - q0);
+        r.M = n; r.N = n; r.K = n;
     } else {
         const int b1 = b * INV_NB, c1 = a * INV_NB + b1, b2 = min(c * INV_NB, d - c1);
-        r.M = b1; r.N = b2; r.K = (op == INV_MERGE_Y) ? b2 : b1;
+        int first, count;
+        if (op == INV_MERGE_YT) {
+            inv_row_range(b2, r0, rn, first, count);
+            r.M = count; r.N = b1; r.K = b1;
+        } else {
+            inv_row_range(b1, r0, rn, first, count);
+            r.M = count; r.N = b2; r.K = b2;
+        }
     }
     return r;
 }
@@ -164,50 +222,70 @@ __host__ __device__ inline InvDims inv_dims(int op, int d, int a, int b, int c)
 struct InvLaunch {
     static constexpr bool kPackedBf16 = false;
     static constexpr bool kAllowMask = true;
+    static constexpr bool kHasDiag = true;
     InvMatDesc m[INV_MAX_MATS];
     InvNode n[INV_MAX_NODES];
     TnCommon c;
-    int op;
+    float *ws;  // workspace base
     __host__ __device__ int tile_begin(int i) const { return n[i].tile_begin; }
+    __host__ __device__ int fixed_cost(int i) const { return n[i].op == INV_DIAG ? INV_DIAG_COST : 0; }
+    __host__ __device__ float *mat_f(int mat) const { return ws + (size_t)m[mat].f_off * 64; }
+    __host__ __device__ float *mat_s(int mat) const
+    {
+        const size_t bytes = ((size_t)m[mat].d * m[mat].ld * sizeof(float) + 255) / 256 * 256;
+        return mat_f(mat) + bytes / sizeof(float);
+    }
+    __host__ __device__ static TnAttr op_attr(int op)
+    {
+        TnAttr t;
+        t.tile_mode = TILE_FULL;
+        t.mask_a = (op == INV_PANEL_SOLVE) ? MASK_KEEP_K_LE : MASK_NONE;  // W_jj is upper triangular: rows k <= column
+        t.mask_b = (op == INV_MERGE_YT) ? MASK_KEEP_K_GE                  // W11 read through its mirror
+                 : (op == INV_MERGE_W) ? MASK_KEEP_K_LE : MASK_NONE;      // W22 upper triangular
+        t.reverse_cols = (op == INV_MERGE_W) ? 1 : 0;                     // K grows with the tile column
+        t.alpha = (op == INV_ROW_UPDATE || op == INV_MERGE_W) ? -1.f : 1.f;
+        t.beta = (op == INV_ROW_UPDATE) ? 1.f : 0.f;
+        return t;
+    }
+    __host__ __device__ TnAttr attr(int i) const { return op_attr(n[i].op); }
     __host__ __device__ TnProblem problem(int i) const
     {
-        const InvNode nd = n[i];
+        const InvNode &nd = n[i];
         const InvMatDesc &mt = m[nd.mat];
         const size_t ld = (size_t)mt.ld;
-        const InvDims dm = inv_dims(op, mt.d, nd.a, nd.b, nd.c);
+        float *F = mat_f(nd.mat), *S = mat_s(nd.mat);
+        const InvDims dm = inv_dims(nd.op, mt.d, nd.a, nd.b, nd.c, nd.r0, nd.rn);
         TnProblem r;
         r.M = dm.M; r.N = dm.N; r.K = dm.K;
         r.lda = r.ldb = r.ldc = r.ldct = mt.ld;
         r.tile_begin = nd.tile_begin;
         r.guard = nullptr;
         r.Ct = nullptr;
-        if (op == INV_PANEL_SOLVE) {
-            const size_t r0 = (size_t)nd.a * INV_NB, nn = (size_t)dm.M;
-            r.A = mt.S + r0 * ld + r0;
-            r.B = mt.F + r0 * ld + r0 + nn;
-            r.C = mt.F + r0 * ld + r0 + nn;
-            r.Ct = mt.F + (r0 + nn) * ld + r0;
-        } else if (op == INV_ROW_UPDATE) {
-            const size_t k0 = (size_t)nd.a * INV_NB, r0 = (size_t)nd.b * INV_NB;
-            r.A = mt.F + k0 * ld + r0;
-            r.B = mt.F + k0 * ld + r0;
-            r.C = mt.F + r0 * ld + r0;
-        } else if (op == INV_TRAIL_UPDATE) {
-            const size_t k0 = (size_t)nd.a * INV_NB, r0 = (size_t)nd.b * INV_NB;
-            r.A = mt.F + k0 * ld + r0;
-            r.B = mt.F + k0 * ld + r0;
-            r.C = mt.F + r0 * ld + r0;
+        if (nd.op == INV_PANEL_SOLVE || nd.op == INV_DIAG) {
+            const size_t q0 = (size_t)nd.a * INV_NB, nn = (size_t)dm.M;
+            r.A = S + q0 * ld + q0;
+            r.B = F + q0 * ld + q0 + nn;
+            r.C = F + q0 * ld + q0 + nn;
+        } else if (nd.op == INV_ROW_UPDATE) {
+            const size_t k0 = (size_t)nd.a * INV_NB, q0 = (size_t)nd.b * INV_NB;
+            r.A = F + k0 * ld + q0;
+            r.B = F + k0 * ld + q0;
+            r.C = F + q0 * ld + q0;
         } else {
-            const size_t r0 = (size_t)nd.a * INV_NB, c1 = r0 + (size_t)nd.b * INV_NB;
-            if (op == INV_MERGE_Y) {
-                r.A = mt.F + c1 * ld + r0;
-                r.B = mt.S + c1 * ld + c1;
-                r.C = mt.F + r0 * ld + c1;
+            const size_t q0 = (size_t)nd.a * INV_NB, c1 = q0 + (size_t)nd.b * INV_NB;
+            const int b1 = nd.b * INV_NB, b2 = min(nd.c * INV_NB, (int)mt.d - (int)c1);
+            int first, count;
+            if (nd.op == INV_MERGE_YT) {
+                inv_row_range(b2, nd.r0, nd.rn, first, count);
+                r.A = F + q0 * ld + c1 + first;          // U12: K = b1 rows, its columns are the rows of Y^T
+                r.B = S + q0 * ld + q0;                  // mirror of W11: element (k, n) = W11[n][k], k >= n
+                r.C = F + (c1 + first) * ld + q0;        // Y^T, b2 x b1
             } else {
-                r.A = mt.S + r0 * ld + r0;
-                r.B = mt.F + r0 * ld + c1;
-                r.C = mt.S + r0 * ld + c1;
-                r.Ct = mt.S + c1 * ld + r0;
+                inv_row_range(b1, nd.r0, nd.rn, first, count);
+                r.A = F + c1 * ld + q0 + first;          // Y^T: K = b2 rows, its columns are the rows of W12
+                r.B = S + c1 * ld + c1;                  // W22
+                r.C = S + (q0 + first) * ld + c1;        // W12
+                r.Ct = S + c1 * ld + q0 + first;         // and its mirror
             }
         }
         return r;
@@ -282,13 +360,17 @@ __device__ inline int tn_logical_tile(int bid, int nblocks, const TnCommon &c)
 {
     if (!c.xcd_balanced) return tn_logical_tile(bid, nblocks);
     const int xcd = bid & 7;
-    const int t = c.xcd_begin[xcd] + (bid >> 3);
-    return t < c.xcd_begin[xcd + 1] ? t : -1;
+    int q = bid >> 3;
+    const int n1 = c.xcd_begin[xcd + 1] - c.xcd_begin[xcd];
+    if (q < n1) return c.xcd_begin[xcd] + q;
+    q -= n1;
+    const int t = c.xcd_begin2[xcd] + q;
+    return t < c.xcd_begin2[xcd + 1] ? t : -1;
 }
 
 // K range of a tile that can hold non-zeros under the operand masks: first row kb (a multiple
 // of BK) and length in slabs of BK.
-__host__ __device__ inline void tn_k_range(const TnCommon &lp, int K, int m0, int n0, int &kb, int &nslab)
+__host__ __device__ inline void tn_k_range(const TnAttr &lp, int K, int m0, int n0, int &kb, int &nslab)
 {
     kb = 0;
     int ke = K;
@@ -306,7 +388,7 @@ struct TnTile {
 };
 
 template <class L>
-__device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
+__device__ __forceinline__ TnTile tn_locate(const L &ll, int t, TnProblem &pr, TnAttr &at)
 {
     const TnCommon &lp = ll.c;
     TnTile tl;
@@ -319,27 +401,28 @@ __device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
             hi = mid;
     }
     pr = ll.problem(pi);
+    at = ll.attr(pi);
     const int local = t - pr.tile_begin;
     const int tile = local / lp.splits;
     tl.prob = pi;
     tl.split = local - tile * lp.splits;
     const int tm = (pr.M + BM - 1) / BM, tn = (pr.N + BN - 1) / BN;
-    if (lp.tile_mode == TILE_FULL) {
+    if (at.tile_mode == TILE_FULL) {
         tn_decode_full(tile, tm, tn, tl.ti, tl.tj);
-        if (lp.reverse_cols) tl.tj = tn - 1 - tl.tj;
+        if (at.reverse_cols) tl.tj = tn - 1 - tl.tj;
     } else {
         tn_decode_lower(tile, tm, tl.ti, tl.tj);
-        if (lp.tile_mode == TILE_UPPER) {
+        if (at.tile_mode == TILE_UPPER) {
             const int s = tl.ti;
             tl.ti = tl.tj;
             tl.tj = s;
         }
     }
-    tl.diag = (lp.tile_mode != TILE_FULL) && (tl.ti == tl.tj);
+    tl.diag = (at.tile_mode != TILE_FULL) && (tl.ti == tl.tj);
     tl.m0 = tl.ti * BM;
     tl.n0 = tl.tj * BN;
     int kb, nslab;
-    tn_k_range(lp, pr.K, tl.m0, tl.n0, kb, nslab);
+    tn_k_range(at, pr.K, tl.m0, tl.n0, kb, nslab);
     int per = (nslab + lp.splits - 1) / lp.splits;
     if (lp.slab_align > 1) per = (per + lp.slab_align - 1) / lp.slab_align * lp.slab_align;
     tl.kbase = kb;
@@ -348,52 +431,85 @@ __device__ inline TnTile tn_locate(const L &ll, int t, TnProblem &pr)
     return tl;
 }
 
-// Host side of the cost-balanced XCD ranges: cuts the logical tiles of a launch into eight
-// contiguous ranges of (nearly) equal cost, cost of a tile = slabs of its K range plus a
-// constant for its prologue and epilogue, and returns the number of workgroups to launch.
+// Host side of the cost-balanced XCD ranges.  Cost of a tile = slabs of its K range plus a constant for
+// its prologue and epilogue (or the fixed cost of a node that is not a contraction).  The logical tiles
+// [0, first_tiles) are cut into eight contiguous ranges of (nearly) equal cost, one per XCD; the tiles
+// [first_tiles, total_tiles), if any, are then dealt out so that the eight XCDs end up with equal total
+// cost.  Every XCD works through its first range, then through its second: what the next launch waits
+// for is spread over the whole chip and starts at once, the rest fills the chip behind it.  Returns the
+// number of workgroups to launch.
 template <class L>
-inline int tn_balance_xcds(L &ll, int total_tiles)
+inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1)
 {
     TnCommon &c = ll.c;
+    if (first_tiles < 0 || first_tiles > total_tiles) first_tiles = total_tiles;
     c.xcd_balanced = 0;
     if (total_tiles < 64) return total_tiles;
     constexpr int TILE_OVERHEAD = 4;
-    auto for_each_cost = [&](auto &&fn) {
-        for (int pi = 0; pi < c.count; ++pi) {
-            const TnProblem pr = ll.problem(pi);
-            const int end = pi + 1 < c.count ? ll.tile_begin(pi + 1) : total_tiles;
-            const int tm = (pr.M + BM - 1) / BM, tn = (pr.N + BN - 1) / BN;
-            for (int t = pr.tile_begin; t < end; ++t) {
-                const int local = t - pr.tile_begin, tile = local / c.splits, split = local - tile * c.splits;
-                int ti, tj;
-                if (c.tile_mode == TILE_FULL) {
-                    tn_decode_full(tile, tm, tn, ti, tj);
-                    if (c.reverse_cols) tj = tn - 1 - tj;
-                } else {
-                    tn_decode_lower(tile, tm, ti, tj);
-                    if (c.tile_mode == TILE_UPPER) { const int sw = ti; ti = tj; tj = sw; }
-                }
-                int kb, nslab;
-                tn_k_range(c, pr.K, ti * BM, tj * BN, kb, nslab);
-                int per = (nslab + c.splits - 1) / c.splits;
-                if (c.slab_align > 1) per = (per + c.slab_align - 1) / c.slab_align * c.slab_align;
-                const int kt0 = min(nslab, split * per), kt1 = min(nslab, kt0 + per);
-                fn(t, kt1 - kt0 + TILE_OVERHEAD);
+    std::vector<int> cost((size_t)total_tiles, 0);
+    for (int pi = 0; pi < c.count; ++pi) {
+        const TnProblem pr = ll.problem(pi);
+        const TnAttr at = ll.attr(pi);
+        const int fixed = ll.fixed_cost(pi);
+        const int end = pi + 1 < c.count ? ll.tile_begin(pi + 1) : total_tiles;
+        const int tm = (pr.M + BM - 1) / BM, tn = (pr.N + BN - 1) / BN;
+        for (int t = pr.tile_begin; t < end; ++t) {
+            if (fixed > 0) {
+                cost[(size_t)t] = fixed;
+                continue;
             }
+            const int local = t - pr.tile_begin, tile = local / c.splits, split = local - tile * c.splits;
+            int ti, tj;
+            if (at.tile_mode == TILE_FULL) {
+                tn_decode_full(tile, tm, tn, ti, tj);
+                if (at.reverse_cols) tj = tn - 1 - tj;
+            } else {
+                tn_decode_lower(tile, tm, ti, tj);
+                if (at.tile_mode == TILE_UPPER) { const int sw = ti; ti = tj; tj = sw; }
+            }
+            int kb, nslab;
+            tn_k_range(at, pr.K, ti * BM, tj * BN, kb, nslab);
+            int per = (nslab + c.splits - 1) / c.splits;
+            if (c.slab_align > 1) per = (per + c.slab_align - 1) / c.slab_align * c.slab_align;
+            const int kt0 = min(nslab, split * per), kt1 = min(nslab, kt0 + per);
+            cost[(size_t)t] = kt1 - kt0 + TILE_OVERHEAD;
         }
-    };
-    long long total = 0;
-    for_each_cost([&](int, int w) { total += w; });
-    int x = 1;
-    long long run = 0;
+    }
+    long long total1 = 0, total2 = 0;
+    for (int t = 0; t < first_tiles; ++t) total1 += cost[(size_t)t];
+    for (int t = first_tiles; t < total_tiles; ++t) total2 += cost[(size_t)t];
+    // first list: equal cost per XCD
+    long long run = 0, have[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int x = 0;
     c.xcd_begin[0] = 0;
-    for_each_cost([&](int t, int w) {
-        while (x < 8 && run * 8 >= (long long)x * total) c.xcd_begin[x++] = t;
-        run += w;
-    });
-    while (x <= 8) c.xcd_begin[x++] = total_tiles;
+    for (int t = 0; t < first_tiles; ++t) {
+        while (x < 7 && run * 8 >= (long long)(x + 1) * total1) c.xcd_begin[++x] = t;
+        run += cost[(size_t)t];
+        have[x] += cost[(size_t)t];
+    }
+    while (x < 8) c.xcd_begin[++x] = first_tiles;
+    // second list: each XCD is filled up to the common level
+    const long long level = (total1 + total2 + 7) / 8;
+    long long want[8], want_sum = 0;
+    for (int i = 0; i < 8; ++i) {
+        want[i] = level > have[i] ? level - have[i] : 0;
+        want_sum += want[i];
+    }
+    x = 0;
+    run = 0;
+    long long upto = want[0];
+    c.xcd_begin2[0] = first_tiles;
+    for (int t = first_tiles; t < total_tiles; ++t) {
+        while (x < 7 && run * want_sum >= upto * total2) {
+            c.xcd_begin2[++x] = t;
+            upto += want[x];
+        }
+        run += cost[(size_t)t];
+    }
+    while (x < 8) c.xcd_begin2[++x] = total_tiles;
     int longest = 0;
-    for (int i = 0; i < 8; ++i) longest = max(longest, c.xcd_begin[i + 1] - c.xcd_begin[i]);
+    for (int i = 0; i < 8; ++i)
+        longest = max(longest, c.xcd_begin[i + 1] - c.xcd_begin[i] + c.xcd_begin2[i + 1] - c.xcd_begin2[i]);
     c.xcd_balanced = 1;
     return 8 * longest;
 }
@@ -472,7 +588,7 @@ constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_W
 // the end of the K range are clamped to valid rows and their data is never
 // used, which keeps the loop body free of branches.
 template <bool FAST, bool MASKED>
-__device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, const TnTile &tl,
+__device__ __forceinline__ void tn_mainloop(const TnAttr &lp, const TnProblem &pr, const TnTile &tl,
                                    float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                    floatx16 (&sum)[2][2])
 {
@@ -615,6 +731,18 @@ __device__ inline void tn_mainloop(const TnCommon &lp, const TnProblem &pr, cons
         for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
 }
 
+// Values that are the same in every lane, moved to scalar registers.  The direct-to-LDS loads below take
+// their base address from scalar registers; where the compiler cannot prove that a problem descriptor
+// is wave-uniform (it is: it only depends on the workgroup index) this makes it so.
+__device__ inline int tn_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline const float *tn_uniform(const float *p)
+{
+    const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return reinterpret_cast<const float *>(((unsigned long long)hi << 32) | lo);
+}
+
 // 16 bytes per lane from global memory straight into LDS: lane l's data lands at
 // lds_addr + 16 * l (lds_addr, a byte address in LDS, is the same for the whole wave).  The global
 // address is a wave-uniform base (scalar registers) plus a 32-bit per-lane byte offset: a K loop
@@ -642,16 +770,16 @@ __device__ inline void tn_dma16_s(const float *sbase, unsigned voff, unsigned ld
 // whatever is not an MFMA must be little and sit between MFMAs.  The loop is unrolled over
 // the four stages (LDS addresses become immediates), the loads take a scalar base that is
 // advanced with scalar arithmetic, and scheduling barriers pin the order written here.
-__device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
+__device__ __forceinline__ void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
                                           float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                           floatx16 (&sum)[2][2])
 {
     static_assert(TN_LDS_STAGES == 4, "the loop below is unrolled over four stages");
     const int tid = threadIdx.x;
-    const int K = pr.K;
-    const float *__restrict__ A = pr.A;
-    const float *__restrict__ B = pr.B;
-    const size_t lda = (size_t)pr.lda, ldb = (size_t)pr.ldb;
+    const int K = tn_uniform(pr.K);
+    const float *__restrict__ A = tn_uniform(pr.A);
+    const float *__restrict__ B = tn_uniform(pr.B);
+    const size_t lda = (size_t)tn_uniform(pr.lda), ldb = (size_t)tn_uniform(pr.ldb);
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int li = lane & 31, lh = lane >> 5;
@@ -665,10 +793,10 @@ __device__ inline void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nslab = tl.kt1 - tl.kt0;
+    const int nslab = tn_uniform(tl.kt1 - tl.kt0);
     if (nslab <= 0) return;
     float2 fa[2][4], fb[2][4];
-    int kd = tl.kbase + tl.kt0 * BK;  // first K row of the next slab to request (wave-uniform)
+    int kd = tn_uniform(tl.kbase + tl.kt0 * BK);  // first K row of the next slab to request (wave-uniform)
 
     // per-lane byte offsets of the four loads of a slab, relative to the slab's first row
     const unsigned va0 = (unsigned)(((size_t)drow * lda + tl.m0 + 4 * li) * sizeof(float));
@@ -1009,15 +1137,13 @@ __device__ inline void tn_mainloop_bf16_packed(const TnProblem &pr, const TnTile
         for (int j = 0; j < 2; ++j) sum[i][j] += acc[i][j];
 }
 
+// One output tile (already located: problem pr with attributes at, tile tl, logical index `logical`).
 template <class L>
-__device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN])
+__device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, const TnAttr &at, const TnTile &tl, int logical,
+                                    float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN])
 {
     const TnCommon &lp = ll.c;
     const int tid = threadIdx.x;
-    TnProblem pr;
-    const int logical = tn_logical_tile(blockIdx.x, gridDim.x, lp);
-    if (logical < 0) return;  // surplus workgroup of a short XCD range (the whole workgroup leaves)
-    const TnTile tl = tn_locate(ll, logical, pr);
     const int M = pr.M, N = pr.N;
 
     // vector loads need 16-byte aligned rows
@@ -1036,7 +1162,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
 #pragma unroll
             for (int r = 0; r < 16; ++r) sum[i][j][r] = 0.f;
 
-    const bool masked = L::kAllowMask && (lp.mask_a | lp.mask_b) != 0;
+    const bool masked = L::kAllowMask && (at.mask_a | at.mask_b) != 0;
     bool done = false;
     if constexpr (L::kPackedBf16) {
         tn_mainloop_bf16_packed(pr, tl, As, Bs, sum);
@@ -1057,8 +1183,8 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
                     // clipped K range holds whole rows.  Those slabs take the direct loop, which is
                     // faster than the masked one; short remainders are not worth its start-up.
                     int p0 = pr.K, p1 = 0;  // hull of the partly kept K rows
-                    if (lp.mask_a != MASK_NONE) { p0 = min(p0, tl.m0); p1 = max(p1, tl.m0 + BM); }
-                    if (lp.mask_b != MASK_NONE) { p0 = min(p0, tl.n0); p1 = max(p1, tl.n0 + BN); }
+                    if (at.mask_a != MASK_NONE) { p0 = min(p0, tl.m0); p1 = max(p1, tl.m0 + BM); }
+                    if (at.mask_b != MASK_NONE) { p0 = min(p0, tl.n0); p1 = max(p1, tl.n0 + BN); }
                     int s0 = max(tl.kt0, min(tl.kt1, (p0 - tl.kbase) / BK));             // first masked slab
                     int s1 = max(s0, min(tl.kt1, (p1 - tl.kbase + BK - 1) / BK));        // one past the last
                     constexpr int MIN_DIRECT = 8;
@@ -1071,23 +1197,23 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
                         __syncthreads();
                     }
                     seg.kt0 = s0; seg.kt1 = s1;
-                    tn_mainloop<true, true>(lp, pr, seg, As, Bs, sum);
+                    tn_mainloop<true, true>(at, pr, seg, As, Bs, sum);
                     if (s1 < tl.kt1) {
                         __syncthreads();
                         seg.kt0 = s1; seg.kt1 = tl.kt1;
                         tn_mainloop_direct(pr, seg, As, Bs, sum);
                     }
                 } else {
-                    tn_mainloop<false, true>(lp, pr, tl, As, Bs, sum);
+                    tn_mainloop<false, true>(at, pr, tl, As, Bs, sum);
                 }
                 done = true;
             }
         }
         if (!done) {
             if (fast_a && fast_b)
-                tn_mainloop<true, false>(lp, pr, tl, As, Bs, sum);
+                tn_mainloop<true, false>(at, pr, tl, As, Bs, sum);
             else
-                tn_mainloop<false, false>(lp, pr, tl, As, Bs, sum);
+                tn_mainloop<false, false>(at, pr, tl, As, Bs, sum);
         }
     }
 
@@ -1112,7 +1238,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
     float *__restrict__ C = pr.C;
     float *__restrict__ Ct = pr.Ct;
     const int ldc = pr.ldc, ldct = pr.ldct;
-    const float alpha = lp.alpha, beta = lp.beta;
+    const float alpha = at.alpha, beta = at.beta;
     const bool interior = (tl.m0 + BM <= M) && (tl.n0 + BN <= N) && !tl.diag;
     const bool fast_c = interior && ((ldc & 1) == 0) && ((reinterpret_cast<uintptr_t>(C) & 7) == 0);
 
@@ -1144,7 +1270,7 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
                     const int m = tl.m0 + wm + 2 * (8 * (r >> 2) + 4 * lh + (r & 3)) + bi;
                     const int n = tl.n0 + wn + 2 * li + bj;
                     float v = alpha * sum[bi][bj][r];
-                    if (m < M && n < N && tn_keep(tl.diag, lp.tile_mode, m, n)) {
+                    if (m < M && n < N && tn_keep(tl.diag, at.tile_mode, m, n)) {
                         float *dst = C + (size_t)m * ldc + n;
                         if (beta != 0.f) v += beta * (*dst);
                         *dst = v;
@@ -1170,12 +1296,23 @@ __device__ inline void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const int m = mq + e;
-                        const bool strict = !tl.diag || (m != n && tn_keep(true, lp.tile_mode, m, n));
+                        const bool strict = !tl.diag || (m != n && tn_keep(true, at.tile_mode, m, n));
                         if (m < M && n < N && strict) Ct[(size_t)n * ldct + m] = sum[e & 1][bj][4 * q + (e >> 1)];
                     }
                 }
             }
     }
+}
+
+template <class L>
+__device__ __forceinline__ void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN])
+{
+    const int logical = tn_logical_tile(blockIdx.x, gridDim.x, ll.c);
+    if (logical < 0) return;  // surplus workgroup of a short XCD range (the whole workgroup leaves)
+    TnProblem pr;
+    TnAttr at;
+    const TnTile tl = tn_locate(ll, logical, pr, at);
+    tn_tile_work(ll, pr, at, tl, logical, As, Bs);
 }
 
 // Second pass of a split-K launch: adds the partial tiles of each output tile in
@@ -1187,7 +1324,8 @@ __device__ inline void tn_reduce_body(const L &ll)
     const TnCommon &lp = ll.c;
     const int t0 = blockIdx.x * lp.splits;  // logical index of split 0 of this output tile
     TnProblem pr;
-    const TnTile tl = tn_locate(ll, t0, pr);
+    TnAttr at;
+    const TnTile tl = tn_locate(ll, t0, pr, at);
     if (pr.guard != nullptr && *pr.guard != 0) return;
     const float *P = lp.partial + (size_t)t0 * (BM * BN);
     const int tid = threadIdx.x;
@@ -1208,10 +1346,10 @@ __device__ inline void tn_reduce_body(const L &ll)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int n = tl.n0 + ln + e;
-            if (m < M && n < N && tn_keep(tl.diag, lp.tile_mode, m, n)) {
-                float v = lp.alpha * vals[e];
+            if (m < M && n < N && tn_keep(tl.diag, at.tile_mode, m, n)) {
+                float v = at.alpha * vals[e];
                 float *dst = pr.C + (size_t)m * pr.ldc + n;
-                if (lp.beta != 0.f) v += lp.beta * (*dst);
+                if (at.beta != 0.f) v += at.beta * (*dst);
                 *dst = v;
                 if (pr.Ct != nullptr && (!tl.diag || m != n)) pr.Ct[(size_t)n * pr.ldct + m] = v;
             }
@@ -1249,7 +1387,10 @@ __global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_bf16mfma_kernel(
 
 __global__ __launch_bounds__(TN_THREADS) void curvature_reduce_packed_kernel(const SyrkLaunchPacked lp) { tn_reduce_body(lp); }
 
-// The products of the blocked inversion (panel solves, row / trailing updates, merges).
+static_assert(sizeof(InvLaunch) <= 4096 && sizeof(TnLaunch) <= 4096 && sizeof(SyrkLaunch) <= 4096,
+              "launch descriptors travel in the kernel arguments (4 KB)");
+
+// The products of the blocked inversion (panel solves, row updates, merges).
 __global__ __launch_bounds__(TN_THREADS, 2) void invert_gemm_kernel(const InvLaunch lp)
 {
     __shared__ float As[TN_LDS_STAGES][BK][BM];
