@@ -167,6 +167,32 @@ kfac_status kfac_invert_plan_run(kfac_invert_plan *plan, int64_t n_steps, void *
 kfac_status kfac_invert_plan_reset(kfac_invert_plan *plan);
 void kfac_invert_plan_destroy(kfac_invert_plan *plan);
 
+/* ---------------------------------------- inversion without a workspace argument
+ * For callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same computation and result as kfac_invert (bit for bit: the same
+ * kernels), with the working arrays in a 32 MiB array that is part of the
+ * library's code object instead of a caller workspace.
+ *
+ *  - d <= kfac_invert_noalloc_max_d() (2048); larger d returns
+ *    KFAC_ERR_UNSUPPORTED and nothing is enqueued.  All other argument rules,
+ *    info_dev and the "inv untouched on failure" rule are those of kfac_invert.
+ *  - The call allocates and frees nothing on the device (no hipMalloc / hipFree,
+ *    no allocating library routine); every GPU that runs the library holds its
+ *    own copy of the array from the moment the library is loaded until the
+ *    process ends.
+ *  - The device that `stream` belongs to must be the current device.  The
+ *    array's address on a device is looked up on the first call made there
+ *    (KFAC_ERR_HIP if that fails).
+ *  - All calls on one GPU share that GPU's array: two calls whose work overlaps
+ *    in time (different streams, or one stream per thread) race.  Calls on one
+ *    stream are ordered and safe.  The array keeps the last call's contents; the
+ *    kernels write every element before they read it, so nothing is cleared.
+ */
+kfac_status kfac_invert_noalloc(const float *factor, int64_t d, int64_t ldf, float damping,
+                                float *inv, int64_t ldi, int32_t *info_dev, void *stream);
+int64_t kfac_invert_noalloc_max_d(void);
+
 /* ------------------------------------------------------------- precondition
  * Section 2.3.1: (A (x) B)^-1 vec(G) = vec(B^-1 G A^-1), vec stacking columns.
  *

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     kfac_curvature_grouped_workspace,
     kfac_invert,
     kfac_invert_batched,
+    kfac_invert_noalloc,
     kfac_invert_batched_workspace,
     kfac_precondition,
     kfac_precondition_grouped,

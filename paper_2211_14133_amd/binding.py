@@ -46,6 +46,8 @@ SIGNATURES = {
     "kfac_invert_workspace": (_sz, [_i64]),
     "kfac_invert_batched": (ctypes.c_int, [ctypes.POINTER(InvertItem), _i64, _f32, _vp, _sz, _vp]),
     "kfac_invert_batched_workspace": (_sz, [ctypes.POINTER(InvertItem), _i64]),
+    "kfac_invert_noalloc": (ctypes.c_int, [_vp, _i64, _i64, _f32, _vp, _i64, _vp, _vp]),
+    "kfac_invert_noalloc_max_d": (_i64, []),
     "kfac_precondition": (ctypes.c_int, [_vp, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _sz, _vp]),
     "kfac_precondition_workspace": (_sz, [_i64, _i64]),
     "kfac_precondition_grouped": (ctypes.c_int, [ctypes.POINTER(PreconditionItem), _i64, _vp, _sz, _vp]),
@@ -198,6 +200,15 @@ def kfac_invert(factor, damping, inv, info=None, workspace=None, stream=None):
     _check(lib.kfac_invert(ctypes.c_void_p(factor.data_ptr()), factor.shape[0], factor.stride(0), damping,
                            ctypes.c_void_p(inv.data_ptr()), inv.stride(0), ctypes.c_void_p(info.data_ptr()),
                            ws, nbytes, _stream(stream)))
+    return info
+
+
+def kfac_invert_noalloc(factor, damping, inv, info, stream=None):
+    """kfac_invert with the library's built-in scratch array (d <= 2048): nothing is allocated, here or there."""
+    _inv_items([factor], [inv], info)
+    _check(load().kfac_invert_noalloc(ctypes.c_void_p(factor.data_ptr()), factor.shape[0], factor.stride(0), damping,
+                                      ctypes.c_void_p(inv.data_ptr()), inv.stride(0), ctypes.c_void_p(info.data_ptr()),
+                                      _stream(stream)))
     return info
 
 

@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <functional>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -935,6 +936,52 @@ kfac_status kfac_invert(const float *factor, int64_t d, int64_t ldf, float dampi
     it.ldi = ldi;
     it.info_dev = info_dev;
     return kfac_invert_batched(&it, 1, damping, workspace, workspace_bytes, stream);
+}
+
+// ------------------------------------------- inversion without a workspace argument
+
+// Scratch of kfac_invert_noalloc: the two working arrays of one inversion of up to NOALLOC_MAX_D rows.
+// The array lives in the code object, so every GPU that loads the library holds its own copy at its
+// own address until the process ends.  The name below is only a host-side handle: the device address
+// comes from hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
+constexpr int64_t NOALLOC_MAX_D = 2048;
+constexpr size_t NOALLOC_SCRATCH_BYTES = 2 * (size_t)NOALLOC_MAX_D * NOALLOC_MAX_D * sizeof(float);  // 32 MiB
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[NOALLOC_MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call for that device).
+void *scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
+
+}  // namespace
+
+int64_t kfac_invert_noalloc_max_d(void) { return NOALLOC_MAX_D; }
+
+kfac_status kfac_invert_noalloc(const float *factor, int64_t d, int64_t ldf, float damping,
+                                float *inv, int64_t ldi, int32_t *info_dev, void *stream)
+{
+    if (d > NOALLOC_MAX_D) return KFAC_ERR_UNSUPPORTED;
+    if (d > 0 && invert_item_bytes(d) > NOALLOC_SCRATCH_BYTES) return KFAC_ERR_UNSUPPORTED;
+    void *ws = scratch_of_current_device();
+    if (ws == nullptr) return KFAC_ERR_HIP;
+    // Every kernel of the inversion writes what it later reads (working copy, factor, inverse factor),
+    // so nothing of the previous call's contents has to be cleared.
+    return kfac_invert(factor, d, ldf, damping, inv, ldi, info_dev, ws, NOALLOC_SCRATCH_BYTES, stream);
 }
 
 // --------------------------------------------------------------- precondition
