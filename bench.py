@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--cpu-baseline", choices=["sample", "full"], default="sample",
                     help="sample: time the oracle on a bounded part of the workload (default, seconds); "
                          "full: run the oracle over the whole step (minutes)")
+    ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
+                    help="2: after the curvature, invert the small factors (and precondition the layers that only need "
+                         "them) on one stream and the large factors on another (same results; default 1)")
     ap.add_argument("--phase", choices=["all", "curvature", "inversion", "precondition"], default="all",
                     help="for profiling: after one full untimed step, time only this phase (prints a short JSON "
                          "line that is not the benchmark line)")
@@ -127,6 +130,38 @@ def main():
         if st != 0:
             raise RuntimeError("kfac call failed: %s" % lib.kfac_status_string(st).decode())
 
+    # ---- optional two-stream split of inversion + precondition (small factors / large factors)
+    if args.streams == 2:
+        dsmall = min(f.shape[0] for f in facs)
+        small = [i for i, f in enumerate(facs) if f.shape[0] == dsmall]
+        large = [i for i, f in enumerate(facs) if f.shape[0] != dsmall]
+        lay_small = [l for l, (di, do) in enumerate(layers) if di == dsmall and do == dsmall]
+        lay_rest = [l for l in range(nlay) if l not in lay_small]
+        sel = lambda seq, idx: [seq[i] for i in idx]  # noqa: E731
+        inv_s = binding._inv_items(sel(facs, small), sel(invs, small), infos[:len(small)])
+        inv_l = binding._inv_items(sel(facs, large), sel(invs, large), infos[len(small):])
+        prec_s = binding._prec_items(sel(b_invs, lay_small), sel(a_invs, lay_small), sel(grads, lay_small), sel(outs, lay_small))
+        prec_r = binding._prec_items(sel(b_invs, lay_rest), sel(a_invs, lay_rest), sel(grads, lay_rest), sel(outs, lay_rest))
+        ws2_bytes = lib.kfac_invert_batched_workspace(inv_l, len(large))
+        ws2 = torch.empty(ws2_bytes + 256, dtype=torch.uint8, device=dev)
+        ws2p = ctypes.c_void_p((ws2.data_ptr() + 255) // 256 * 256)
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        s1p, s2p = ctypes.c_void_p(s1.cuda_stream), ctypes.c_void_p(s2.cuda_stream)
+        ev_fork, ev_j1, ev_j2 = torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event()
+
+        def invert_and_precondition_two_streams():
+            ev_fork.record(stream)
+            s1.wait_event(ev_fork)
+            s2.wait_event(ev_fork)
+            check(lib.kfac_invert_batched(inv_s, len(small), damping, wsp, ws_bytes, s1p))
+            check(lib.kfac_precondition_grouped(prec_s, len(lay_small), wsp, ws_bytes, s1p))
+            check(lib.kfac_invert_batched(inv_l, len(large), damping, ws2p, ws2_bytes, s2p))
+            ev_j1.record(s1)
+            ev_j2.record(s2)
+            stream.wait_event(ev_j1)
+            stream.wait_event(ev_j2)
+            check(lib.kfac_precondition_grouped(prec_r, len(lay_rest), wsp, ws_bytes, sp))
+
     def step(events=None):
         if events is not None:
             events["t0"].record(stream)
@@ -137,6 +172,12 @@ def main():
                                              0.0 if m == 0 else 1.0, wsp, ws_bytes, sp))
             if events is not None:
                 events["c1"][m].record(stream)
+        if args.streams == 2:
+            invert_and_precondition_two_streams()
+            if events is not None:
+                events["t2"].record(stream)  # (the two phases overlap: only their sum is meaningful)
+                events["t3"].record(stream)
+            return
         check(lib.kfac_invert_batched(inv_items, nfac, damping, wsp, ws_bytes, sp))
         if events is not None:
             events["t2"].record(stream)
@@ -251,6 +292,7 @@ def main():
                            "bf16 activations and errors, fp32 factors / inverses / gradients" if bf16 else "fp32", damping),
             "factors": nfac,
             "layers": nlay,
+            "streams": args.streams,
         },
         "useful_tflops": round(f_total / (ms_per_step * 1e-3) / 1e12, 2),
         "phases_ms": {"curvature": round(curv_ms, 3), "inversion": round(inv_ms, 3), "precondition": round(prec_ms, 3)},
@@ -286,6 +328,16 @@ def main():
         },
     }
 
+    if args.streams == 2:
+        # the two phases overlap: report their sum, and none of the blocks that need them separately
+        both = inv_ms + prec_ms
+        result["phases_ms"] = {"curvature": round(curv_ms, 3), "inversion_plus_precondition": round(both, 3)}
+        for key in ("phases_ms_median", "phases_ms_min", "phases_min_traffic_gbps", "phases_useful_tflops"):
+            result.pop(key)
+        result["inversion_plus_precondition_useful_tflops"] = round((f_inv + f_prec) / (both * 1e-3) / 1e12, 2)
+        print(json.dumps(result))
+        return
+
     # Section 3.3 of the paper with the measured K-FAC times.  T_f and T_b are NOT measured (no model is
     # run here): they are the stage's forward GEMM flops at the rate this engine reaches on the
     # precondition products, and twice that.
@@ -302,6 +354,37 @@ def main():
         "t_pipe_ms": round(model["t_pipe"], 3), "t_bubble_ms": round(model["t_bubble"], 3),
         "t_kfac_ms": round(model["t_kfac"], 3),
         "curvature_plus_inversion_over_bubble": round(model["ratio"], 3),
+    }
+
+    # Section 3.1 with measured durations: the work of the stage cut into chunks (one grouped curvature call per
+    # micro-batch and side, every launch step of the inversion), each timed with HIP events, and assigned to the
+    # bubbles of each GPipe stage under rules 1 - 3.  steps_per_refresh is the paper's refresh interval.
+    from paper_2211_14133_amd import bubble_schedule as bs
+
+    a_items = binding._curv_items(xs[0][0::2], facs[0::2])
+    b_items = binding._curv_items(xs[0][1::2], facs[1::2])
+    t_curv_a = bs.time_ms(lambda: check(lib.kfac_curvature_grouped(a_items, nlay, in_dtype, alpha, 0.0, wsp, ws_bytes, sp)))
+    t_curv_b = bs.time_ms(lambda: check(lib.kfac_curvature_grouped(b_items, nlay, in_dtype, alpha, 0.0, wsp, ws_bytes, sp)))
+    step()  # factors of the whole mini-batch again
+    plan = binding.InvertPlan(facs, damping, invs, infos=infos, workspace=ws)
+    chunk_ms = bs.measure_plan_steps(plan, reps=3)
+    by_kind = {}
+    for i, t in enumerate(chunk_ms):
+        by_kind[plan.step_label(i)] = by_kind.get(plan.step_label(i), 0.0) + t
+    refresh = []
+    for stage in range(depth):
+        tl = binding.kfac_gpipe_stage(stage, depth, n_micro, t_f, t_b)
+        works = [bs.Work("A%d" % m, [None], [t_curv_a], release_ms=tl["forward_end"][m]) for m in range(n_micro)]
+        works += [bs.Work("B%d" % m, [None], [t_curv_b], release_ms=tl["backward_end"][m]) for m in range(n_micro)]
+        works.append(bs.Work("inversion", [None] * len(chunk_ms), chunk_ms, deps=list(range(2 * n_micro))))
+        _, needed = bs.assign(tl, tl["t_step"] + prec_ms, works)
+        refresh.append(needed)
+    plan.close()
+    result["pipefisher_assignment"] = {
+        "chunks": {"curvature_A_per_microbatch_ms": round(t_curv_a, 3), "curvature_B_per_microbatch_ms": round(t_curv_b, 3),
+                   "inversion_steps": len(chunk_ms), "longest_inversion_step_ms": round(max(chunk_ms), 3)},
+        "inversion_ms_by_kind_of_step": {k2: round(v, 3) for k2, v in by_kind.items()},
+        "steps_per_refresh_by_gpipe_stage": refresh,
     }
 
     if not args.no_cpu_baseline:

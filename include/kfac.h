@@ -162,6 +162,8 @@ int64_t kfac_invert_plan_steps(const kfac_invert_plan *plan);
 int64_t kfac_invert_plan_position(const kfac_invert_plan *plan);
 /* model cost of a step in floating point operations (0 for copies, -1 for a bad index) */
 double kfac_invert_plan_step_flops(const kfac_invert_plan *plan, int64_t step);
+/* what a step does, as a short static string such as "panel solve" (NULL for a bad index) */
+const char *kfac_invert_plan_step_label(const kfac_invert_plan *plan, int64_t step);
 /* enqueue the next n_steps steps (fewer if the end is reached) on `stream` */
 kfac_status kfac_invert_plan_run(kfac_invert_plan *plan, int64_t n_steps, void *stream);
 kfac_status kfac_invert_plan_reset(kfac_invert_plan *plan);
@@ -263,6 +265,20 @@ kfac_status kfac_assign_work(int64_t n_bubbles, const double *bubble_start, cons
                              const double *release, const int64_t *dep_begin, const int64_t *dep_ids,
                              int64_t *out_step, int64_t *out_bubble, double *out_start,
                              int64_t *steps_needed);
+
+/* One pipeline step of GPipe seen from one stage (section 2.1: every forward pass
+ * of the step, then every backward pass; t_f, t_b per micro-batch and stage,
+ * stages numbered from 0 in forward direction).  Gives what kfac_assign_work
+ * needs: forward_end[m] and backward_end[m] (release times of the curvature
+ * work of micro-batch m under rule 1; n_micro entries each), the bubbles of
+ * the stage (at most 3: before the first forward pass, between the forward and
+ * the backward passes, after the last backward pass; caller provides room for
+ * 3 starts and 3 lengths) and the length of the step.  Host arrays.
+ * KFAC_ERR_ARG for null pointers, stage outside [0, depth), non-positive
+ * sizes or times. */
+kfac_status kfac_gpipe_stage(int64_t stage, int64_t depth, int64_t n_micro, double t_f, double t_b,
+                             double *forward_end, double *backward_end,
+                             double *bubble_start, double *bubble_length, int64_t *n_bubbles, double *t_step);
 
 /* Section 3.3 "Performance Modeling", closed forms for one pipeline step:
  *   t_pipe   = c_f * t_f + c_b * t_b

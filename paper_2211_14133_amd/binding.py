@@ -56,10 +56,12 @@ SIGNATURES = {
     "kfac_invert_plan_steps": (_i64, [_vp]),
     "kfac_invert_plan_position": (_i64, [_vp]),
     "kfac_invert_plan_step_flops": (ctypes.c_double, [_vp, _i64]),
+    "kfac_invert_plan_step_label": (ctypes.c_char_p, [_vp, _i64]),
     "kfac_invert_plan_run": (ctypes.c_int, [_vp, _i64, _vp]),
     "kfac_invert_plan_reset": (ctypes.c_int, [_vp]),
     "kfac_invert_plan_destroy": (None, [_vp]),
     "kfac_assign_work": (ctypes.c_int, [_i64, _dp, _dp, ctypes.c_double, _i64, _ip, _dp, _dp, _ip, _ip, _ip, _ip, _dp, _ip]),
+    "kfac_gpipe_stage": (ctypes.c_int, [_i64, _i64, _i64, ctypes.c_double, ctypes.c_double, _dp, _dp, _dp, _dp, _ip, _dp]),
     "kfac_perf_model": (ctypes.c_int, [ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double, _i64,
                                        ctypes.c_double, ctypes.c_double, ctypes.c_double, _dp]),
     "kfac_mfma_probe": (ctypes.c_int, [ctypes.c_int, _i64, _vp, _dp, _vp]),
@@ -299,6 +301,10 @@ class InvertPlan:
     def step_flops(self, i):
         return float(load().kfac_invert_plan_step_flops(self._h, i))
 
+    def step_label(self, i):
+        label = load().kfac_invert_plan_step_label(self._h, i)
+        return None if label is None else label.decode()
+
     def run(self, n_steps, stream=None):
         _check(load().kfac_invert_plan_run(self._h, n_steps, _stream(stream)))
 
@@ -350,6 +356,17 @@ def kfac_assign_work(bubble_start, bubble_length, step_period, chunk_times, rele
         res.append([(int(out_step[k + i]), int(out_bubble[k + i]), float(out_start[k + i])) for i in range(c)])
         k += c
     return res, int(needed.value)
+
+
+def kfac_gpipe_stage(stage, depth, n_micro, t_f, t_b):
+    """One GPipe step seen from `stage`: release times, bubbles and the step length (host only)."""
+    fwd, bwd = _darr([0.0] * n_micro), _darr([0.0] * n_micro)
+    bs, bl = _darr([0.0] * 3), _darr([0.0] * 3)
+    nb, t_step = ctypes.c_int64(0), ctypes.c_double(0.0)
+    _check(load().kfac_gpipe_stage(stage, depth, n_micro, float(t_f), float(t_b), fwd, bwd, bs, bl,
+                                   ctypes.cast(ctypes.byref(nb), _ip), ctypes.cast(ctypes.byref(t_step), _dp)))
+    return {"forward_end": [fwd[m] for m in range(n_micro)], "backward_end": [bwd[m] for m in range(n_micro)],
+            "bubbles": [(bs[i], bl[i]) for i in range(nb.value)], "t_step": t_step.value}
 
 
 def kfac_perf_model(c_f, c_b, t_f, t_b, n_micro, t_curv, t_inv, t_prec):

@@ -89,6 +89,37 @@ kfac_status kfac_assign_work(int64_t n_bubbles, const double *bubble_start, cons
     return KFAC_OK;
 }
 
+kfac_status kfac_gpipe_stage(int64_t stage, int64_t depth, int64_t n_micro, double t_f, double t_b,
+                             double *forward_end, double *backward_end,
+                             double *bubble_start, double *bubble_length, int64_t *n_bubbles, double *t_step)
+{
+    if (depth <= 0 || stage < 0 || stage >= depth || n_micro <= 0 || !(t_f > 0.0) || !(t_b > 0.0)) return KFAC_ERR_ARG;
+    if (!forward_end || !backward_end || !bubble_start || !bubble_length || !n_bubbles || !t_step) return KFAC_ERR_ARG;
+    // Forward passes enter stage `stage` after `stage` earlier stages and follow one another; the backward
+    // passes start on the last stage once it has seen every micro-batch and travel back stage by stage.
+    const double first_forward = (double)stage * t_f;
+    const double all_forward_done = (double)(depth - 1 + n_micro) * t_f;  // on the last stage
+    const double first_backward = all_forward_done + (double)(depth - 1 - stage) * t_b;
+    for (int64_t m = 0; m < n_micro; ++m) {
+        forward_end[m] = first_forward + (double)(m + 1) * t_f;
+        backward_end[m] = first_backward + (double)(m + 1) * t_b;
+    }
+    *t_step = (double)(depth - 1 + n_micro) * (t_f + t_b);
+    // idle: before the first forward pass, between the last forward and the first backward pass, after the last
+    // backward pass until the last stage-0 backward pass ends the step
+    const double idle_from[3] = {0.0, forward_end[n_micro - 1], backward_end[n_micro - 1]};
+    const double idle_to[3] = {first_forward, first_backward, *t_step};
+    int64_t nb = 0;
+    for (int k = 0; k < 3; ++k)
+        if (idle_to[k] > idle_from[k]) {
+            bubble_start[nb] = idle_from[k];
+            bubble_length[nb] = idle_to[k] - idle_from[k];
+            ++nb;
+        }
+    *n_bubbles = nb;
+    return KFAC_OK;
+}
+
 kfac_status kfac_perf_model(double c_f, double c_b, double t_f, double t_b, int64_t n_micro,
                             double t_curv, double t_inv, double t_prec, double *out)
 {

@@ -47,6 +47,7 @@ inline double tn_problem_flops(int M, int N, int K, int tile_mode, int mask_a, i
 // Where the launches of a work item go: straight to a stream, or into a recorded plan.
 struct Emitter {
     virtual ~Emitter() {}
+    const char *label = "";  // what the next launches do (static string; kept with recorded steps)
     virtual void prep(const PrepLaunch &pl, int count, int grid_x) = 0;
     virtual void inv(const InvLaunch &lp, int grid, bool with_diag, double flops) = 0;
     virtual void tn(const TnLaunch &lp, int grid, int tiles, double flops) = 0;
@@ -84,6 +85,7 @@ struct StreamEmitter : Emitter {
 struct PlanStep {
     std::function<void(hipStream_t)> run;
     double flops;  // model cost: multiply-adds x 2 of the launch (0 for copies)
+    const char *label;
 };
 typedef std::vector<PlanStep> PlanSteps;
 
@@ -92,15 +94,15 @@ struct RecordEmitter : Emitter {
     explicit RecordEmitter(PlanSteps &st) : steps(st) {}
     void prep(const PrepLaunch &pl, int count, int grid_x) override
     {
-        steps.push_back(PlanStep{[pl, count, grid_x](hipStream_t s) { launch_prep(s, pl, count, grid_x); }, 0.0});
+        steps.push_back(PlanStep{[pl, count, grid_x](hipStream_t s) { launch_prep(s, pl, count, grid_x); }, 0.0, label});
     }
     void inv(const InvLaunch &lp, int grid, bool with_diag, double flops) override
     {
-        steps.push_back(PlanStep{[lp, grid, with_diag](hipStream_t s) { launch_inv(s, lp, grid, with_diag); }, flops});
+        steps.push_back(PlanStep{[lp, grid, with_diag](hipStream_t s) { launch_inv(s, lp, grid, with_diag); }, flops, label});
     }
     void tn(const TnLaunch &lp, int grid, int tiles, double flops) override
     {
-        steps.push_back(PlanStep{[lp, grid, tiles](hipStream_t s) { launch_tn(s, lp, grid, tiles); }, flops});
+        steps.push_back(PlanStep{[lp, grid, tiles](hipStream_t s) { launch_tn(s, lp, grid, tiles); }, flops, label});
     }
 };
 
@@ -259,8 +261,9 @@ public:
     }
 
     // One launch of the chain: its own nodes `crit` plus tasks that ride along.
-    bool launch(const std::vector<NodeSpec> &crit, bool with_diag)
+    bool launch(const std::vector<NodeSpec> &crit, bool with_diag, const char *label)
     {
+        label_ = label;
         size_t i = 0;
         do {
             // leave room for some tasks even when a launch has many nodes of its own
@@ -409,6 +412,8 @@ private:
         lp.c.splits = 1;
         if (!in_bounds(lp, cnt)) return false;
         const int grid = tn_balance_xcds(lp, tiles, first_tiles);
+        em_.label = drain ? "tasks: deferred row updates and products of the triangular inverse"
+                          : (tiles > first_tiles ? "diagonal blocks + tasks riding along" : label_);
         em_.inv(lp, grid, with_diag, flops);
         ++launch_idx_;
         return true;
@@ -444,6 +449,7 @@ private:
     const std::vector<InvMat> &mats_;
     float *ws_;
     Emitter &em_;
+    const char *label_ = "";
     std::vector<Group> groups_;
     std::vector<Task> urgent_, bulk_;
     size_t head_u_ = 0, head_b_ = 0;
@@ -754,6 +760,7 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
             dmax = std::max(dmax, m.d);
         }
         pl.damping = damping;
+        em.label = "copy + damping";
         em.prep(pl, (int)n, std::min(dmax, 512));
     }
 
@@ -809,12 +816,12 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
                 for (size_t mi = 0; mi < mats.size(); ++mi)
                     if (j < mats[mi].nblk)
                         crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)s0, (unsigned char)j, (unsigned char)j, INV_ROW_UPDATE, 0, 0});
-                if (!crit.empty() && !sch.launch(crit, false)) return KFAC_ERR_HIP;
+                if (!crit.empty() && !sch.launch(crit, false, "row update inside the super-panel")) return KFAC_ERR_HIP;
             }
             crit.clear();
             for (size_t mi = 0; mi < mats.size(); ++mi)
                 if (j < mats[mi].nblk) crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)j, 0, 0, INV_DIAG, 0, 0});
-            if (!crit.empty() && !sch.launch(crit, true)) return KFAC_ERR_HIP;
+            if (!crit.empty() && !sch.launch(crit, true, "diagonal blocks")) return KFAC_ERR_HIP;
             // W_jj is there: second products of the tree nodes that end with block j, smallest first
             for (size_t mi = 0; mi < mats.size(); ++mi)
                 for (TriNode &t : trees[mi])
@@ -822,7 +829,7 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
             crit.clear();
             for (size_t mi = 0; mi < mats.size(); ++mi)
                 if (j + 1 < mats[mi].nblk) crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)j, 0, 0, INV_PANEL_SOLVE, 0, 0});
-            if (!crit.empty() && !sch.launch(crit, false)) return KFAC_ERR_HIP;
+            if (!crit.empty() && !sch.launch(crit, false, "panel solve")) return KFAC_ERR_HIP;
             // block row j of U is final: first products of the tree nodes whose first part ends with it
             for (size_t mi = 0; mi < mats.size(); ++mi)
                 for (TriNode &t : trees[mi])
@@ -837,7 +844,7 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
                 wait.push_back(row_group[mi][(size_t)i]);  // after their earlier deferred updates
             }
         if (!sch.finish_groups(wait)) return KFAC_ERR_HIP;
-        if (!crit.empty() && !sch.launch(crit, false)) return KFAC_ERR_HIP;
+        if (!crit.empty() && !sch.launch(crit, false, "update of the next super-panel's rows")) return KFAC_ERR_HIP;
         // ... the rows below as tasks, each after the previous update of the same row
         for (size_t mi = 0; mi < mats.size(); ++mi)
             for (int i = e + SUPER_PANEL; i < mats[mi].nblk; ++i) {
@@ -854,6 +861,7 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
     lu.mask_a = MASK_KEEP_K_GE;
     lu.mask_b = MASK_KEEP_K_GE;
     for (const InvMat &m : mats) lu.add(m.S, m.ld, m.S, m.ld, m.inv, m.ldi, m.d, m.d, m.d, m.inv, m.ldi, m.info);
+    em.label = "inverse = W W^T";
     lu.launch(em);
     return KFAC_OK;
 }
@@ -903,6 +911,12 @@ double kfac_invert_plan_step_flops(const kfac_invert_plan *plan, int64_t step)
 {
     if (plan == nullptr || step < 0 || step >= (int64_t)plan->steps.size()) return -1.0;
     return plan->steps[(size_t)step].flops;
+}
+
+const char *kfac_invert_plan_step_label(const kfac_invert_plan *plan, int64_t step)
+{
+    if (plan == nullptr || step < 0 || step >= (int64_t)plan->steps.size()) return nullptr;
+    return plan->steps[(size_t)step].label;
 }
 
 kfac_status kfac_invert_plan_run(kfac_invert_plan *plan, int64_t n_steps, void *stream)

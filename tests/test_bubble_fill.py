@@ -205,6 +205,24 @@ def test_product_assign_work_matches_oracle_with_holes():
     assert holes >= 30
 
 
+def test_product_gpipe_stage_matches_oracle_timeline():
+    for depth, n_micro, tf, tb in [(4, 4, 1.0, 2.0), (8, 8, 0.7, 1.3), (4, 8, 1.0, 1.0), (1, 3, 0.5, 0.25), (6, 1, 2.0, 3.0)]:
+        for stage in range(depth):
+            want = po.gpipe_stage_timeline(stage, depth, n_micro, tf, tb)
+            got = k.kfac_gpipe_stage(stage, depth, n_micro, tf, tb)
+            assert got["t_step"] == pytest.approx(want["t_step"], rel=1e-14)
+            assert got["forward_end"] == pytest.approx([e for _, e in want["forward"]], rel=1e-14)
+            assert got["backward_end"] == pytest.approx([e for _, e in want["backward"]], rel=1e-14)
+            assert len(got["bubbles"]) == len(want["bubbles"])
+            for (gs, gl), (ws, wl) in zip(got["bubbles"], want["bubbles"]):
+                assert gs == pytest.approx(ws, rel=1e-14, abs=1e-14) and gl == pytest.approx(wl, rel=1e-13)
+            # idle time of every stage = the bubble term of section 3.3 with C_f = C_b = n_micro + depth - 1
+            c = n_micro + depth - 1
+            assert sum(l for _, l in got["bubbles"]) == pytest.approx(k.kfac_perf_model(c, c, tf, tb, n_micro, 0, 0, 0)["t_bubble"], rel=1e-12)
+    with pytest.raises(k.KfacError):
+        k.kfac_gpipe_stage(4, 4, 2, 1.0, 1.0)
+
+
 def test_product_assign_work_rejects_bad_input():
     with pytest.raises(k.KfacError):
         k.kfac_assign_work([2.0, 1.0], [1.0, 1.0], 10.0, [[0.1]], [0.0], [[]])  # bubbles not sorted
