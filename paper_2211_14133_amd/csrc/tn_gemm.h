@@ -770,6 +770,9 @@ __device__ inline void tn_dma16_s(const float *sbase, unsigned voff, unsigned ld
 // whatever is not an MFMA must be little and sit between MFMAs.  The loop is unrolled over
 // the four stages (LDS addresses become immediates), the loads take a scalar base that is
 // advanced with scalar arithmetic, and scheduling barriers pin the order written here.
+// IDLE: the wave takes part in the loads and barriers of the tile but computes nothing (its quarter of a
+// diagonal tile of a triangular launch lies on the side that is only stored as a mirror).
+template <bool IDLE>
 __device__ __forceinline__ void tn_mainloop_direct(const TnProblem &pr, const TnTile &tl,
                                           float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                           floatx16 (&sum)[2][2])
@@ -831,17 +834,19 @@ __device__ __forceinline__ void tn_mainloop_direct(const TnProblem &pr, const Tn
     } while (0)
 #define TN_R(st, half)                                                                                            \
     do {                                                                                                          \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                           \
+        if (!IDLE) _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                \
             fa[half][q] = *reinterpret_cast<const float2 *>(&As[st][8 * (half) + 2 * q + lh][wm + 2 * li]);       \
             fb[half][q] = *reinterpret_cast<const float2 *>(&Bs[st][8 * (half) + 2 * q + lh][wn + 2 * li]);       \
         }                                                                                                         \
     } while (0)
 #define TN_MQ(half, q)                                                                                        \
     do {                                                                                                      \
+        if (!IDLE) {                                                                                          \
         acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].x, acc[0][0], 0, 0, 0);   \
         acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].x, fb[half][q].y, acc[0][1], 0, 0, 0);   \
         acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].x, acc[1][0], 0, 0, 0);   \
         acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[half][q].y, fb[half][q].y, acc[1][1], 0, 0, 0);   \
+        }                                                                                                     \
     } while (0)
 #define TN_PIN() __builtin_amdgcn_sched_barrier(0)
     // s_waitcnt vmcnt(4): everything but the four newest loads has landed (gfx9 encoding:
@@ -1170,8 +1175,15 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
     }
     // (the direct loop addresses a slab with 32-bit byte offsets from its first row)
     const bool direct_ok = (pr.K % BK) == 0 && pr.lda < (1 << 25) && pr.ldb < (1 << 25);
+    // diagonal tile of a triangular launch: the wave whose 64 x 64 quarter lies wholly on the mirrored side
+    // has nothing to compute (its stores are all masked); in the direct loop it only helps to move the slabs,
+    // which leaves its share of the matrix core to the co-resident workgroup and saves power
+    const bool idle_wave = tl.diag && ((at.tile_mode == TILE_LOWER && wn > wm) || (at.tile_mode == TILE_UPPER && wm > wn));
     if (!done && fast_a && fast_b && !masked && direct_ok) {
-        tn_mainloop_direct(pr, tl, As, Bs, sum);
+        if (idle_wave)
+            tn_mainloop_direct<true>(pr, tl, As, Bs, sum);
+        else
+            tn_mainloop_direct<false>(pr, tl, As, Bs, sum);
         done = true;
     }
     if (!done) {
@@ -1193,7 +1205,10 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
                     TnTile seg = tl;
                     if (s0 > tl.kt0) {
                         seg.kt0 = tl.kt0; seg.kt1 = s0;
-                        tn_mainloop_direct(pr, seg, As, Bs, sum);
+                        if (idle_wave)
+                            tn_mainloop_direct<true>(pr, seg, As, Bs, sum);
+                        else
+                            tn_mainloop_direct<false>(pr, seg, As, Bs, sum);
                         __syncthreads();
                     }
                     seg.kt0 = s0; seg.kt1 = s1;
@@ -1201,7 +1216,10 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
                     if (s1 < tl.kt1) {
                         __syncthreads();
                         seg.kt0 = s1; seg.kt1 = tl.kt1;
-                        tn_mainloop_direct(pr, seg, As, Bs, sum);
+                        if (idle_wave)
+                            tn_mainloop_direct<true>(pr, seg, As, Bs, sum);
+                        else
+                            tn_mainloop_direct<false>(pr, seg, As, Bs, sum);
                     }
                 } else {
                     tn_mainloop<false, true>(at, pr, tl, As, Bs, sum);
