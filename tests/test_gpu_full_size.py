@@ -186,3 +186,56 @@ def test_curvature_long_sequence(oracle):
     k.kfac_curvature(xs[0][n // 2:], f2, 1.0 / n, 1.0)
     torch.cuda.synchronize()
     assert oracle.rel_fro(f2.cpu().numpy(), want) <= 1e-6
+
+
+def test_block_diagonal_factor_at_the_size_the_appendix_names(oracle, capsys):
+    """Appendix A.2: for d >= 16,384 a factor is replaced by K independent diagonal blocks.  A 16,384-dimensional
+    A factor as K = 4 blocks of 4096 (B: 1024-dimensional, whole), every step on the blocks addressed inside the
+    big arrays through leading dimensions; against the oracle block by block."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import time
+
+    import paper_2211_14133_amd as k
+
+    dev = torch.device("cuda:0")
+    n, d_in, d_out, kb, lam = 4096, 16384, 1024, 4, synth.DAMPING
+    blk = d_in // kb
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.SEED + 16384)
+    x = torch.randn(n, d_in, device=dev, generator=gen)
+    e = torch.randn(n, d_out, device=dev, generator=gen) * 1e-3
+    g = ((e.double().t() @ x.double()) / n).float()
+    a = torch.zeros(d_in, d_in, device=dev)
+    a_inv = torch.zeros(d_in, d_in, device=dev)
+    b = torch.empty(d_out, d_out, device=dev)
+    b_inv = torch.empty_like(b)
+    ablocks = [a[i * blk:(i + 1) * blk, i * blk:(i + 1) * blk] for i in range(kb)]
+    iblocks = [a_inv[i * blk:(i + 1) * blk, i * blk:(i + 1) * blk] for i in range(kb)]
+    k.kfac_curvature_grouped([x[:, i * blk:(i + 1) * blk] for i in range(kb)] + [e], ablocks + [b], 1.0 / n, 0.0)
+    infos = k.kfac_invert_batched(ablocks + [b], lam, iblocks + [b_inv])
+    p = torch.empty_like(g)
+    k.kfac_precondition_grouped([b_inv] * kb, iblocks, [g[:, i * blk:(i + 1) * blk] for i in range(kb)],
+                                [p[:, i * blk:(i + 1) * blk] for i in range(kb)])
+    torch.cuda.synchronize()
+    assert int(infos.abs().max()) == 0
+    # nothing outside the diagonal blocks was touched
+    mask = torch.ones(kb, kb, device=dev) - torch.eye(kb, device=dev)
+    assert float((a.view(kb, blk, kb, blk).abs().amax(dim=(1, 3)) * mask).max()) == 0.0
+    assert float((a_inv.view(kb, blk, kb, blk).abs().amax(dim=(1, 3)) * mask).max()) == 0.0
+    he, hg = e.cpu().numpy(), g.cpu().numpy()
+    ob = oracle.curvature(he)
+    obi, _ = oracle.invert(ob, lam)
+    t0 = time.perf_counter()
+    for i in range(kb):
+        hx = x[:, i * blk:(i + 1) * blk].cpu().numpy()
+        oa = oracle.curvature(hx)
+        oai, info = oracle.invert(oa, lam)
+        assert info == 0
+        op = oracle.precondition(obi, hg[:, i * blk:(i + 1) * blk], oai)
+        ea = oracle.rel_fro(ablocks[i].cpu().numpy(), oa)
+        eai = oracle.rel_fro(iblocks[i].cpu().numpy(), oai)
+        ep = oracle.rel_fro(p[:, i * blk:(i + 1) * blk].cpu().numpy(), op)
+        with capsys.disabled():
+            print("  block %d of %d: A %.2e  A^-1 %.2e  P %.2e   (%.0f s)" % (i, kb, ea, eai, ep, time.perf_counter() - t0), flush=True)
+        assert ea <= 1e-4 and ep <= 5e-3
