@@ -730,3 +730,38 @@ def test_mfma_probe_reports_its_work(k):
         torch.cuda.synchronize()
         assert flops == 256 * 2 * 8 * 4 * 50 * 8 * per_mfma
     assert float(sink.abs().max()) == 0.0
+
+
+def test_stage_wise_errors_at_block_shapes(k, oracle):
+    """Each stage of the path fed with the oracle's previous-stage output (rounded once to fp32), so that the error a
+    kernel adds is seen apart from what the conditioning of its input amplifies: BERT-Large block shapes, the
+    attention linear and the second feed-forward linear (4096-dimensional A, smallest eigenvalue about the damping)."""
+    c = synth.CONFIGS[3]
+    n = c["tokens"]
+    for li in (0, 5):
+        name, d_in, d_out, gelu = c["layers"][li]
+        x = synth.activations(3, 0, li, 0, n, d_in, gelu=gelu)
+        e = synth.errors(3, 0, li, 0, n, d_out)
+        g = synth.weight_gradient([e], [x])
+        oa32 = oracle.curvature(x).astype(np.float32)
+        ob32 = oracle.curvature(e).astype(np.float32)
+        # inversion alone: GPU and oracle invert the same fp32 matrix
+        ai, bi = torch.empty(d_in, d_in, device="cuda"), torch.empty(d_out, d_out, device="cuda")
+        infos = k.kfac_invert_batched([dev(oa32), dev(ob32)], synth.DAMPING, [ai, bi])
+        assert host(infos).tolist() == [0, 0]
+        oai, _ = oracle.invert(oa32.astype(np.float64), synth.DAMPING)
+        obi, _ = oracle.invert(ob32.astype(np.float64), synth.DAMPING)
+        e_ai, e_bi = oracle.rel_fro(host(ai), oai), oracle.rel_fro(host(bi), obi)
+        # precondition alone: GPU and oracle multiply the same fp32 inverses
+        oai32, obi32 = oai.astype(np.float32), obi.astype(np.float32)
+        p = torch.empty(d_out, d_in, device="cuda")
+        k.kfac_precondition(dev(obi32), dev(oai32), dev(g), p)
+        want_p = oracle.precondition(obi32, g, oai32)
+        e_p = oracle.rel_fro(host(p), want_p)
+        cond = np.linalg.cond(oa32.astype(np.float64) + synth.DAMPING * np.eye(d_in))
+        # what rounding may cost a product whose terms cancel: |B^-1| |G| |A^-1| against |B^-1 G A^-1|
+        cancel = np.linalg.norm(np.abs(obi32).astype(np.float64) @ np.abs(g).astype(np.float64) @ np.abs(oai32).astype(np.float64)) / np.linalg.norm(want_p)
+        print("cfg 3 %-5s stage-wise: A^-1 %.2e (cond %.2e)  B^-1 %.2e  P %.2e (cancellation %.1f)"
+              % (name, e_ai, cond, e_bi, e_p, cancel), flush=True)
+        assert e_ai <= 2e-6 * cond + 1e-6 and e_bi <= 1e-5
+        assert e_p <= 1e-6 * cancel + 1e-6  # two fp32 products with chunked accumulation: a few ulp of the terms
