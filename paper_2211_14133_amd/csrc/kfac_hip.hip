@@ -257,7 +257,6 @@ public:
         if (t.tiles == 0) return;
         groups_[(size_t)group].pending++;
         (urgent ? urgent_ : bulk_).push_back(t);
-        (urgent ? urgent_cost_ : bulk_cost_) += t.cost;
     }
 
     // One launch of the chain: its own nodes `crit` plus tasks that ride along.
@@ -292,8 +291,6 @@ public:
             if (!emit(nullptr, 0, false, true)) return false;
         return true;
     }
-
-    int launches() const { return launch_idx_; }
 
 private:
     struct Task {
@@ -344,8 +341,8 @@ private:
         return true;
     }
 
-    // Takes ready tasks from a queue, in order, while they fit the budget.
-    void take(std::vector<Task> &q, size_t &head, long long &queue_cost, long long &budget, int longest_allowed,
+    // Takes ready tasks from a queue, in order, until `budget` tiles are taken or the launch is full.
+    void take(std::vector<Task> &q, size_t &head, long long &budget, int longest_allowed,
               InvLaunch &lp, int &cnt, int &tiles, double &flops)
     {
         constexpr size_t WINDOW = 2048;  // tasks looked at behind the first one that cannot go yet
@@ -355,7 +352,6 @@ private:
             add_node(lp, cnt, tiles, t.n, t.tiles);
             flops += t.flops;
             budget -= t.tiles;
-            queue_cost -= t.cost;
             t.done = true;
             Group &g = groups_[(size_t)t.group];
             g.pending--;
@@ -405,8 +401,8 @@ private:
         const int slots = 256;  // one workgroup per CU in a launch with diagonal blocks
         long long budget = drain ? (1 << 20) : (with_diag ? std::max(0, slots * 3 / 4 - first_tiles) : 0);
         const int longest_allowed = drain ? (1 << 30) : std::max(own_longest, INV_DIAG_COST);
-        take(urgent_, head_u_, urgent_cost_, budget, longest_allowed, lp, cnt, tiles, flops);
-        take(bulk_, head_b_, bulk_cost_, budget, longest_allowed, lp, cnt, tiles, flops);
+        take(urgent_, head_u_, budget, longest_allowed, lp, cnt, tiles, flops);
+        take(bulk_, head_b_, budget, longest_allowed, lp, cnt, tiles, flops);
         if (cnt == 0) return !drain;  // draining with nothing that can run: a dependency cycle (cannot happen)
         lp.c.count = cnt;
         lp.c.splits = 1;
@@ -453,7 +449,6 @@ private:
     std::vector<Group> groups_;
     std::vector<Task> urgent_, bulk_;
     size_t head_u_ = 0, head_b_ = 0;
-    long long urgent_cost_ = 0, bulk_cost_ = 0;
     int launch_idx_ = 0;
 };
 
