@@ -222,7 +222,8 @@ struct NodeSpec {
     unsigned char mat, a, b, c, op, r0, rn;
 };
 
-constexpr int SUPER_PANEL = 4;  // block rows factored between two updates of the rest of the matrix (K = 512)
+constexpr int SUPER_PANEL = 4;  // block rows factored between two updates of the rest of the matrix (K = 512;
+                                // with 8 the BERT-Large stage takes as long and the stress block 6 % longer)
 
 // Builds the launch sequence of a batched inversion.
 //
@@ -397,7 +398,8 @@ private:
         // length on three quarters of the other CUs leave it 17 us longer and are done at twice the rate
         // they reach in a launch of their own.  The panel solves and row updates of the chain take nothing
         // along: they are shorter than any task, and measured with riders they lost as much time as the
-        // riders would have taken alone (12.4 - 12.6 against 12.2 ms for the BERT-Large stage).
+        // riders would have taken alone (12.4 - 12.6 against 12.1 ms for the BERT-Large stage).  Riders in the
+        // diagonal-block launches: 11.8 against 12.1 ms there, 16.25 against 17.2 ms for the stress block.
         const int slots = 256;  // one workgroup per CU in a launch with diagonal blocks
         long long budget = drain ? (1 << 20) : (with_diag ? std::max(0, slots * 3 / 4 - first_tiles) : 0);
         const int longest_allowed = drain ? (1 << 30) : std::max(own_longest, INV_DIAG_COST);
