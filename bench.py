@@ -24,7 +24,7 @@ PEAK_F32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
 PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 # HBM traffic of one curvature launch of the default workload, from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (None = not measured).
-CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 15.03e9  # profiles/curvature_syrk_pmc.txt: 13.94 GB fetched + 1.09 GB written
+CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 13.40e9  # profiles/curvature_syrk_pmc.txt: 12.31 GB fetched + 1.09 GB written
 
 
 def parse():
@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--cpu-baseline", choices=["sample", "full"], default="sample",
                     help="sample: time the oracle on a bounded part of the workload (default, seconds); "
                          "full: run the oracle over the whole step (minutes)")
+    ap.add_argument("--no-assignment", action="store_true",
+                    help="skip the work-assignment block (it runs extra launches to time the chunks; leave them out of a "
+                         "profile whose per-kernel averages should be those of the timed steps)")
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="2: after the curvature, invert the small factors (and precondition the layers that only need "
                          "them) on one stream and the large factors on another (same results; default 1)")
@@ -359,6 +362,22 @@ def main():
     # Section 3.1 with measured durations: the work of the stage cut into chunks (one grouped curvature call per
     # micro-batch and side, every launch step of the inversion), each timed with HIP events, and assigned to the
     # bubbles of each GPipe stage under rules 1 - 3.  steps_per_refresh is the paper's refresh interval.
+    if not args.no_assignment:
+        result["pipefisher_assignment"] = work_assignment(
+            binding, lib, check, xs, facs, invs, infos, ws, wsp, ws_bytes, sp, in_dtype, alpha, damping, nlay,
+            n_micro, depth, t_f, t_b, prec_ms, step)
+
+    if not args.no_cpu_baseline:
+        if args.cpu_baseline == "full":
+            result["cpu_baseline"] = cpu_baseline_full(xs, grads, layers, tokens, n_micro, damping)
+        else:
+            result["cpu_baseline"] = cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping,
+                                                  f_curv, f_inv, f_prec)
+    print(json.dumps(result))
+
+
+def work_assignment(binding, lib, check, xs, facs, invs, infos, ws, wsp, ws_bytes, sp, in_dtype, alpha, damping, nlay,
+                    n_micro, depth, t_f, t_b, prec_ms, step):
     from paper_2211_14133_amd import bubble_schedule as bs
 
     a_items = binding._curv_items(xs[0][0::2], facs[0::2])
@@ -380,20 +399,12 @@ def main():
         _, needed = bs.assign(tl, tl["t_step"] + prec_ms, works)
         refresh.append(needed)
     plan.close()
-    result["pipefisher_assignment"] = {
+    return {
         "chunks": {"curvature_A_per_microbatch_ms": round(t_curv_a, 3), "curvature_B_per_microbatch_ms": round(t_curv_b, 3),
                    "inversion_steps": len(chunk_ms), "longest_inversion_step_ms": round(max(chunk_ms), 3)},
         "inversion_ms_by_kind_of_step": {k2: round(v, 3) for k2, v in by_kind.items()},
         "steps_per_refresh_by_gpipe_stage": refresh,
     }
-
-    if not args.no_cpu_baseline:
-        if args.cpu_baseline == "full":
-            result["cpu_baseline"] = cpu_baseline_full(xs, grads, layers, tokens, n_micro, damping)
-        else:
-            result["cpu_baseline"] = cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping,
-                                                  f_curv, f_inv, f_prec)
-    print(json.dumps(result))
 
 
 def cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping, f_curv, f_inv, f_prec):
