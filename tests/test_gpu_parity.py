@@ -156,7 +156,7 @@ def gpu_invert(k, f, lam):
     return host(inv), int(host(info)[0])
 
 
-@pytest.mark.parametrize("d", [1, 2, 3, 63, 64, 65, 127, 128, 129, 200, 256, 257, 384, 767, 768, 769, 1024])
+@pytest.mark.parametrize("d", [1, 2, 3, 63, 64, 65, 127, 128, 129, 200, 256, 257, 384, 511, 513, 767, 768, 769, 1024, 1025, 1537, 2049])
 def test_invert_parity(k, oracle, d):
     print("invert d=%d" % d, flush=True)
     n = max(2 * d, 64)
