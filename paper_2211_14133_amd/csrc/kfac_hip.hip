@@ -1,7 +1,8 @@
 // C ABI of the K-FAC work-item library (see include/kfac.h) and the host-side
 // drivers that turn each work item into launches of the TN contraction engine
 // and of the diagonal-block kernel.  Everything runs on the caller's stream;
-// nothing here allocates, frees or synchronises.
+// nothing here allocates or frees device memory or synchronises (host-side
+// bookkeeping lives on the heap for the length of a call, or of a plan).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
