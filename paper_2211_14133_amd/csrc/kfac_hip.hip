@@ -39,9 +39,13 @@ inline bool ws_ok(const void *ws, size_t have, size_t need)
 
 inline double tn_problem_flops(int M, int N, int K, int tile_mode, int mask_a, int mask_b)
 {
+    // useful multiply-adds x 2: a triangular operand halves the K range on average; two of them with a
+    // triangular tile set (W W^T) leave a sixth of the full product, d^3 / 3
     double f = 2.0 * M * N * K;
-    if (tile_mode != TILE_FULL) f *= 0.5;
-    if (mask_a != MASK_NONE || mask_b != MASK_NONE) f *= (mask_a != MASK_NONE && mask_b != MASK_NONE) ? (2.0 / 3.0) : 0.5;
+    const bool both = mask_a != MASK_NONE && mask_b != MASK_NONE;
+    if (tile_mode != TILE_FULL) f *= both ? 1.0 / 6.0 : 0.5;
+    else if (both) f *= 1.0 / 3.0;
+    if (!both && (mask_a != MASK_NONE || mask_b != MASK_NONE)) f *= 0.5;
     return f;
 }
 

@@ -143,3 +143,40 @@ def test_header_is_plain_c_and_cxx():
         r = subprocess.run([cc, *flags, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", header],
                            capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_inversion_plans_are_built_on_the_host_for_every_size():
+    """Recording a plan launches nothing, so the host side of the inversion (block structure, task
+    dependencies, bounds of every operand, launch descriptors) runs here without a GPU: every size must
+    give a plan whose steps are labelled and whose model cost is the d^3 of the three phases."""
+    lib = binding.load()
+    cases = [[1], [2], [127], [128], [129], [511, 513], [1024] * 5 + [4096, 640], [2049, 100], [4096] * 3, [8192],
+             [96] * 80, [32640]]
+    for ds in cases:
+        n = len(ds)
+        items = (binding.InvertItem * n)()
+        base = 1 << 40  # made-up device addresses: nothing is dereferenced
+        for i, d in enumerate(ds):
+            items[i] = binding.InvertItem(base, d, d, base + 4 * d * d + 256, d, (1 << 39) + 4 * i)
+            base += 8 * d * d + 4096
+        need = lib.kfac_invert_batched_workspace(items, n)
+        assert need >= sum(8 * d * d for d in ds)
+        handle = ctypes.c_void_p()
+        ws = ctypes.c_void_p(1 << 42)
+        assert lib.kfac_invert_plan_create(items, n, 1e-3, ws, need - 256, ctypes.byref(handle)) == 3  # too small
+        assert lib.kfac_invert_plan_create(items, n, 1e-3, ws, need, ctypes.byref(handle)) == 0, ds
+        steps = lib.kfac_invert_plan_steps(handle)
+        assert steps >= 3
+        labels = [lib.kfac_invert_plan_step_label(handle, i) for i in range(steps)]
+        assert all(lb for lb in labels) and labels[0] == b"copy + damping" and labels[-1] == b"inverse = W W^T"
+        flops = sum(lib.kfac_invert_plan_step_flops(handle, i) for i in range(steps))
+        want = sum(float(d) ** 3 for d in ds)
+        if min(ds) >= 511:
+            assert 0.98 * want <= flops <= 1.10 * want, (ds, flops / want)
+        lib.kfac_invert_plan_destroy(handle)
+    # one row more than the block indices can address
+    items = (binding.InvertItem * 1)()
+    items[0] = binding.InvertItem(1 << 40, 32641, 32641, 1 << 41, 32641, 1 << 39)
+    handle = ctypes.c_void_p()
+    need = lib.kfac_invert_batched_workspace(items, 1)
+    assert lib.kfac_invert_plan_create(items, 1, 1e-3, ctypes.c_void_p(1 << 42), need, ctypes.byref(handle)) == 2

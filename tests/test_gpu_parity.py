@@ -437,8 +437,8 @@ def test_invert_plan_equals_batched_and_can_be_cut_anywhere(k, oracle):
     assert n > 10 and plan.position == 0
     flops = [plan.step_flops(i) for i in range(n)]
     assert all(f >= 0 for f in flops) and plan.step_flops(n) == -1.0
-    # model cost is in the right ball park: d^3 per matrix (triangular work counted at its useful share)
-    assert 0.5 * sum(d ** 3 for d in ds) <= sum(flops) <= 3.0 * sum(d ** 3 for d in ds)
+    # model cost: d^3 per matrix (the LAPACK count of the three phases; triangular work at its useful share)
+    assert 0.9 * sum(d ** 3 for d in ds) <= sum(flops) <= 1.3 * sum(d ** 3 for d in ds)
     side = torch.cuda.Stream()
     rng = np.random.default_rng(0)
     while plan.position < n:
