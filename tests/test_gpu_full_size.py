@@ -239,3 +239,49 @@ def test_block_diagonal_factor_at_the_size_the_appendix_names(oracle, capsys):
         with capsys.disabled():
             print("  block %d of %d: A %.2e  A^-1 %.2e  P %.2e   (%.0f s)" % (i, kb, ea, eai, ep, time.perf_counter() - t0), flush=True)
         assert ea <= 1e-4 and ep <= 5e-3
+
+
+def test_inversion_at_the_largest_size_the_library_takes(capsys):
+    """d = 32,640 = 255 panels of 128, the limit stated at the boundary (block indices travel as bytes).  The
+    oracle cannot invert a matrix of this size in minutes, so the result is checked through what holds at any
+    size: info, bitwise symmetry, and the residual of sampled columns with the fp64 products formed by torch."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2211_14133_amd as k
+
+    dev = torch.device("cuda:0")
+    d, lam = 255 * 128, synth.DAMPING
+    n = 2 * d  # eigenvalues of X^T X / n within about [(1 - sqrt(1/2))^2, (1 + sqrt(1/2))^2]: condition number 34
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.SEED + d)
+    f = torch.empty(d, d, device=dev)
+    half = n // 2
+    for i in range(2):  # two halves of the tokens, so that the activations take 4 GiB at a time
+        x = torch.randn(half, d, device=dev, generator=gen)
+        k.kfac_curvature(x, f, 1.0 / n, 0.0 if i == 0 else 1.0)
+        torch.cuda.synchronize()
+        del x
+    with capsys.disabled():
+        print("  factor of %d rows built" % d, flush=True)
+    inv = torch.empty_like(f)
+    info = k.kfac_invert(f, lam, inv)
+    torch.cuda.synchronize()
+    assert int(info) == 0
+    with capsys.disabled():
+        print("  inverted", flush=True)
+    # symmetric bit for bit (compared in row chunks, so that no transposed copy of the whole matrix is made)
+    for r0 in range(0, d, 4096):
+        r1 = min(d, r0 + 4096)
+        assert torch.equal(inv[r0:r1, :], inv[:, r0:r1].t())
+    cols = sorted({0, 1, 127, 128, 129, 511, 512, 4095, 4096, d // 2, d - 4097, d - 513, d - 129, d - 128, d - 2, d - 1})
+    inv_j = inv[:, cols].double()
+    res = lam * inv_j
+    for r0 in range(0, d, 2048):
+        r1 = min(d, r0 + 2048)
+        res[r0:r1] += f[r0:r1].double() @ inv_j
+    for c, j in enumerate(cols):
+        res[j, c] -= 1.0
+    worst = float(res.norm(dim=0).max())  # every sampled column of the identity has norm 1
+    with capsys.disabled():
+        print("  worst column residual %.2e" % worst, flush=True)
+    assert worst <= 2e-6 * 34 + 1e-6 * (d / 1024) ** 0.5
