@@ -336,6 +336,22 @@ __global__ void invert_clear_info_kernel(const PrepLaunch pl, int count)
     if (i < count) *pl.it[i].info = 0;
 }
 
+// Zeroes what lies above the diagonal inside the NB x NB diagonal blocks of dst (one workgroup per block:
+// blockIdx.x = block, blockIdx.y = matrix).  After the triangular inverse those blocks hold W_jj above and its
+// mirror below the diagonal; the final product reads the mirror, and with zeros above it needs no masks.
+__global__ __launch_bounds__(256) void invert_clear_upper_kernel(const PrepLaunch pl)
+{
+    const PrepItem &it = pl.it[blockIdx.y];
+    const int b0 = blockIdx.x * NB;
+    if (b0 >= it.d) return;
+    const int n = min(NB, it.d - b0);
+    float *blk = it.dst + (size_t)b0 * it.ldd + b0;
+    for (int i = threadIdx.x; i < n * n; i += 256) {
+        const int r = i / n, c = i % n;
+        if (c > r) blk[(size_t)r * it.ldd + c] = 0.f;
+    }
+}
+
 // dst = src + damping * I (full copy); a non-finite element of the upper triangle sets info = -1.
 __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl)
 {

@@ -37,8 +37,11 @@ constexpr int TN_CHUNK_SLABS = 16;  // fold the running sum every 16 * 16 = 256 
 constexpr int SUPER_ROWS = 8;      // tiles of 8 consecutive tile-rows are scheduled together
 
 enum TileMode : int { TILE_FULL = 0, TILE_LOWER = 1, TILE_UPPER = 2 };
-// Element (k, m) of an operand is kept if ...
-enum OperandMask : int { MASK_NONE = 0, MASK_KEEP_K_GE = 1, MASK_KEEP_K_LE = 2 };
+// Element (k, m) of an operand is kept if ... (MASK_KEEP_*: the other elements are read and replaced by zero).
+// MASK_ZEROS_K_LT: the caller guarantees that the operand already holds zeros where k < m, so the K range of a
+// tile is clipped as for MASK_KEEP_K_GE and no element needs a mask: such tiles take the unmasked loops.
+enum OperandMask : int { MASK_NONE = 0, MASK_KEEP_K_GE = 1, MASK_KEEP_K_LE = 2, MASK_ZEROS_K_LT = 3 };
+__host__ __device__ inline bool tn_mask_elements(int mask) { return mask == MASK_KEEP_K_GE || mask == MASK_KEEP_K_LE; }
 
 struct TnProblem {
     const float *A;    // K x M, lda
@@ -374,9 +377,9 @@ __host__ __device__ inline void tn_k_range(const TnAttr &lp, int K, int m0, int 
 {
     kb = 0;
     int ke = K;
-    if (lp.mask_a == MASK_KEEP_K_GE) kb = max(kb, m0);
+    if (lp.mask_a == MASK_KEEP_K_GE || lp.mask_a == MASK_ZEROS_K_LT) kb = max(kb, m0);
     if (lp.mask_a == MASK_KEEP_K_LE) ke = min(ke, m0 + BM);
-    if (lp.mask_b == MASK_KEEP_K_GE) kb = max(kb, n0);
+    if (lp.mask_b == MASK_KEEP_K_GE || lp.mask_b == MASK_ZEROS_K_LT) kb = max(kb, n0);
     if (lp.mask_b == MASK_KEEP_K_LE) ke = min(ke, n0 + BN);
     kb = (kb / BK) * BK;
     nslab = ke > kb ? (ke - kb + BK - 1) / BK : 0;
@@ -1167,7 +1170,7 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
 #pragma unroll
             for (int r = 0; r < 16; ++r) sum[i][j][r] = 0.f;
 
-    const bool masked = L::kAllowMask && (at.mask_a | at.mask_b) != 0;
+    const bool masked = L::kAllowMask && (tn_mask_elements(at.mask_a) || tn_mask_elements(at.mask_b));
     bool done = false;
     if constexpr (L::kPackedBf16) {
         tn_mainloop_bf16_packed(pr, tl, As, Bs, sum);
@@ -1195,8 +1198,8 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
                     // clipped K range holds whole rows.  Those slabs take the direct loop, which is
                     // faster than the masked one; short remainders are not worth its start-up.
                     int p0 = pr.K, p1 = 0;  // hull of the partly kept K rows
-                    if (at.mask_a != MASK_NONE) { p0 = min(p0, tl.m0); p1 = max(p1, tl.m0 + BM); }
-                    if (at.mask_b != MASK_NONE) { p0 = min(p0, tl.n0); p1 = max(p1, tl.n0 + BN); }
+                    if (tn_mask_elements(at.mask_a)) { p0 = min(p0, tl.m0); p1 = max(p1, tl.m0 + BM); }
+                    if (tn_mask_elements(at.mask_b)) { p0 = min(p0, tl.n0); p1 = max(p1, tl.n0 + BN); }
                     int s0 = max(tl.kt0, min(tl.kt1, (p0 - tl.kbase) / BK));             // first masked slab
                     int s1 = max(s0, min(tl.kt1, (p1 - tl.kbase + BK - 1) / BK));        // one past the last
                     constexpr int MIN_DIRECT = 8;
