@@ -82,6 +82,7 @@ struct TnCommon {
     // only fills the chip; see tn_balance_xcds)
     int xcd_begin[9];
     int xcd_begin2[9];
+    unsigned xcd_reverse;  // bit x: XCD x walks its first range from the end (its long tiles lie there)
     __host__ __device__ TnAttr attr() const
     {
         TnAttr a;
@@ -365,7 +366,7 @@ __device__ inline int tn_logical_tile(int bid, int nblocks, const TnCommon &c)
     const int xcd = bid & 7;
     int q = bid >> 3;
     const int n1 = c.xcd_begin[xcd + 1] - c.xcd_begin[xcd];
-    if (q < n1) return c.xcd_begin[xcd] + q;
+    if (q < n1) return ((c.xcd_reverse >> xcd) & 1u) ? c.xcd_begin[xcd + 1] - 1 - q : c.xcd_begin[xcd] + q;
     q -= n1;
     const int t = c.xcd_begin2[xcd] + q;
     return t < c.xcd_begin2[xcd + 1] ? t : -1;
@@ -447,6 +448,7 @@ inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1)
     TnCommon &c = ll.c;
     if (first_tiles < 0 || first_tiles > total_tiles) first_tiles = total_tiles;
     c.xcd_balanced = 0;
+    c.xcd_reverse = 0;
     if (total_tiles < 64) return total_tiles;
     constexpr int TILE_OVERHEAD = 4;
     std::vector<int> cost((size_t)total_tiles, 0);
@@ -491,6 +493,15 @@ inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1)
         have[x] += cost[(size_t)t];
     }
     while (x < 8) c.xcd_begin[++x] = first_tiles;
+    // Workgroups are dispatched in order, so a range that ends with its longest tiles finishes late: such a
+    // range is walked backwards (decided by where the cost of the range has its centre of gravity).
+    c.xcd_reverse = 0;
+    for (int i = 0; i < 8; ++i) {
+        const int b = c.xcd_begin[i], e = c.xcd_begin[i + 1];
+        long long moment = 0;
+        for (int t = b; t < e; ++t) moment += (long long)cost[(size_t)t] * (2 * (t - b) - (e - b - 1));
+        if (moment > 0) c.xcd_reverse |= 1u << i;
+    }
     // second list: each XCD is filled up to the common level
     const long long level = (total1 + total2 + 7) / 8;
     long long want[8], want_sum = 0;
