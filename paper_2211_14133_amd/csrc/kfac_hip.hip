@@ -129,6 +129,7 @@ struct TnBatch {
     int tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE, splits = 1;
     float alpha = 1.f, beta = 0.f;
     float *partial = nullptr;
+    bool deal = false;  // tiles cost the same within a problem: longest problems first, each dealt to all XCDs
 
     void add(const float *A, int lda, const float *B, int ldb, float *C, int ldc, int M, int N, int K,
              float *Ct = nullptr, int ldct = 0, const int *guard = nullptr)
@@ -144,6 +145,8 @@ struct TnBatch {
 
     void launch(Emitter &em)
     {
+        if (deal)
+            std::stable_sort(probs.begin(), probs.end(), [](const TnProblem &a, const TnProblem &b) { return a.K > b.K; });
         size_t i = 0;
         while (i < probs.size()) {
             TnLaunch lp;
@@ -166,7 +169,7 @@ struct TnBatch {
             lp.c.alpha = alpha;
             lp.c.beta = beta;
             lp.c.partial = partial;
-            const int grid = tn_balance_xcds(lp, tiles);
+            const int grid = deal && tiles >= 64 ? tn_deal_xcds(lp, tiles) : tn_balance_xcds(lp, tiles);
             em.tn(lp, grid, tiles, fl);
         }
         probs.clear();
@@ -1109,6 +1112,7 @@ kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64
             TnBatch b;
             b.tile_mode = TILE_FULL;
             b.splits = pass == 0 ? pl.splits1 : pl.splits2;
+            b.deal = true;
             b.partial = partial;
             for (size_t i = done; i < done + n; ++i) {
                 const kfac_precondition_item &it = items[i];

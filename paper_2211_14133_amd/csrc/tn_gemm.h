@@ -76,13 +76,14 @@ struct TnCommon {
     float *partial;  // [total logical tiles][BM * BN]
     int slab_align;  // K ranges of split tiles are multiples of this many slabs (0 or 1: any)
     int reverse_cols;
-    int xcd_balanced;  // 0: each XCD takes a contiguous eighth of the tiles; 1: the ranges below
+    int xcd_balanced;  // 0: each XCD takes a contiguous eighth of the tiles; 1: the ranges below;
+                       // 2: each XCD takes an eighth of every problem (tn_deal_xcds)
+    int total_tiles;   // logical tiles of the launch (used when xcd_balanced == 2)
     // XCD x works on logical tiles xcd_begin[x] .. xcd_begin[x+1]-1 and then on xcd_begin2[x] .. xcd_begin2[x+1]-1
     // (two lists of tiles, each dealt to all eight XCDs: work that the next launch waits for, then work that
     // only fills the chip; see tn_balance_xcds)
     int xcd_begin[9];
     int xcd_begin2[9];
-    unsigned xcd_reverse;  // bit x: XCD x walks its first range from the end (its long tiles lie there)
     __host__ __device__ TnAttr attr() const
     {
         TnAttr a;
@@ -366,10 +367,30 @@ __device__ inline int tn_logical_tile(int bid, int nblocks, const TnCommon &c)
     const int xcd = bid & 7;
     int q = bid >> 3;
     const int n1 = c.xcd_begin[xcd + 1] - c.xcd_begin[xcd];
-    if (q < n1) return ((c.xcd_reverse >> xcd) & 1u) ? c.xcd_begin[xcd + 1] - 1 - q : c.xcd_begin[xcd] + q;
+    if (q < n1) return c.xcd_begin[xcd] + q;
     q -= n1;
     const int t = c.xcd_begin2[xcd] + q;
     return t < c.xcd_begin2[xcd + 1] ? t : -1;
+}
+
+// xcd_balanced == 2: XCD x takes the x-th eighth of the tiles of every problem, problem after problem.
+// For launches whose tiles cost the same within a problem and differ between problems (the precondition:
+// K is the layer's width): every XCD then holds the same mix, and with the problems sorted by decreasing
+// tile cost on the host each XCD starts its long tiles first and fills up with the short ones.
+template <class L>
+__device__ inline int tn_logical_tile_dealt(const L &ll, int bid)
+{
+    const int xcd = bid & 7;
+    int q = bid >> 3;
+    const int count = ll.c.count;
+    for (int p = 0; p < count; ++p) {
+        const int b = ll.tile_begin(p);
+        const int n = (p + 1 < count ? ll.tile_begin(p + 1) : ll.c.total_tiles) - b;
+        const int lo = (int)((long long)n * xcd / 8), hi = (int)((long long)n * (xcd + 1) / 8);
+        if (q < hi - lo) return b + lo + q;
+        q -= hi - lo;
+    }
+    return -1;  // surplus workgroup
 }
 
 // K range of a tile that can hold non-zeros under the operand masks: first row kb (a multiple
@@ -448,7 +469,6 @@ inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1)
     TnCommon &c = ll.c;
     if (first_tiles < 0 || first_tiles > total_tiles) first_tiles = total_tiles;
     c.xcd_balanced = 0;
-    c.xcd_reverse = 0;
     if (total_tiles < 64) return total_tiles;
     constexpr int TILE_OVERHEAD = 4;
     std::vector<int> cost((size_t)total_tiles, 0);
@@ -493,15 +513,6 @@ inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1)
         have[x] += cost[(size_t)t];
     }
     while (x < 8) c.xcd_begin[++x] = first_tiles;
-    // Workgroups are dispatched in order, so a range that ends with its longest tiles finishes late: such a
-    // range is walked backwards (decided by where the cost of the range has its centre of gravity).
-    c.xcd_reverse = 0;
-    for (int i = 0; i < 8; ++i) {
-        const int b = c.xcd_begin[i], e = c.xcd_begin[i + 1];
-        long long moment = 0;
-        for (int t = b; t < e; ++t) moment += (long long)cost[(size_t)t] * (2 * (t - b) - (e - b - 1));
-        if (moment > 0) c.xcd_reverse |= 1u << i;
-    }
     // second list: each XCD is filled up to the common level
     const long long level = (total1 + total2 + 7) / 8;
     long long want[8], want_sum = 0;
@@ -525,6 +536,27 @@ inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1)
     for (int i = 0; i < 8; ++i)
         longest = max(longest, c.xcd_begin[i + 1] - c.xcd_begin[i] + c.xcd_begin2[i + 1] - c.xcd_begin2[i]);
     c.xcd_balanced = 1;
+    return 8 * longest;
+}
+
+// Sets up the dealt mapping (xcd_balanced == 2, see tn_logical_tile_dealt) for a launch whose problems are
+// already in the order they should run.  Returns the number of workgroups to launch.
+template <class L>
+inline int tn_deal_xcds(L &ll, int total_tiles)
+{
+    TnCommon &c = ll.c;
+    c.xcd_balanced = 2;
+    c.total_tiles = total_tiles;
+    int longest = 0;
+    for (int x = 0; x < 8; ++x) {
+        int have = 0;
+        for (int p = 0; p < c.count; ++p) {
+            const int b = ll.tile_begin(p);
+            const int n = (p + 1 < c.count ? ll.tile_begin(p + 1) : total_tiles) - b;
+            have += (int)((long long)n * (x + 1) / 8) - (int)((long long)n * x / 8);
+        }
+        longest = max(longest, have);
+    }
     return 8 * longest;
 }
 
@@ -1339,7 +1371,7 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
 template <class L>
 __device__ __forceinline__ void tn_tile_body(const L &ll, float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN])
 {
-    const int logical = tn_logical_tile(blockIdx.x, gridDim.x, ll.c);
+    const int logical = ll.c.xcd_balanced == 2 ? tn_logical_tile_dealt(ll, blockIdx.x) : tn_logical_tile(blockIdx.x, gridDim.x, ll.c);
     if (logical < 0) return;  // surplus workgroup of a short XCD range (the whole workgroup leaves)
     TnProblem pr;
     TnAttr at;
