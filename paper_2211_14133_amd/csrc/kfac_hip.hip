@@ -280,14 +280,16 @@ public:
     }
 
     // One launch of the chain: its own nodes `crit` plus tasks that ride along.
-    bool launch(const std::vector<NodeSpec> &crit, bool with_diag, const char *label)
+    // fill_round: tasks whose tiles are no longer than the launch's own may take the slots that its last
+    // round of workgroups leaves free
+    bool launch(const std::vector<NodeSpec> &crit, bool with_diag, const char *label, bool fill_round = false)
     {
         label_ = label;
         size_t i = 0;
         do {
             // leave room for some tasks even when a launch has many nodes of its own
             const size_t n = std::min(crit.size() - i, (size_t)INV_MAX_NODES - 32);
-            if (!emit(crit.data() + i, n, with_diag, false)) return false;
+            if (!emit(crit.data() + i, n, with_diag, false, fill_round)) return false;
             i += n;
         } while (i < crit.size());
         return true;
@@ -301,14 +303,14 @@ public:
             for (int g : gs)
                 if (g >= 0 && groups_[(size_t)g].pending > 0) open = true;
             if (!open) return true;
-            if (!emit(nullptr, 0, false, true)) return false;
+            if (!emit(nullptr, 0, false, true, false)) return false;
         }
     }
 
     bool finish_all()
     {
         while (head_u_ < urgent_.size() || head_b_ < bulk_.size())
-            if (!emit(nullptr, 0, false, true)) return false;
+            if (!emit(nullptr, 0, false, true, false)) return false;
         return true;
     }
 
@@ -362,13 +364,13 @@ private:
     }
 
     // Takes ready tasks from a queue, in order, until `budget` tiles are taken or the launch is full.
-    void take(std::vector<Task> &q, size_t &head, long long &budget, int longest_allowed,
+    void take(std::vector<Task> &q, size_t &head, long long &budget, int longest_allowed, bool whole_tasks_only,
               InvLaunch &lp, int &cnt, int &tiles, double &flops)
     {
         constexpr size_t WINDOW = 2048;  // tasks looked at behind the first one that cannot go yet
         for (size_t i = head; i < q.size() && i < head + WINDOW && cnt < INV_MAX_NODES && budget > 0; ++i) {
             Task &t = q[i];
-            if (t.done || t.longest > longest_allowed || !ready(t)) continue;
+            if (t.done || t.longest > longest_allowed || (whole_tasks_only && t.tiles > budget) || !ready(t)) continue;
             add_node(lp, cnt, tiles, t.n, t.tiles);
             flops += t.flops;
             budget -= t.tiles;
@@ -388,7 +390,7 @@ private:
         tiles += ntiles;
     }
 
-    bool emit(const NodeSpec *crit, size_t ncrit, bool with_diag, bool drain)
+    bool emit(const NodeSpec *crit, size_t ncrit, bool with_diag, bool drain, bool fill_round)
     {
         InvLaunch lp;
         std::memset(&lp, 0, sizeof(lp));
@@ -421,16 +423,20 @@ private:
         // diagonal-block launches: 11.8 against 12.1 ms there, 16.25 against 17.2 ms for the stress block.
         const int slots = 256;  // one workgroup per CU in a launch with diagonal blocks
         long long budget = drain ? (1 << 20) : (with_diag ? std::max(0, slots * 3 / 4 - first_tiles) : 0);
-        const int longest_allowed = drain ? (1 << 30) : std::max(own_longest, INV_DIAG_COST);
-        take(urgent_, head_u_, budget, longest_allowed, lp, cnt, tiles, flops);
-        take(bulk_, head_b_, budget, longest_allowed, lp, cnt, tiles, flops);
+        // a launch of equal tiles runs in rounds of TARGET_TILES workgroups: what the last round leaves free
+        // (less one tile per XCD: the eight XCDs take their shares separately)
+        if (fill_round && first_tiles > 0)
+            budget = std::max(0, (first_tiles + TARGET_TILES - 1) / TARGET_TILES * TARGET_TILES - first_tiles - 8);
+        const int longest_allowed = drain ? (1 << 30) : (fill_round ? own_longest : std::max(own_longest, INV_DIAG_COST));
+        take(urgent_, head_u_, budget, longest_allowed, fill_round, lp, cnt, tiles, flops);
+        take(bulk_, head_b_, budget, longest_allowed, fill_round, lp, cnt, tiles, flops);
         if (cnt == 0) return !drain;  // draining with nothing that can run: a dependency cycle (cannot happen)
         lp.c.count = cnt;
         lp.c.splits = 1;
         if (!in_bounds(lp, cnt)) return false;
         const int grid = tn_balance_xcds(lp, tiles, first_tiles);
         em_.label = drain ? "tasks: deferred row updates and products of the triangular inverse"
-                          : (tiles > first_tiles ? "diagonal blocks + tasks riding along" : label_);
+                          : (tiles > first_tiles && with_diag ? "diagonal blocks + tasks riding along" : label_);
         em_.inv(lp, grid, with_diag, flops);
         ++launch_idx_;
         return true;
@@ -860,14 +866,15 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
                 wait.push_back(row_group[mi][(size_t)i]);  // after their earlier deferred updates
             }
         if (!sch.finish_groups(wait)) return KFAC_ERR_HIP;
-        if (!crit.empty() && !sch.launch(crit, false, "update of the next super-panel's rows")) return KFAC_ERR_HIP;
-        // ... the rows below as tasks, each after the previous update of the same row
+        // ... the rows below as tasks, each after the previous update of the same row; as many of them as
+        // the last round of the launch above leaves room for go with it (their tiles are the same)
         for (size_t mi = 0; mi < mats.size(); ++mi)
             for (int i = e + SUPER_PANEL; i < mats[mi].nblk; ++i) {
                 const int g = sch.new_group(std::vector<int>{row_group[mi][(size_t)i]});
                 sch.push(NodeSpec{(unsigned char)mi, (unsigned char)s0, (unsigned char)i, (unsigned char)e, INV_ROW_UPDATE, 0, 0}, g, true);
                 row_group[mi][(size_t)i] = g;
             }
+        if (!crit.empty() && !sch.launch(crit, false, "update of the next super-panel's rows", true)) return KFAC_ERR_HIP;
     }
     if (!sch.finish_all()) return KFAC_ERR_HIP;
 
