@@ -295,9 +295,23 @@ __global__ __launch_bounds__(TN_THREADS, 1) void invert_diag_gemm_kernel(const I
     if (logical < 0) return;  // whole workgroup
     TnProblem pr;
     TnAttr at;
-    const TnTile tl = tn_locate(lp, logical, pr, at);
+    TnTile tl = tn_locate(lp, logical, pr, at);
     const InvNode &nd = lp.n[tl.prob];
-    if (nd.op == INV_DIAG) {
+    const bool is_diag = nd.op == INV_DIAG;
+    if (is_diag && nd.c != 0) {
+        // the diagonal block first takes the update with the block rows above it (one tile, K = 128 (a - b))
+        pr = lp.diag_update(tl.prob);
+        at = InvLaunch::op_attr(INV_ROW_UPDATE);
+        tl.ti = tl.tj = tl.m0 = tl.n0 = tl.split = tl.kbase = tl.kt0 = 0;
+        tl.kt1 = pr.K / BK;
+        tl.diag = false;
+    }
+    if (!is_diag || nd.c != 0)
+        tn_tile_work(lp, pr, at, tl, logical,
+                     *reinterpret_cast<float (*)[TN_LDS_STAGES][BK][BM]>(lds),
+                     *reinterpret_cast<float (*)[TN_LDS_STAGES][BK][BN]>(lds + TN_LDS_STAGES * BK * BM));
+    if (is_diag) {
+        if (nd.c != 0) __syncthreads();  // the block's stores above are read back below, by other lanes
         const InvMatDesc &mt = lp.m[nd.mat];
         const size_t q0 = (size_t)nd.a * NB, off = q0 * mt.ld + q0;
         DiagItem it;
@@ -309,11 +323,7 @@ __global__ __launch_bounds__(TN_THREADS, 1) void invert_diag_gemm_kernel(const I
         it.lds = mt.ld;
         it.pivot_base = (int)q0;
         diag_block_body(it, reinterpret_cast<float (*)[LDT]>(lds), reinterpret_cast<float (*)[LDT]>(lds + NB * LDT));
-        return;
     }
-    tn_tile_work(lp, pr, at, tl, logical,
-                 *reinterpret_cast<float (*)[TN_LDS_STAGES][BK][BM]>(lds),
-                 *reinterpret_cast<float (*)[TN_LDS_STAGES][BK][BN]>(lds + TN_LDS_STAGES * BK * BM));
 }
 
 struct PrepItem {

@@ -335,9 +335,10 @@ private:
         flops = 0.0;
         if (dm.M <= 0 || dm.N <= 0) return;
         if (n.op == INV_DIAG) {
+            const int ku = n.c ? ((int)n.a - (int)n.b) * NB : 0;  // rows of the update it applies to itself first
             tiles = 1;
-            cost = INV_DIAG_COST;
-            flops = 2.0 / 3.0 * dm.M * (double)dm.M * dm.M;
+            cost = INV_DIAG_COST + (ku ? ku / BK + 4 : 0);
+            flops = 2.0 / 3.0 * dm.M * (double)dm.M * dm.M + (double)dm.M * dm.M * ku;
             return;
         }
         const TnAttr at = InvLaunch::op_attr(n.op);
@@ -427,7 +428,7 @@ private:
         // (less one tile per XCD: the eight XCDs take their shares separately)
         if (fill_round && first_tiles > 0)
             budget = std::max(0, (first_tiles + TARGET_TILES - 1) / TARGET_TILES * TARGET_TILES - first_tiles - 8);
-        const int longest_allowed = drain ? (1 << 30) : (fill_round ? own_longest : std::max(own_longest, INV_DIAG_COST));
+        const int longest_allowed = drain ? (1 << 30) : (fill_round ? own_longest : INV_DIAG_COST);
         take(urgent_, head_u_, budget, longest_allowed, fill_round, lp, cnt, tiles, flops);
         take(bulk_, head_b_, budget, longest_allowed, fill_round, lp, cnt, tiles, flops);
         if (cnt == 0) return !drain;  // draining with nothing that can run: a dependency cycle (cannot happen)
@@ -460,8 +461,13 @@ private:
                 return r + (size_t)rows <= (size_t)m.d && c + (size_t)cols <= (size_t)m.d;
             };
             bool ok;
-            if (nd.op == INV_DIAG)
-                ok = (int)nd.a < m.nblk;
+            if (nd.op == INV_DIAG) {
+                ok = (int)nd.a < m.nblk && (nd.c == 0 || nd.b < nd.a);
+                if (ok && nd.c != 0) {
+                    const TnProblem up = lp.diag_update(i);
+                    ok = inside(up.A, up.K, up.M) && inside(up.C, up.M, up.N);
+                }
+            }
             else
                 ok = inside(pr.A, pr.K, pr.M) && inside(pr.B, pr.K, pr.N) && inside(pr.C, pr.M, pr.N) && inside(pr.Ct, pr.N, pr.M);
             if (!ok) return false;
@@ -833,17 +839,20 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
     for (int s0 = 0; s0 < max_blk; s0 += SUPER_PANEL) {
         const int e = std::min(s0 + SUPER_PANEL, max_blk);
         for (int j = s0; j < e; ++j) {
-            if (j > s0) {
-                crit.clear();
-                for (size_t mi = 0; mi < mats.size(); ++mi)
-                    if (j < mats[mi].nblk)
-                        crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)s0, (unsigned char)j, (unsigned char)j, INV_ROW_UPDATE, 0, 0});
-                if (!crit.empty() && !sch.launch(crit, false, "row update inside the super-panel")) return KFAC_ERR_HIP;
-            }
+            // One launch brings block row j up to date with the rows s0..j-1 of the super-panel and factors
+            // its diagonal block: the workgroup of the diagonal block updates that tile itself and goes
+            // straight on, the other tiles of the row are finished next to it (the panel solve, which
+            // needs both, is the next launch).
             crit.clear();
             for (size_t mi = 0; mi < mats.size(); ++mi)
-                if (j < mats[mi].nblk) crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)j, 0, 0, INV_DIAG, 0, 0});
-            if (!crit.empty() && !sch.launch(crit, true, "diagonal blocks")) return KFAC_ERR_HIP;
+                if (j < mats[mi].nblk)
+                    crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)j, (unsigned char)s0, (unsigned char)(j > s0 ? 1 : 0), INV_DIAG, 0, 0});
+            if (j > s0)
+                for (size_t mi = 0; mi < mats.size(); ++mi)
+                    if (j + 1 < mats[mi].nblk)
+                        crit.push_back(NodeSpec{(unsigned char)mi, (unsigned char)s0, (unsigned char)j, (unsigned char)j, INV_ROW_UPDATE, 1, 0});
+            if (!crit.empty() && !sch.launch(crit, true, j > s0 ? "diagonal blocks with the update of their block row" : "diagonal blocks"))
+                return KFAC_ERR_HIP;
             // W_jj is there: second products of the tree nodes that end with block j, smallest first
             for (size_t mi = 0; mi < mats.size(); ++mi)
                 for (TriNode &t : trees[mi])

@@ -160,12 +160,14 @@ constexpr int INV_DIAG_COST = 40;  // a diagonal-block node takes about as long 
 enum InvOp : int {
     INV_PANEL_SOLVE = 0,  // a = block row j:                  U[j, j+1:] = W_jj^T M[j, j+1:]
     INV_ROW_UPDATE = 1,   // a = s, b = block row j, c = e:    M[j, j:] -= U[s:e, j]^T U[s:e, j:]
+                          // (r0 = 1: without the diagonal tile, M[j, j+1:] only)
     // Triangular inverse of the block range [a, a+b+c) from its two inverted parts (b blocks, then c):
     //   [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
     INV_MERGE_YT = 2,     // Y^T = (W11 U12)^T, kept where the mirror of U12 would be (below the diagonal of F)
     INV_MERGE_W = 3,      // W12 = -Y W22, written to S together with its mirror
     INV_DIAG = 4          // a = block row j: factor the diagonal block and invert its factor (diag_block.h);
-                          // only in launches of invert_diag_gemm_kernel
+                          // c = 1: first bring it up to date, M[j, j] -= U[b:j, j]^T U[b:j, j] (the diagonal tile
+                          // that a row update with r0 = 1 leaves out); only in launches of invert_diag_gemm_kernel
 };
 
 struct InvMatDesc {
@@ -178,7 +180,7 @@ struct InvMatDesc {
 struct InvNode {
     unsigned char mat, a, b, c;
     unsigned char op;
-    unsigned char r0, rn;  // merges only: tile rows r0 .. r0+rn-1 of the output (rn = 0: all)
+    unsigned char r0, rn;  // merges: tile rows r0 .. r0+rn-1 of the output (rn = 0: all); row update: see there
     unsigned char pad_;
     int tile_begin;
 };
@@ -206,7 +208,7 @@ __host__ __device__ inline InvDims inv_dims(int op, int d, int a, int b, int c, 
         r.M = n; r.N = d - q0 - n; r.K = n;
     } else if (op == INV_ROW_UPDATE) {
         const int q0 = b * INV_NB, n = min(INV_NB, d - q0);
-        r.M = n; r.N = d - q0; r.K = (c - a) * INV_NB;
+        r.M = n; r.N = d - q0 - (r0 ? n : 0); r.K = (c - a) * INV_NB;
     } else if (op == INV_DIAG) {
         const int q0 = a * INV_NB, n = min(INV_NB, d - q0);
         r.M = n; r.N = n; r.K = n;
@@ -233,7 +235,30 @@ struct InvLaunch {
     TnCommon c;
     float *ws;  // workspace base
     __host__ __device__ int tile_begin(int i) const { return n[i].tile_begin; }
-    __host__ __device__ int fixed_cost(int i) const { return n[i].op == INV_DIAG ? INV_DIAG_COST : 0; }
+    __host__ __device__ int fixed_cost(int i) const
+    {
+        if (n[i].op != INV_DIAG) return 0;
+        return INV_DIAG_COST + (n[i].c ? ((int)n[i].a - (int)n[i].b) * (INV_NB / BK) + 4 : 0);
+    }
+    // the update of a diagonal block that its own workgroup applies before factoring it (INV_DIAG with c = 1)
+    __host__ __device__ TnProblem diag_update(int i) const
+    {
+        const InvNode &nd = n[i];
+        const InvMatDesc &mt = m[nd.mat];
+        const size_t ld = (size_t)mt.ld, k0 = (size_t)nd.b * INV_NB, q0 = (size_t)nd.a * INV_NB;
+        float *F = mat_f(nd.mat);
+        TnProblem r;
+        r.M = r.N = min(INV_NB, (int)mt.d - (int)q0);
+        r.K = ((int)nd.a - (int)nd.b) * INV_NB;
+        r.lda = r.ldb = r.ldc = r.ldct = mt.ld;
+        r.tile_begin = nd.tile_begin;
+        r.guard = nullptr;
+        r.Ct = nullptr;
+        r.A = F + k0 * ld + q0;
+        r.B = F + k0 * ld + q0;
+        r.C = F + q0 * ld + q0;
+        return r;
+    }
     __host__ __device__ float *mat_f(int mat) const { return ws + (size_t)m[mat].f_off * 64; }
     __host__ __device__ float *mat_s(int mat) const
     {
@@ -272,10 +297,10 @@ struct InvLaunch {
             r.B = F + q0 * ld + q0 + nn;
             r.C = F + q0 * ld + q0 + nn;
         } else if (nd.op == INV_ROW_UPDATE) {
-            const size_t k0 = (size_t)nd.a * INV_NB, q0 = (size_t)nd.b * INV_NB;
+            const size_t k0 = (size_t)nd.a * INV_NB, q0 = (size_t)nd.b * INV_NB, skip = nd.r0 ? (size_t)dm.M : 0;
             r.A = F + k0 * ld + q0;
-            r.B = F + k0 * ld + q0;
-            r.C = F + q0 * ld + q0;
+            r.B = F + k0 * ld + q0 + skip;
+            r.C = F + q0 * ld + q0 + skip;
         } else {
             const size_t q0 = (size_t)nd.a * INV_NB, c1 = q0 + (size_t)nd.b * INV_NB;
             const int b1 = nd.b * INV_NB, b2 = min(nd.c * INV_NB, (int)mt.d - (int)c1);
