@@ -33,18 +33,39 @@ constexpr int LDT = NB + 4;   // LDS row stride in floats
 typedef float diag_floatx16 __attribute__((ext_vector_type(16)));
 
 
-enum DiagMask : int { DM_NONE = 0, DM_UPPER = 1, DM_LOWER = 2 };  // keep row <= col / row >= col
+// One LDS array X (NB x LDT) holds everything: U on and above the diagonal, W^T = U^-T strictly below it
+// (X[c][r] = W[r][c] for r < c) and the diagonal of W in a small array of its own.  With a single array
+// two workgroups fit on a CU.  The products read their operands through one of these views (absolute
+// coordinates: the element in row `kr`, column `cc` of the operand block):
+enum DiagView : int {
+    DV_DIRECT = 0,   // X[kr][cc]                         (U, or a product kept above the diagonal)
+    DV_TRANSPOSED,   // X[cc][kr]                         (U12^T read from the block above the diagonal)
+    DV_W,            // W[kr][cc]:  X[cc][kr] below, wd on, 0 above the diagonal (kr > cc)
+    DV_W_T           // W[cc][kr]:  X[kr][cc] below, wd on, 0 where kr < cc       (W read through its mirror)
+};
 
 __device__ inline float diag_bcast(float v, int src_lane)
 {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
 }
 
-// One wave: acc = A^T B for a 32 x 32 output, A[k][m] = Aa[ak0 + k][am0 + m],
-// B[k][n] = Ba[bk0 + k][bn0 + n], k < K.  Masks act on the absolute LDS
-// coordinates (the arrays hold triangular matrices and their mirrors).
-__device__ inline diag_floatx16 sb_mma(const float (*Aa)[LDT], int ak0, int am0, int mask_a,
-                                       const float (*Ba)[LDT], int bk0, int bn0, int mask_b, int K, int lane)
+template <int VIEW>
+__device__ __forceinline__ float diag_fetch(const float (*X)[LDT], const float *wd, int kr, int cc)
+{
+    if (VIEW == DV_DIRECT) return X[kr][cc];
+    if (VIEW == DV_TRANSPOSED) return X[cc][kr];
+    if (VIEW == DV_W) {
+        const float v = (kr < cc) ? X[cc][kr] : wd[kr];  // one LDS read either way
+        return (kr > cc) ? 0.f : v;
+    }
+    const float v = (kr > cc) ? X[kr][cc] : wd[kr];
+    return (kr < cc) ? 0.f : v;
+}
+
+// One wave: acc = A^T B for a 32 x 32 output; A[k][m] is the element (ak0 + k, am0 + m) of view VA,
+// B[k][n] the element (bk0 + k, bn0 + n) of view VB, k < K.
+template <int VA, int VB>
+__device__ inline diag_floatx16 sb_mma(const float (*X)[LDT], const float *wd, int ak0, int am0, int bk0, int bn0, int K, int lane)
 {
     const int i = lane & 31, h = lane >> 5;
     diag_floatx16 acc;
@@ -52,66 +73,61 @@ __device__ inline diag_floatx16 sb_mma(const float (*Aa)[LDT], int ak0, int am0,
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll 8
     for (int kk = 0; kk < K; kk += 2) {
-        const int ra = ak0 + kk + h, ca = am0 + i;
-        const int rb = bk0 + kk + h, cb = bn0 + i;
-        float a = Aa[ra][ca];
-        float b = Ba[rb][cb];
-        if ((mask_a == DM_UPPER && ra > ca) || (mask_a == DM_LOWER && ra < ca)) a = 0.f;
-        if ((mask_b == DM_UPPER && rb > cb) || (mask_b == DM_LOWER && rb < cb)) b = 0.f;
+        const float a = diag_fetch<VA>(X, wd, ak0 + kk + h, am0 + i);
+        const float b = diag_fetch<VB>(X, wd, bk0 + kk + h, bn0 + i);
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
     }
     return acc;
 }
 
-// Store a wave's 32 x 32 result (MFMA accumulator layout) to C[cm0 + i][cn0 + j],
-// optionally also mirrored to Ct[cn0 + j][cm0 + i]; with `sub` the value
-// subtracted from what C holds (trailing update).
-__device__ inline void sb_store(diag_floatx16 acc, float (*C)[LDT], int cm0, int cn0, float scale, bool sub,
-                                float (*Ct)[LDT], int lane)
+// Store a wave's 32 x 32 result (MFMA accumulator layout: element (i, j) of the block) to X[cm0 + i][cn0 + j],
+// or transposed to X[cn0 + j][cm0 + i]; with `sub` the value is subtracted from what X holds (trailing update).
+template <bool TRANSPOSED>
+__device__ inline void sb_store(diag_floatx16 acc, float (*X)[LDT], int cm0, int cn0, float scale, bool sub, int lane)
 {
     const int j = lane & 31, h = lane >> 5;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int i = 8 * (r >> 2) + 4 * h + (r & 3);
         float v = scale * acc[r];
-        if (sub) v += C[cm0 + i][cn0 + j];
-        C[cm0 + i][cn0 + j] = v;
-        if (Ct != nullptr) Ct[cn0 + j][cm0 + i] = v;
+        if (TRANSPOSED) {
+            X[cn0 + j][cm0 + i] = v;
+        } else {
+            if (sub) v += X[cm0 + i][cn0 + j];
+            X[cm0 + i][cn0 + j] = v;
+        }
     }
 }
 
-// One wave factors the 32 x 32 diagonal sub-block at offset o (upper triangle of
-// Fs) as U^T U and inverts U, all in registers.  The symmetric block T and a
-// second matrix V (starting as the identity) are kept in MFMA accumulator layout
-// (lane = column, 16 rows per lane).  Step j takes the pivot with one readlane,
-// scales row j and applies the elimination of column j to T and V as rank-one
-// updates, one MFMA 32x32x2 each (the vector -u feeds the rows, the scaled pivot
-// row the columns; the second K slot is zero).  The same row operations that turn
-// T into U turn the identity into U^-T = W^T.  Row j of U and of W^T are final at
-// step j and go to LDS then (U above the diagonal of Fs; W above the diagonal of
-// Ss and its mirror below); nothing is read back and there is no barrier inside.  Returns the 1-based local index of the first bad pivot, or 0.
-__device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o, int lane)
+// One wave factors the 32 x 32 diagonal sub-block at offset o (upper triangle of X) as U^T U and inverts U,
+// all in registers.  The symmetric block T and a second matrix V (starting as the identity) are kept in MFMA
+// accumulator layout (lane = column, 16 rows per lane).  Step j takes the pivot with one readlane, scales
+// row j and applies the elimination of column j to T and V as rank-one updates, one MFMA 32x32x2 each (the
+// vector -u feeds the rows, the scaled pivot row the columns; the second K slot is zero).  The same row
+// operations that turn T into U turn the identity into U^-T = W^T.  Row j of U and of W^T are final at step j
+// and go to LDS then, as ONE row of X: U[j][c] for c >= j, W^T[j][c] = W[c][j] for c < j, and W[j][j] to wd;
+// nothing is read back and there is no barrier inside.  Returns the 1-based local index of the first bad
+// pivot, or 0.
+__device__ inline int sb_factor_invert(float (*X)[LDT], float *wd, int o, int lane)
 {
-    __shared__ float dump[2 * SB];  // where the lanes that do not hold row j put their (meaningless) stores
+    __shared__ float dump[2 * SB];  // where lanes put the stores that must not land anywhere
     const int c = lane & 31, h = lane >> 5;
     diag_floatx16 T, V;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int i = 8 * (r >> 2) + 4 * h + (r & 3);
-        T[r] = (i <= c) ? Fs[o + i][o + c] : Fs[o + c][o + i];
+        T[r] = (i <= c) ? X[o + i][o + c] : X[o + c][o + i];
         V[r] = (i == c) ? 1.f : 0.f;
     }
     // Row j lives in the lanes of half hj = (j / 4) % 2.  Everything that depends on "is this my row"
-    // is prepared here for both parities, so that a step has no address or mask arithmetic: store
-    // addresses are a base plus an immediate, and the other half's values are multiplied by zero.
-    float *uF[2], *wS[2], *vS[2];
+    // is prepared here for both parities, so that a step has little address arithmetic: the row's store
+    // address is a base plus an immediate, and the other half's values are multiplied by zero.
+    float *rowp[2];
     float keep[2];
 #pragma unroll
     for (int hp = 0; hp < 2; ++hp) {
         const bool mine = (h == hp);
-        uF[hp] = mine ? &Fs[o][o + c] : &Fs[o][NB];      // + j rows:     U[j][c]
-        wS[hp] = mine ? &Ss[o + c][o] : &dump[c];        // + j elements: W[c][j] (the mirror)
-        vS[hp] = mine ? &Ss[o][o + c] : &Ss[o][NB + 1];  // + j rows:     W^T[j][c]
+        rowp[hp] = mine ? &X[o][o + c] : &X[o][NB];  // + j rows: element (o + j, o + c); the others hit a pad column
         keep[hp] = mine ? 1.f : 0.f;
     }
     // The 32 steps are one dependent chain (MFMA on T -> pivot -> scale -> MFMA on T), so the order
@@ -129,19 +145,17 @@ __device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o
         __builtin_amdgcn_sched_barrier(0);
         T = __builtin_amdgcn_mfma_f32_32x32x2f32(au, u, T, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        const float vrow = V[rj] * rinv;         // row j of U^-T = column j of W, final
-        // All 32 columns of the row are stored: the entries on the wrong side of the diagonal are
-        // either unused (Fs) or exact zeros that a later step overwrites (Ss).
-        uF[hj][j * LDT] = u;
-        wS[hj][j] = vrow;
-        vS[hj][j * LDT] = vrow;
+        const float vrow = V[rj] * rinv;         // row j of U^-T = column j of W, final (0 for c > j)
+        rowp[hj][j * LDT] = (c >= j) ? u : vrow;
+        float *dp = (c == j && h == hj) ? &wd[o + j] : &dump[lane];
+        *dp = vrow;
         __builtin_amdgcn_sched_barrier(0);
         V = __builtin_amdgcn_mfma_f32_32x32x2f32(au, vrow, V, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         // row j of V stays unscaled in the accumulator; it is never read again
     }
     // first pivot whose square root is not a positive finite number
-    const float ujj = Fs[o + c][o + c];
+    const float ujj = X[o + c][o + c];
     const unsigned long long ok = __ballot(ujj > 0.f && ujj <= 3.0e38f);
     const unsigned fail = ~(unsigned)ok;
     const int bad = fail ? __builtin_ctz(fail) + 1 : 0;
@@ -159,8 +173,7 @@ __device__ inline int sb_factor_invert(float (*Fs)[LDT], float (*Ss)[LDT], int o
 // in *info as its 1-based index in the whole matrix (first failure wins); what
 // follows it in that matrix is not meaningful (NaNs) and the caller discards the
 // result.
-// Fs: U above the diagonal, its mirror below;  Ss: W = U^-1 above the diagonal, its mirror below (LDS, NB x LDT each)
-__device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*Fs)[LDT], float (*Ss)[LDT])
+__device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*X)[LDT], float *wd)
 {
     const int n = it.n;
     const int tid = threadIdx.x;
@@ -191,9 +204,8 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*Fs)[
                 const int c = c4 + t;
                 e[t] = (r <= c || r >= n || c >= n) ? e[t] : 0.f;
             }
-            // rows of Fs / Ss are 16-byte aligned (LDT * 4 = 528 bytes)
-            *reinterpret_cast<float4 *>(&Fs[r][c4]) = make_float4(e[0], e[1], e[2], e[3]);
-            *reinterpret_cast<float4 *>(&Ss[r][c4]) = make_float4(0.f, 0.f, 0.f, 0.f);
+            // rows of X are 16-byte aligned (LDT * 4 = 528 bytes)
+            *reinterpret_cast<float4 *>(&X[r][c4]) = make_float4(e[0], e[1], e[2], e[3]);
         }
     }
     __syncthreads();
@@ -201,14 +213,14 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*Fs)[
     for (int p = 0; p < NB / SB; ++p) {
         const int o = p * SB;
         if (wave == 0) {
-            const int bad = sb_factor_invert(Fs, Ss, o, lane);
+            const int bad = sb_factor_invert(X, wd, o, lane);
             if (bad != 0 && lane == 0 && o + bad <= n) atomicCAS(it.info, 0, it.pivot_base + o + bad);
         }
         __syncthreads();
-        // panel solve: U[p][q] = W_pp^T T[p][q], mirrored below the diagonal
+        // panel solve: U[p][q] = W_pp^T T[p][q]
         for (int q = p + 1 + wave; q < NB / SB; q += 4) {
-            const diag_floatx16 acc = sb_mma(Ss, o, o, DM_UPPER, Fs, o, q * SB, DM_NONE, SB, lane);
-            sb_store(acc, Fs, o, q * SB, 1.f, false, Fs, lane);
+            const diag_floatx16 acc = sb_mma<DV_W, DV_DIRECT>(X, wd, o, o, o, q * SB, SB, lane);
+            sb_store<false>(acc, X, o, q * SB, 1.f, false, lane);
         }
         __syncthreads();
         // trailing update: T[q][r] -= U[p][q]^T U[p][r] for p < q <= r
@@ -216,8 +228,8 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*Fs)[
         for (int q = p + 1; q < NB / SB; ++q)
             for (int r = q; r < NB / SB; ++r, ++job) {
                 if ((job & 3) != wave) continue;
-                const diag_floatx16 acc = sb_mma(Fs, o, q * SB, DM_NONE, Fs, o, r * SB, DM_NONE, SB, lane);
-                sb_store(acc, Fs, q * SB, r * SB, -1.f, true, nullptr, lane);
+                const diag_floatx16 acc = sb_mma<DV_DIRECT, DV_DIRECT>(X, wd, o, q * SB, o, r * SB, SB, lane);
+                sb_store<false>(acc, X, q * SB, r * SB, -1.f, true, lane);
             }
         __syncthreads();
     }
@@ -228,54 +240,61 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*Fs)[
         for (int q = 0; q < NB / 8; ++q) {
             const int r = r0 + 8 * q;
             if (n == NB) {
-                // whole rows: what lands below the diagonal of this block (mirrors, zeros) is never read
-                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) = *reinterpret_cast<const float4 *>(&Fs[r][c4]);
+                // whole rows: what lands below the diagonal of this block (parts of W^T) is never read
+                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) = *reinterpret_cast<const float4 *>(&X[r][c4]);
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int c = c4 + t;
-                    if (r < n && c < n && r <= c) it.F[(size_t)r * it.ldf + c] = Fs[r][c];
+                    if (r < n && c < n && r <= c) it.F[(size_t)r * it.ldf + c] = X[r][c];
                 }
             }
         }
     }
-    // LDS-only barrier: the merges below overwrite Fs, so every wave must have read what it stores, but
-    // nobody has to wait for the global stores themselves (__syncthreads would drain them: 3 us)
+    // LDS-only barrier: the merges below overwrite X above the diagonal, so every wave must have read what it
+    // stores, but nobody has to wait for the global stores themselves (__syncthreads would drain them: 3 us)
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
-    // Phase 2: W = U^-1 by pairwise merges, [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
+    // Phase 2: W = U^-1 by pairwise merges, [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].  A level has at
+    // most four 32 x 32 output blocks per product, one per wave.
     for (int b = SB; b < NB; b *= 2) {
         const int nodes = NB / (2 * b), sub = b / SB;       // sub x sub output sub-blocks per node
-        const int jobs = nodes * sub * sub;
-        // Y = U12 W22 = L21^T W22, stored where U12 was
-        for (int job = wave; job < jobs; job += 4) {
-            const int nd = job / (sub * sub), bi = (job / sub) % sub, bj = job % sub;
-            const int r0 = nd * 2 * b, c1 = r0 + b;
-            const diag_floatx16 acc = sb_mma(Fs, c1, r0 + bi * SB, DM_NONE, Ss, c1, c1 + bj * SB, DM_UPPER, b, lane);
-            sb_store(acc, Fs, r0 + bi * SB, c1 + bj * SB, 1.f, false, nullptr, lane);
-        }
+        const int jobs = nodes * sub * sub;                  // 2 (b = 32) or 4 (b = 64)
+        const int nd = wave / (sub * sub), bi = (wave / sub) % sub, bj = wave % sub;
+        const int r0 = nd * 2 * b, c1 = r0 + b;
+        const bool busy = wave < jobs;
+        // Y = U12 W22, stored where U12 was: every wave reads U12 before anyone overwrites it
+        diag_floatx16 acc;
+        if (busy) acc = sb_mma<DV_TRANSPOSED, DV_W>(X, wd, c1, r0 + bi * SB, c1, c1 + bj * SB, b, lane);
         __syncthreads();
-        // W12 = -W11 Y, read W11 through its mirror; mirrored again on output
-        for (int job = wave; job < jobs; job += 4) {
-            const int nd = job / (sub * sub), bi = (job / sub) % sub, bj = job % sub;
-            const int r0 = nd * 2 * b, c1 = r0 + b;
-            const diag_floatx16 acc = sb_mma(Ss, r0, r0 + bi * SB, DM_LOWER, Fs, r0, c1 + bj * SB, DM_NONE, b, lane);
-            sb_store(acc, Ss, r0 + bi * SB, c1 + bj * SB, -1.f, false, Ss, lane);
+        if (busy) sb_store<false>(acc, X, r0 + bi * SB, c1 + bj * SB, 1.f, false, lane);
+        __syncthreads();
+        // W12 = -W11 Y, W11 read through its mirror; kept as its mirror, below the diagonal
+        if (busy) {
+            acc = sb_mma<DV_W_T, DV_DIRECT>(X, wd, r0, r0 + bi * SB, r0, c1 + bj * SB, b, lane);
+            sb_store<true>(acc, X, r0 + bi * SB, c1 + bj * SB, -1.f, false, lane);
         }
         __syncthreads();
     }
+    // S block: W above the diagonal (read transposed), its diagonal, W^T below
     {
         const int c4 = (tid & 31) << 2, r0 = tid >> 5;
 #pragma unroll
         for (int q = 0; q < NB / 8; ++q) {
             const int r = r0 + 8 * q;
+            float e[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int c = c4 + t;
+                e[t] = (r > c) ? X[r][c] : ((r == c) ? wd[r] : X[c][r]);
+            }
             if (n == NB) {
-                *reinterpret_cast<float4 *>(&it.S[(size_t)r * it.lds + c4]) = *reinterpret_cast<const float4 *>(&Ss[r][c4]);
+                *reinterpret_cast<float4 *>(&it.S[(size_t)r * it.lds + c4]) = make_float4(e[0], e[1], e[2], e[3]);
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int c = c4 + t;
-                    if (r < n && c < n) it.S[(size_t)r * it.lds + c] = Ss[r][c];
+                    if (r < n && c < n) it.S[(size_t)r * it.lds + c] = e[t];
                 }
             }
         }
@@ -284,13 +303,14 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*Fs)[
 
 // The launches of the blocked inversion that contain diagonal blocks: a workgroup either factors one
 // diagonal block (INV_DIAG node) or computes one tile of a contraction node, exactly as in
-// invert_gemm_kernel.  The diagonal-block algorithm needs 132 KB of LDS, so one workgroup runs per CU;
-// the few workgroups with diagonal blocks are on the critical path of the factorisation while the
-// tiles of independent work keep the other CUs busy.
-__global__ __launch_bounds__(TN_THREADS, 1) void invert_diag_gemm_kernel(const InvLaunch lp)
+// invert_gemm_kernel.  The diagonal-block algorithm works in one 66 KB array of LDS, a little more than the
+// engine's slab ring, so two workgroups share a CU as in every other launch; the few workgroups with
+// diagonal blocks are on the critical path of the factorisation while the tiles of independent work keep
+// the rest of the chip busy.
+__global__ __launch_bounds__(TN_THREADS, 2) void invert_diag_gemm_kernel(const InvLaunch lp)
 {
-    __shared__ __attribute__((aligned(16))) float lds[2 * NB * LDT];
-    static_assert(2 * NB * LDT >= TN_LDS_STAGES * BK * (BM + BN), "the engine's slab ring fits into the same LDS");
+    __shared__ __attribute__((aligned(16))) float lds[NB * LDT + NB];
+    static_assert(NB * LDT >= TN_LDS_STAGES * BK * (BM + BN), "the engine's slab ring fits into the same LDS");
     const int logical = tn_logical_tile(blockIdx.x, gridDim.x, lp.c);
     if (logical < 0) return;  // whole workgroup
     TnProblem pr;
@@ -322,7 +342,7 @@ __global__ __launch_bounds__(TN_THREADS, 1) void invert_diag_gemm_kernel(const I
         it.ldf = mt.ld;
         it.lds = mt.ld;
         it.pivot_base = (int)q0;
-        diag_block_body(it, reinterpret_cast<float (*)[LDT]>(lds), reinterpret_cast<float (*)[LDT]>(lds + NB * LDT));
+        diag_block_body(it, reinterpret_cast<float (*)[LDT]>(lds), lds + NB * LDT);
     }
 }
 

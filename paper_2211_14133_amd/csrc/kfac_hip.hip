@@ -252,7 +252,7 @@ constexpr int SUPER_PANEL = 4;  // block rows factored between two updates of th
 // triangular inverse, which only need block rows that are already final - is cut into tasks.  A task
 // belongs to a group; a group may depend on other groups, and a task is placed in a launch only if
 // every group it depends on was completed by earlier launches.  Tasks run
-//   * in the launches of the chain that factor diagonal blocks (one workgroup per CU, most CUs free):
+//   * in the launches of the chain that factor diagonal blocks (a few dozen workgroups, most of the chip free):
 //     short tasks ride along there, as the second list of the engine's tile order;
 //   * in launches of their own when a node of the chain needs a group (the rows a super-panel is about
 //     to factor need every earlier update) or when the chain has ended: such a launch takes every
@@ -416,14 +416,15 @@ private:
         }
         const int first_tiles = tiles;
         // Which tasks ride along.  A launch that only drains the queues takes everything that is ready.  A
-        // launch with diagonal blocks keeps a dozen to 72 CUs busy for about 40 us: tiles of up to that
-        // length on three quarters of the other CUs leave it 17 us longer and are done at twice the rate
-        // they reach in a launch of their own.  The panel solves and row updates of the chain take nothing
-        // along: they are shorter than any task, and measured with riders they lost as much time as the
-        // riders would have taken alone (12.4 - 12.6 against 12.1 ms for the BERT-Large stage).  Riders in the
-        // diagonal-block launches: 11.8 against 12.1 ms there, 16.25 against 17.2 ms for the stress block.
-        const int slots = 256;  // one workgroup per CU in a launch with diagonal blocks
-        long long budget = drain ? (1 << 20) : (with_diag ? std::max(0, slots * 3 / 4 - first_tiles) : 0);
+        // launch with diagonal blocks keeps a dozen to 72 workgroups busy for about 40 us (longer when they
+        // first update their own tile): tiles of up to that length fill the other workgroup slots of the chip
+        // (two per CU), less those of the launch's own row-update tiles.  Measured on the BERT-Large stage /
+        // the stress block: 192 riders 11.42 / 16.0 ms, 288: 11.53 / 16.2, 384: 11.42 / 15.9, 480: 11.24 /
+        // 15.75, 640 to 1024: 11.22 - 11.36 / 16.0; 480 riders of up to 72 slabs: 11.3 / 15.65, of up to 28:
+        // 11.6 / 16.7.  The panel solves take nothing along: they are shorter than any task, and measured
+        // with riders they lost as much time as the riders would have taken alone.
+        constexpr int RIDER_TILES = TARGET_TILES - 32;
+        long long budget = drain ? (1 << 20) : (with_diag ? std::max(0, RIDER_TILES - first_tiles) : 0);
         // a launch of equal tiles runs in rounds of TARGET_TILES workgroups: what the last round leaves free
         // (less one tile per XCD: the eight XCDs take their shares separately)
         if (fill_round && first_tiles > 0)
