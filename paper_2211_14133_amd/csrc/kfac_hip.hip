@@ -37,15 +37,28 @@ inline bool ws_ok(const void *ws, size_t have, size_t need)
     return ws != nullptr && have >= need && (reinterpret_cast<uintptr_t>(ws) % WS_ALIGN) == 0;
 }
 
+// Kept elements of a masked operand: K rows, W columns, column c keeps the rows k >= c or k <= c.
+inline double kept_elements(int mask, double K, double W)
+{
+    if (mask == MASK_KEEP_K_LE) return W <= K ? W * (W + 1) / 2 : K * (K + 1) / 2 + (W - K) * K;
+    return W <= K ? W * K - W * (W - 1) / 2 : K * (K + 1) / 2;  // MASK_KEEP_K_GE, MASK_ZEROS_K_LT
+}
+
+// Useful multiply-adds x 2 of a problem: a triangular operand only counts with the elements it keeps; two
+// of them with a triangular tile set (W W^T) leave a sixth of the full product, d^3 / 3.
 inline double tn_problem_flops(int M, int N, int K, int tile_mode, int mask_a, int mask_b)
 {
-    // useful multiply-adds x 2: a triangular operand halves the K range on average; two of them with a
-    // triangular tile set (W W^T) leave a sixth of the full product, d^3 / 3
-    double f = 2.0 * M * N * K;
-    const bool both = mask_a != MASK_NONE && mask_b != MASK_NONE;
-    if (tile_mode != TILE_FULL) f *= both ? 1.0 / 6.0 : 0.5;
-    else if (both) f *= 1.0 / 3.0;
-    if (!both && (mask_a != MASK_NONE || mask_b != MASK_NONE)) f *= 0.5;
+    const bool ma = mask_a != MASK_NONE, mb = mask_b != MASK_NONE;
+    double f;
+    if (ma && mb)
+        f = 2.0 * M * N * K / (tile_mode != TILE_FULL ? 6.0 : 3.0);
+    else if (ma)
+        f = 2.0 * N * kept_elements(mask_a, K, M);
+    else if (mb)
+        f = 2.0 * M * kept_elements(mask_b, K, N);
+    else
+        f = 2.0 * M * N * K;
+    if (tile_mode != TILE_FULL && !(ma && mb)) f *= 0.5;
     return f;
 }
 
@@ -129,7 +142,7 @@ struct TnBatch {
     int tile_mode = TILE_FULL, mask_a = MASK_NONE, mask_b = MASK_NONE, splits = 1;
     float alpha = 1.f, beta = 0.f;
     float *partial = nullptr;
-    bool deal = false;  // tiles cost the same within a problem: longest problems first, each dealt to all XCDs
+    bool sort_by_k = false;  // the order of the problems is free: longest tiles first
 
     void add(const float *A, int lda, const float *B, int ldb, float *C, int ldc, int M, int N, int K,
              float *Ct = nullptr, int ldct = 0, const int *guard = nullptr)
@@ -145,7 +158,7 @@ struct TnBatch {
 
     void launch(Emitter &em)
     {
-        if (deal)
+        if (sort_by_k)
             std::stable_sort(probs.begin(), probs.end(), [](const TnProblem &a, const TnProblem &b) { return a.K > b.K; });
         size_t i = 0;
         while (i < probs.size()) {
@@ -169,7 +182,7 @@ struct TnBatch {
             lp.c.alpha = alpha;
             lp.c.beta = beta;
             lp.c.partial = partial;
-            const int grid = deal && tiles >= 64 ? tn_deal_xcds(lp, tiles) : tn_balance_xcds(lp, tiles);
+            const int grid = tn_map_xcds(lp, tiles);
             em.tn(lp, grid, tiles, fl);
         }
         probs.clear();
@@ -1130,7 +1143,7 @@ kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64
             TnBatch b;
             b.tile_mode = TILE_FULL;
             b.splits = pass == 0 ? pl.splits1 : pl.splits2;
-            b.deal = true;
+            b.sort_by_k = true;
             b.partial = partial;
             for (size_t i = done; i < done + n; ++i) {
                 const kfac_precondition_item &it = items[i];

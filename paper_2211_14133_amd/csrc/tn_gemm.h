@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+#include <functional>
 #include <vector>
 
 namespace kfac {
@@ -411,7 +413,8 @@ __device__ inline int tn_logical_tile_dealt(const L &ll, int bid)
     for (int p = 0; p < count; ++p) {
         const int b = ll.tile_begin(p);
         const int n = (p + 1 < count ? ll.tile_begin(p + 1) : ll.c.total_tiles) - b;
-        const int lo = (int)((long long)n * xcd / 8), hi = (int)((long long)n * (xcd + 1) / 8);
+        const int part = (xcd + p) & 7;  // rotated from problem to problem: no XCD always gets the same part
+        const int lo = (int)((long long)n * part / 8), hi = (int)((long long)n * (part + 1) / 8);
         if (q < hi - lo) return b + lo + q;
         q -= hi - lo;
     }
@@ -481,21 +484,15 @@ __device__ __forceinline__ TnTile tn_locate(const L &ll, int t, TnProblem &pr, T
     return tl;
 }
 
-// Host side of the cost-balanced XCD ranges.  Cost of a tile = slabs of its K range plus a constant for
-// its prologue and epilogue (or the fixed cost of a node that is not a contraction).  The logical tiles
-// [0, first_tiles) are cut into eight contiguous ranges of (nearly) equal cost, one per XCD; the tiles
-// [first_tiles, total_tiles), if any, are then dealt out so that the eight XCDs end up with equal total
-// cost.  Every XCD works through its first range, then through its second: what the next launch waits
-// for is spread over the whole chip and starts at once, the rest fills the chip behind it.  Returns the
-// number of workgroups to launch.
+// Host side of the blockIdx -> tile mappings.  Cost of a tile = slabs of its K range plus a constant for
+// its prologue and epilogue (or the fixed cost of a node that is not a contraction).
+constexpr int TN_TILE_OVERHEAD = 4;  // prologue and epilogue of a tile, in slabs
+
+// Cost of every logical tile of a launch.
 template <class L>
-inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1)
+inline std::vector<int> tn_tile_costs(const L &ll, int total_tiles)
 {
-    TnCommon &c = ll.c;
-    if (first_tiles < 0 || first_tiles > total_tiles) first_tiles = total_tiles;
-    c.xcd_balanced = 0;
-    if (total_tiles < 64) return total_tiles;
-    constexpr int TILE_OVERHEAD = 4;
+    const TnCommon &c = ll.c;
     std::vector<int> cost((size_t)total_tiles, 0);
     for (int pi = 0; pi < c.count; ++pi) {
         const TnProblem pr = ll.problem(pi);
@@ -522,9 +519,31 @@ inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1)
             int per = (nslab + c.splits - 1) / c.splits;
             if (c.slab_align > 1) per = (per + c.slab_align - 1) / c.slab_align * c.slab_align;
             const int kt0 = min(nslab, split * per), kt1 = min(nslab, kt0 + per);
-            cost[(size_t)t] = kt1 - kt0 + TILE_OVERHEAD;
+            cost[(size_t)t] = kt1 - kt0 + TN_TILE_OVERHEAD;
         }
     }
+    return cost;
+}
+
+// Cost-balanced XCD ranges.  The logical tiles
+// [0, first_tiles) are cut into eight contiguous ranges of (nearly) equal cost, one per XCD; the tiles
+// [first_tiles, total_tiles), if any, are then dealt out so that the eight XCDs end up with equal total
+// cost.  Every XCD works through its first range, then through its second: what the next launch waits
+// for is spread over the whole chip and starts at once, the rest fills the chip behind it.  Returns the
+// number of workgroups to launch.  (costs: tn_tile_costs of the launch, if the caller has them already)
+template <class L>
+inline int tn_balance_xcds(L &ll, int total_tiles, int first_tiles = -1, const std::vector<int> *costs = nullptr)
+{
+    TnCommon &c = ll.c;
+    if (first_tiles < 0 || first_tiles > total_tiles) first_tiles = total_tiles;
+    c.xcd_balanced = 0;
+    if (total_tiles < 64) return total_tiles;
+    std::vector<int> own;
+    if (costs == nullptr) {
+        own = tn_tile_costs(ll, total_tiles);
+        costs = &own;
+    }
+    const std::vector<int> &cost = *costs;
     long long total1 = 0, total2 = 0;
     for (int t = 0; t < first_tiles; ++t) total1 += cost[(size_t)t];
     for (int t = first_tiles; t < total_tiles; ++t) total2 += cost[(size_t)t];
@@ -578,11 +597,66 @@ inline int tn_deal_xcds(L &ll, int total_tiles)
         for (int p = 0; p < c.count; ++p) {
             const int b = ll.tile_begin(p);
             const int n = (p + 1 < c.count ? ll.tile_begin(p + 1) : total_tiles) - b;
-            have += (int)((long long)n * (x + 1) / 8) - (int)((long long)n * x / 8);
+            const int part = (x + p) & 7;
+            have += (int)((long long)n * (part + 1) / 8) - (int)((long long)n * part / 8);
         }
         longest = max(longest, have);
     }
     return 8 * longest;
+}
+
+// Length of a launch under the mapping that is set in ll.c, in slab times: every XCD starts its workgroups in
+// order on 64 slots (32 CUs x 2), each slot taking the next tile when it is free.  This list-scheduling model
+// reproduces the measured launches of the inversion and the precondition at 2.0 us per slab time; the host
+// uses it to choose between the mappings.
+template <class L>
+inline long long tn_predict_launch(const L &ll, int total_tiles, const std::vector<int> &cost)
+{
+    const TnCommon &c = ll.c;
+    constexpr int SLOTS = 64;
+    long long worst = 0;
+    std::vector<long long> heap;
+    for (int x = 0; x < 8; ++x) {
+        heap.assign(SLOTS, 0);  // a min-heap of the times at which the slots get free
+        auto run = [&](int t) {
+            std::pop_heap(heap.begin(), heap.end(), std::greater<long long>());
+            heap.back() += cost[(size_t)t];
+            std::push_heap(heap.begin(), heap.end(), std::greater<long long>());
+        };
+        if (c.xcd_balanced == 2) {
+            for (int p = 0; p < c.count; ++p) {
+                const int b = ll.tile_begin(p);
+                const int n = (p + 1 < c.count ? ll.tile_begin(p + 1) : total_tiles) - b;
+                const int part = (x + p) & 7;
+                for (int t = b + (int)((long long)n * part / 8); t < b + (int)((long long)n * (part + 1) / 8); ++t) run(t);
+            }
+        } else if (c.xcd_balanced == 1) {
+            for (int t = c.xcd_begin[x]; t < c.xcd_begin[x + 1]; ++t) run(t);
+            for (int t = c.xcd_begin2[x]; t < c.xcd_begin2[x + 1]; ++t) run(t);
+        } else {
+            const int base = total_tiles >> 3, rem = total_tiles & 7;
+            const int b = x * base + min(x, rem);
+            for (int t = b; t < b + base + (x < rem ? 1 : 0); ++t) run(t);
+        }
+        for (long long v : heap) worst = max(worst, v);
+    }
+    return worst;
+}
+
+// Sets the mapping with the shorter predicted launch: cost-balanced ranges or dealt.  Returns the number of
+// workgroups to launch.
+template <class L>
+inline int tn_map_xcds(L &ll, int total_tiles)
+{
+    if (total_tiles < 64) return tn_balance_xcds(ll, total_tiles);
+    const std::vector<int> cost = tn_tile_costs(ll, total_tiles);
+    const int grid_b = tn_balance_xcds(ll, total_tiles, -1, &cost);
+    const long long len_b = tn_predict_launch(ll, total_tiles, cost);
+    const TnCommon balanced = ll.c;
+    const int grid_d = tn_deal_xcds(ll, total_tiles);
+    if (tn_predict_launch(ll, total_tiles, cost) < len_b) return grid_d;
+    ll.c = balanced;
+    return grid_b;
 }
 
 // Unconditional load of four consecutive elements of operand row k starting at
