@@ -70,6 +70,7 @@ struct Emitter {
     virtual void clear_upper(const PrepLaunch &pl, int count, int blocks) = 0;
     virtual void inv(const InvLaunch &lp, int grid, bool with_diag, double flops) = 0;
     virtual void tn(const TnLaunch &lp, int grid, int tiles, double flops) = 0;
+    virtual void wwt(const WwtLaunch &lp, int grid, double flops) = 0;
 };
 
 void launch_prep(hipStream_t s, const PrepLaunch &pl, int count, int grid_x)
@@ -91,6 +92,11 @@ void launch_inv(hipStream_t s, const InvLaunch &lp, int grid, bool with_diag)
         hipLaunchKernelGGL(invert_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
 }
 
+void launch_wwt(hipStream_t s, const WwtLaunch &lp, int grid)
+{
+    hipLaunchKernelGGL(invert_product_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
+}
+
 void launch_tn(hipStream_t s, const TnLaunch &lp, int grid, int tiles)
 {
     hipLaunchKernelGGL(tn_gemm_kernel, dim3(grid), dim3(TN_THREADS), 0, s, lp);
@@ -104,6 +110,7 @@ struct StreamEmitter : Emitter {
     void clear_upper(const PrepLaunch &pl, int count, int blocks) override { launch_clear_upper(s, pl, count, blocks); }
     void inv(const InvLaunch &lp, int grid, bool with_diag, double) override { launch_inv(s, lp, grid, with_diag); }
     void tn(const TnLaunch &lp, int grid, int tiles, double) override { launch_tn(s, lp, grid, tiles); }
+    void wwt(const WwtLaunch &lp, int grid, double) override { launch_wwt(s, lp, grid); }
 };
 
 // One step of a recorded sequence: a kernel launch (with its helper launch, if it has one).
@@ -132,6 +139,10 @@ struct RecordEmitter : Emitter {
     void tn(const TnLaunch &lp, int grid, int tiles, double flops) override
     {
         steps.push_back(PlanStep{[lp, grid, tiles](hipStream_t s) { launch_tn(s, lp, grid, tiles); }, flops, label});
+    }
+    void wwt(const WwtLaunch &lp, int grid, double flops) override
+    {
+        steps.push_back(PlanStep{[lp, grid](hipStream_t s) { launch_wwt(s, lp, grid); }, flops, label});
     }
 };
 
@@ -920,13 +931,63 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
         em.label = "zeros above the diagonal of W^T's diagonal blocks";
         em.clear_upper(pl, (int)n, bmax);
     }
-    TnBatch lu;
-    lu.tile_mode = TILE_LOWER;
-    lu.mask_a = MASK_ZEROS_K_LT;
-    lu.mask_b = MASK_ZEROS_K_LT;
-    for (const InvMat &m : mats) lu.add(m.S, m.ld, m.S, m.ld, m.inv, m.ldi, m.d, m.d, m.d, m.inv, m.ldi, m.info);
+    // One launch for the whole batch (more only when it has more than WWT_MAX_NODES bands): a node is a band of
+    // eight tile rows of one matrix; the bands go by decreasing length of their tiles (the first band of every
+    // large matrix, then the second ones, ..., the small matrices last).
+    struct Band {
+        unsigned short mat, band;
+        int tiles, longest;
+        double flops;
+    };
+    std::vector<Band> bands;
+    for (size_t mi = 0; mi < mats.size(); ++mi) {
+        const InvMat &m = mats[mi];
+        const int nt = (m.d + BM - 1) / BM;
+        for (int b = 0; b * SUPER_ROWS < nt; ++b) {
+            const int first = wwt_band_first_tile(b, nt), next = wwt_band_first_tile(b + 1, nt);
+            const int k0 = b * SUPER_ROWS * BM;  // the K range of the band's tiles starts at their row, at k0 or later
+            // useful flops of the band's rows [k0, k1): sum over rows i of 2 (i + 1) (d - i)
+            const double r0 = k0, r1 = std::min(m.d, (b + 1) * SUPER_ROWS * BM), dd = m.d;
+            const double s1 = ((r1 - 1) * r1 - (r0 - 1) * r0) / 2;                                    // sum of i
+            const double s2 = ((r1 - 1) * r1 * (2 * r1 - 1) - (r0 - 1) * r0 * (2 * r0 - 1)) / 6;      // sum of i^2
+            const double fl = 2.0 * ((dd - 1) * s1 - s2 + dd * (r1 - r0));
+            bands.push_back(Band{(unsigned short)mi, (unsigned short)b, next - first, (m.d - k0 + BK - 1) / BK, fl});
+        }
+    }
+    std::stable_sort(bands.begin(), bands.end(), [](const Band &x, const Band &y) { return x.longest > y.longest; });
     em.label = "inverse = W W^T";
-    lu.launch(em);
+    for (size_t i0 = 0; i0 < bands.size(); i0 += WWT_MAX_NODES) {
+        const size_t n = std::min<size_t>(WWT_MAX_NODES, bands.size() - i0);
+        WwtLaunch lw;
+        std::memset(&lw, 0, sizeof(lw));
+        for (size_t mi = 0; mi < mats.size(); ++mi) {
+            lw.m[mi].inv = mats[mi].inv;
+            lw.m[mi].info = mats[mi].info;
+            lw.m[mi].f_off = mats[mi].f_off;
+            lw.m[mi].d = (unsigned short)mats[mi].d;
+            lw.m[mi].ld = (unsigned short)mats[mi].ld;
+            lw.m[mi].ldi = mats[mi].ldi;
+        }
+        lw.ws = static_cast<float *>(workspace);
+        int tiles = 0;
+        double fl = 0.0;
+        for (size_t i = 0; i < n; ++i) {
+            lw.n[i].mat = bands[i0 + i].mat;
+            lw.n[i].band = bands[i0 + i].band;
+            lw.n[i].tile_begin = tiles;
+            tiles += bands[i0 + i].tiles;
+            fl += bands[i0 + i].flops;
+        }
+        lw.c.count = (int)n;
+        lw.c.tile_mode = TILE_LOWER;
+        lw.c.mask_a = MASK_ZEROS_K_LT;
+        lw.c.mask_b = MASK_ZEROS_K_LT;
+        lw.c.splits = 1;
+        lw.c.alpha = 1.f;
+        lw.c.beta = 0.f;
+        const int grid = tn_map_xcds(lw, tiles);
+        em.wwt(lw, grid, fl);
+    }
     return KFAC_OK;
 }
 

@@ -324,6 +324,57 @@ struct InvLaunch {
     }
 };
 
+// Last phase of the inversion, inv = W W^T for every matrix of the batch in ONE launch: a node is a band
+// of SUPER_ROWS tile rows of one matrix's lower tile set (the tiles of a band differ little in length: the
+// K range of a tile starts at its row).  The host sorts the nodes by that length, so that the long tiles
+// of all matrices start first and the short ones fill up the end of the launch.
+constexpr int WWT_MAX_NODES = 160;
+struct WwtMat {
+    float *inv;      // output, ldi
+    const int *info; // stores are skipped when *info != 0
+    unsigned f_off;  // as in InvMatDesc: S follows F in the workspace
+    unsigned short d, ld;
+    int ldi;
+};
+struct WwtNode {
+    unsigned short mat, band;
+    int tile_begin;
+};
+// tiles of a d x d lower tile set (nt tile rows) that lie in the bands before `band`
+__host__ __device__ inline int wwt_band_first_tile(int band, int nt)
+{
+    const int r0 = min(band * 8, nt);
+    return r0 * (r0 + 1) / 2;
+}
+struct WwtLaunch {
+    static constexpr bool kPackedBf16 = false;
+    static constexpr bool kAllowMask = true;
+    static constexpr bool kHasDiag = false;
+    WwtMat m[INV_MAX_MATS];
+    WwtNode n[WWT_MAX_NODES];
+    TnCommon c;
+    float *ws;
+    __host__ __device__ TnAttr attr(int) const { return c.attr(); }
+    __host__ __device__ int fixed_cost(int) const { return 0; }
+    __host__ __device__ int tile_begin(int i) const { return n[i].tile_begin; }
+    __host__ __device__ TnProblem problem(int i) const
+    {
+        const WwtNode &nd = n[i];
+        const WwtMat &mt = m[nd.mat];
+        float *F = ws + (size_t)mt.f_off * 64;
+        const size_t bytes = ((size_t)mt.d * mt.ld * sizeof(float) + 255) / 256 * 256;
+        const float *S = F + bytes / sizeof(float);
+        TnProblem r;
+        r.A = S; r.B = S; r.C = mt.inv; r.Ct = mt.inv; r.guard = mt.info;
+        r.M = r.N = r.K = mt.d;
+        r.lda = r.ldb = mt.ld; r.ldc = r.ldct = mt.ldi;
+        // the node's tiles are the band's part of the matrix's own tile order
+        r.tile_begin = nd.tile_begin - wwt_band_first_tile(nd.band, (mt.d + BM - 1) / BM);
+        return r;
+    }
+};
+static_assert(SUPER_ROWS == 8, "wwt_band_first_tile counts bands of eight tile rows");
+
 __host__ __device__ inline int tn_tiles(int M, int N, int mode)
 {
     const int tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
@@ -500,7 +551,7 @@ inline std::vector<int> tn_tile_costs(const L &ll, int total_tiles)
         const int fixed = ll.fixed_cost(pi);
         const int end = pi + 1 < c.count ? ll.tile_begin(pi + 1) : total_tiles;
         const int tm = (pr.M + BM - 1) / BM, tn = (pr.N + BN - 1) / BN;
-        for (int t = pr.tile_begin; t < end; ++t) {
+        for (int t = ll.tile_begin(pi); t < end; ++t) {
             if (fixed > 0) {
                 cost[(size_t)t] = fixed;
                 continue;
@@ -1550,8 +1601,16 @@ __global__ __launch_bounds__(TN_THREADS, 2) void curvature_syrk_bf16mfma_kernel(
 
 __global__ __launch_bounds__(TN_THREADS) void curvature_reduce_packed_kernel(const SyrkLaunchPacked lp) { tn_reduce_body(lp); }
 
-static_assert(sizeof(InvLaunch) <= 4096 && sizeof(TnLaunch) <= 4096 && sizeof(SyrkLaunch) <= 4096,
+static_assert(sizeof(InvLaunch) <= 4096 && sizeof(TnLaunch) <= 4096 && sizeof(SyrkLaunch) <= 4096 && sizeof(WwtLaunch) <= 4096,
               "launch descriptors travel in the kernel arguments (4 KB)");
+
+// inv = W W^T of a whole batch (see WwtLaunch)
+__global__ __launch_bounds__(TN_THREADS, 2) void invert_product_kernel(const WwtLaunch lp)
+{
+    __shared__ float As[TN_LDS_STAGES][BK][BM];
+    __shared__ float Bs[TN_LDS_STAGES][BK][BN];
+    tn_tile_body(lp, As, Bs);
+}
 
 // The products of the blocked inversion (panel solves, row updates, merges).
 __global__ __launch_bounds__(TN_THREADS, 2) void invert_gemm_kernel(const InvLaunch lp)
