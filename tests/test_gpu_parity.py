@@ -304,6 +304,27 @@ def test_precondition_grouped(k, oracle):
         assert oracle.rel_fro(host(o), oracle.precondition(b, g, a)) <= 2e-6
 
 
+def test_precondition_grouped_many_ragged_problems(k, oracle):
+    """More problems than one launch descriptor holds, ragged sizes, layers of different width (the launches are
+    dealt over the XCDs problem by problem, with tile counts that do not divide by eight)."""
+    shapes = [(1000, 1300), (700, 2100), (384, 520)] + [(130, 257), (65, 129), (257, 130)] * 17
+    rng = np.random.default_rng(3)
+    bs, as_, gs = [], [], []
+    for do, di in shapes:
+        b = rng.standard_normal((do, do)).astype(np.float32)
+        a = rng.standard_normal((di, di)).astype(np.float32)
+        bs.append((b + b.T) / 2)
+        as_.append((a + a.T) / 2)
+        gs.append(rng.standard_normal((do, di)).astype(np.float32))
+    outs = [torch.full((do, di), 7.0, device="cuda") for do, di in shapes]
+    k.kfac_precondition_grouped([dev(b) for b in bs], [dev(a) for a in as_], [dev(g) for g in gs], outs)
+    worst = 0.0
+    for b, a, g, o in zip(bs, as_, gs, outs):
+        worst = max(worst, oracle.rel_fro(host(o), oracle.precondition(b, g, a)))
+    print("  %d problems, worst rel_fro %.2e" % (len(shapes), worst), flush=True)
+    assert worst <= 2e-6
+
+
 # ---------------------------------------------------------------- whole chain
 
 def run_chain(k, oracle, cfg_id, layers=None):
