@@ -253,6 +253,37 @@ def test_invert_batched_mixed_sizes(k, oracle):
         assert np.array_equal(single, host(inv))
 
 
+def test_invert_batch_larger_than_the_launch_descriptors(k, oracle):
+    """90 matrices: more than the 72 one launch describes (the batch is run in slices), and in the first slice more
+    row bands than one launch of the final product holds.  Every inverse must equal, bit for bit, what a call with
+    that matrix alone gives; two of them are compared with the oracle."""
+    ds = [2100] * 60 + [96] * 30
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.SEED + 90)
+    fd = []
+    for d in ds:
+        x = torch.randn(2 * d + 8, d, device="cuda", generator=gen)
+        f = torch.empty(d, d, device="cuda")
+        k.kfac_curvature(x, f, 1.0 / x.shape[0], 0.0)
+        fd.append(f)
+    invs = [torch.empty(d, d, device="cuda") for d in ds]
+    infos = k.kfac_invert_batched(fd, 1e-3, invs)
+    assert np.all(host(infos) == 0)
+    for i in (0, 17, 59, 60, 89):
+        single = torch.empty_like(fd[i])
+        assert int(k.kfac_invert(fd[i], 1e-3, single)) == 0
+        assert torch.equal(single, invs[i]), i
+    for i in (59, 89):
+        want, _ = oracle.invert(host(fd[i]).astype(np.float64), 1e-3)
+        assert oracle.rel_fro(host(invs[i]), want) <= 1e-4
+    for i in range(len(ds)):  # all of them are inverses: residual of a few columns
+        cols = [0, ds[i] // 2, ds[i] - 1]
+        res = fd[i].double() @ invs[i][:, cols].double() + 1e-3 * invs[i][:, cols].double()
+        for c, j in enumerate(cols):
+            res[j, c] -= 1.0
+        assert float(res.norm(dim=0).max()) <= 1e-4, i
+
+
 # --------------------------------------------------------------- precondition
 
 @pytest.mark.parametrize("d_out,d_in", [(64, 64), (2, 3), (5, 7), (130, 257), (768, 300), (256, 1024), (1024, 1024)])
