@@ -40,8 +40,8 @@ typedef float diag_floatx16 __attribute__((ext_vector_type(16)));
 enum DiagView : int {
     DV_DIRECT = 0,   // X[kr][cc]                         (U, or a product kept above the diagonal)
     DV_TRANSPOSED,   // X[cc][kr]                         (U12^T read from the block above the diagonal)
-    DV_W,            // W[kr][cc]:  X[cc][kr] below, wd on, 0 above the diagonal (kr > cc)
-    DV_W_T           // W[cc][kr]:  X[kr][cc] below, wd on, 0 where kr < cc       (W read through its mirror)
+    DV_W,            // W[kr][cc] (upper triangular):  X[cc][kr] for kr < cc, wd[kr] for kr == cc, 0 for kr > cc
+    DV_W_T           // W[cc][kr] (its mirror):        X[kr][cc] for kr > cc, wd[kr] for kr == cc, 0 for kr < cc
 };
 
 __device__ inline float diag_bcast(float v, int src_lane)
