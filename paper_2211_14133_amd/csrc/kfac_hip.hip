@@ -446,7 +446,8 @@ private:
         // (two per CU), less those of the launch's own row-update tiles.  Measured on the BERT-Large stage /
         // the stress block: 192 riders 11.42 / 16.0 ms, 288: 11.53 / 16.2, 384: 11.42 / 15.9, 480: 11.24 /
         // 15.75, 640 to 1024: 11.22 - 11.36 / 16.0; 480 riders of up to 72 slabs: 11.3 / 15.65, of up to 28:
-        // 11.6 / 16.7.  The panel solves take nothing along: they are shorter than any task, and measured
+        // 11.6 / 16.7; riders as long as the launch's own diagonal-block nodes (which take 52 to 68 slab times when
+        // they first update their tile): +0.05 / -0.28 ms.  The panel solves take nothing along: they are shorter than any task, and measured
         // with riders they lost as much time as the riders would have taken alone.
         constexpr int RIDER_TILES = TARGET_TILES - 32;
         long long budget = drain ? (1 << 20) : (with_diag ? std::max(0, RIDER_TILES - first_tiles) : 0);
