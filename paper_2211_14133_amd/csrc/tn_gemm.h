@@ -1457,24 +1457,56 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
     const bool fast_c = interior && ((ldc & 1) == 0) && ((reinterpret_cast<uintptr_t>(C) & 7) == 0);
 
     if (fast_c) {
+        // element (bi, bj, r) of this lane: row 2 (8 (r / 4) + 4 lh + r % 4) + bi, columns 2 li + bj of the quarter
+        float2 *row0 = reinterpret_cast<float2 *>(C + (size_t)(tl.m0 + wm + 8 * lh) * ldc + (tl.n0 + wn + 2 * li));
+        auto at_row = [&](int bi, int r) { return row0 + (size_t)(2 * (8 * (r >> 2) + (r & 3)) + bi) * (size_t)(ldc >> 1); };
+        if (beta != 0.f) {
+            // All of the tile's old values are requested before the first one is used: one memory latency for
+            // the tile, not one per row (the compiler cannot move a load over the stores of the rows before it).
+            float2 old[2][16];
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) old[bi][r] = *at_row(bi, r);
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float2 v = make_float2(alpha * sum[bi][0][r], alpha * sum[bi][1][r]);
+                    v.x += beta * old[bi][r].x;
+                    v.y += beta * old[bi][r].y;
+                    sum[bi][0][r] = v.x;
+                    sum[bi][1][r] = v.y;
+                }
+        } else {
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    sum[bi][0][r] *= alpha;
+                    sum[bi][1][r] *= alpha;
+                }
+        }
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = tl.m0 + wm + 2 * (8 * (r >> 2) + 4 * lh + (r & 3)) + bi;
-                const int n = tl.n0 + wn + 2 * li;
-                float2 *dst = reinterpret_cast<float2 *>(C + (size_t)m * ldc + n);
-                float2 v = make_float2(alpha * sum[bi][0][r], alpha * sum[bi][1][r]);
-                if (beta != 0.f) {
-                    const float2 old = *dst;
-                    v.x += beta * old.x;
-                    v.y += beta * old.y;
-                }
-                sum[bi][0][r] = v.x;
-                sum[bi][1][r] = v.y;
-                *dst = v;
-            }
+            for (int r = 0; r < 16; ++r) *at_row(bi, r) = make_float2(sum[bi][0][r], sum[bi][1][r]);
     } else {
+        // edge and diagonal tiles, element by element; as above, every old value is requested before the first is used
+        float old[2][2][16];
+        if (beta != 0.f) {
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = tl.m0 + wm + 2 * (8 * (r >> 2) + 4 * lh + (r & 3)) + bi;
+                        const int n = tl.n0 + wn + 2 * li + bj;
+                        const bool mine = m < M && n < N && tn_keep(tl.diag, at.tile_mode, m, n);
+                        old[bi][bj][r] = mine ? C[(size_t)m * ldc + n] : 0.f;
+                    }
+        }
 #pragma unroll
         for (int bi = 0; bi < 2; ++bi)
 #pragma unroll
@@ -1485,9 +1517,8 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
                     const int n = tl.n0 + wn + 2 * li + bj;
                     float v = alpha * sum[bi][bj][r];
                     if (m < M && n < N && tn_keep(tl.diag, at.tile_mode, m, n)) {
-                        float *dst = C + (size_t)m * ldc + n;
-                        if (beta != 0.f) v += beta * (*dst);
-                        *dst = v;
+                        if (beta != 0.f) v += beta * old[bi][bj][r];
+                        C[(size_t)m * ldc + n] = v;
                     }
                     sum[bi][bj][r] = v;
                 }
