@@ -163,8 +163,8 @@ __device__ inline int sb_factor_invert(float (*X)[LDT], float *wd, int o, int la
 }
 
 // In:  F block = current (already updated) diagonal block, upper triangle.
-// Out: F block upper triangle = U_kk with U_kk^T U_kk = block,
-//      S block upper triangle = W = U_kk^-1, S block strict lower triangle = W^T.
+// Out: S block upper triangle = W = U_kk^-1 (U_kk^T U_kk = block), S block strict lower triangle = W^T;
+//      F block = W with zeros below the diagonal.
 // The block is handled in LDS as 4 x 4 sub-blocks of 32 with the same blocked
 // algorithm as the whole matrix: wave-level factorisation of a diagonal
 // sub-block, MFMA products for the panel solve, the trailing update and the
@@ -233,28 +233,6 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*X)[L
             }
         __syncthreads();
     }
-    // U is final: write it out before the merges reuse the space above the diagonal.
-    {
-        const int c4 = (tid & 31) << 2, r0 = tid >> 5;
-#pragma unroll
-        for (int q = 0; q < NB / 8; ++q) {
-            const int r = r0 + 8 * q;
-            if (n == NB) {
-                // whole rows: what lands below the diagonal of this block (parts of W^T) is never read
-                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) = *reinterpret_cast<const float4 *>(&X[r][c4]);
-            } else {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int c = c4 + t;
-                    if (r < n && c < n && r <= c) it.F[(size_t)r * it.ldf + c] = X[r][c];
-                }
-            }
-        }
-    }
-    // LDS-only barrier: the merges below overwrite X above the diagonal, so every wave must have read what it
-    // stores, but nobody has to wait for the global stores themselves (__syncthreads would drain them: 3 us)
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
     // Phase 2: W = U^-1 by pairwise merges, [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].  A level has at
     // most four 32 x 32 output blocks per product, one per wave.
     for (int b = SB; b < NB; b *= 2) {
@@ -276,7 +254,8 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*X)[L
         }
         __syncthreads();
     }
-    // S block: W above the diagonal (read transposed), its diagonal, W^T below
+    // S block: W above the diagonal (read transposed), its diagonal, W^T below.  F block: W with zeros below
+    // the diagonal, for the panel solve (U_jj, which was there, is not needed again).
     {
         const int c4 = (tid & 31) << 2, r0 = tid >> 5;
 #pragma unroll
@@ -290,11 +269,16 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*X)[L
             }
             if (n == NB) {
                 *reinterpret_cast<float4 *>(&it.S[(size_t)r * it.lds + c4]) = make_float4(e[0], e[1], e[2], e[3]);
+                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) =
+                    make_float4(r > c4 ? 0.f : e[0], r > c4 + 1 ? 0.f : e[1], r > c4 + 2 ? 0.f : e[2], r > c4 + 3 ? 0.f : e[3]);
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int c = c4 + t;
-                    if (r < n && c < n) it.S[(size_t)r * it.lds + c] = e[t];
+                    if (r < n && c < n) {
+                        it.S[(size_t)r * it.lds + c] = e[t];
+                        it.F[(size_t)r * it.ldf + c] = r > c ? 0.f : e[t];
+                    }
                 }
             }
         }

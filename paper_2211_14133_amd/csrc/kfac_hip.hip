@@ -40,7 +40,7 @@ inline bool ws_ok(const void *ws, size_t have, size_t need)
 // Kept elements of a masked operand: K rows, W columns, column c keeps the rows k >= c or k <= c.
 inline double kept_elements(int mask, double K, double W)
 {
-    if (mask == MASK_KEEP_K_LE) return W <= K ? W * (W + 1) / 2 : K * (K + 1) / 2 + (W - K) * K;
+    if (mask == MASK_KEEP_K_LE || mask == MASK_ZEROS_K_GT) return W <= K ? W * (W + 1) / 2 : K * (K + 1) / 2 + (W - K) * K;
     return W <= K ? W * K - W * (W - 1) / 2 : K * (K + 1) / 2;  // MASK_KEEP_K_GE, MASK_ZEROS_K_LT
 }
 

@@ -40,9 +40,10 @@ constexpr int SUPER_ROWS = 8;      // tiles of 8 consecutive tile-rows are sched
 
 enum TileMode : int { TILE_FULL = 0, TILE_LOWER = 1, TILE_UPPER = 2 };
 // Element (k, m) of an operand is kept if ... (MASK_KEEP_*: the other elements are read and replaced by zero).
-// MASK_ZEROS_K_LT: the caller guarantees that the operand already holds zeros where k < m, so the K range of a
-// tile is clipped as for MASK_KEEP_K_GE and no element needs a mask: such tiles take the unmasked loops.
-enum OperandMask : int { MASK_NONE = 0, MASK_KEEP_K_GE = 1, MASK_KEEP_K_LE = 2, MASK_ZEROS_K_LT = 3 };
+// MASK_ZEROS_K_LT / MASK_ZEROS_K_GT: the caller guarantees that the operand already holds zeros where k < m
+// (k > m), so the K range of a tile is clipped as for MASK_KEEP_K_GE (MASK_KEEP_K_LE) and no element needs a
+// mask: such tiles take the unmasked loops.
+enum OperandMask : int { MASK_NONE = 0, MASK_KEEP_K_GE = 1, MASK_KEEP_K_LE = 2, MASK_ZEROS_K_LT = 3, MASK_ZEROS_K_GT = 4 };
 __host__ __device__ inline bool tn_mask_elements(int mask) { return mask == MASK_KEEP_K_GE || mask == MASK_KEEP_K_LE; }
 
 struct TnProblem {
@@ -156,9 +157,10 @@ constexpr int INV_MAX_MATS = 72;
 constexpr int INV_MAX_NODES = 216;
 constexpr int INV_DIAG_COST = 40;  // a diagonal-block node takes about as long as a tile of 36 slabs
 
-// Working storage of matrix `mat`: F = working copy, then the factor U above the diagonal (the blocks
-// below the diagonal are scratch of the triangular inverse); S = W = U^-1 above the diagonal and its
-// mirror W^T below.
+// Working storage of matrix `mat`: F = working copy, then the factor U in the blocks above the diagonal, in
+// the diagonal blocks W_jj = U_jj^-1 with zeros below its diagonal (what the panel solve multiplies with;
+// U_jj itself is not needed again), and the blocks below the diagonal are scratch of the triangular inverse;
+// S = W = U^-1 above the diagonal and its mirror W^T below.
 enum InvOp : int {
     INV_PANEL_SOLVE = 0,  // a = block row j:                  U[j, j+1:] = W_jj^T M[j, j+1:]
     INV_ROW_UPDATE = 1,   // a = s, b = block row j, c = e:    M[j, j:] -= U[s:e, j]^T U[s:e, j:]
@@ -271,7 +273,8 @@ struct InvLaunch {
     {
         TnAttr t;
         t.tile_mode = TILE_FULL;
-        t.mask_a = (op == INV_PANEL_SOLVE) ? MASK_KEEP_K_LE : MASK_NONE;  // W_jj is upper triangular: rows k <= column
+        t.mask_a = (op == INV_PANEL_SOLVE) ? MASK_ZEROS_K_GT : MASK_NONE;  // W_jj, upper triangular, as the diagonal-block
+                                                                           // kernel leaves it in F: zeros below the diagonal
         t.mask_b = (op == INV_MERGE_YT) ? MASK_KEEP_K_GE                  // W11 read through its mirror
                  : (op == INV_MERGE_W) ? MASK_KEEP_K_LE : MASK_NONE;      // W22 upper triangular
         t.reverse_cols = (op == INV_MERGE_W) ? 1 : 0;                     // K grows with the tile column
@@ -295,7 +298,7 @@ struct InvLaunch {
         r.Ct = nullptr;
         if (nd.op == INV_PANEL_SOLVE || nd.op == INV_DIAG) {
             const size_t q0 = (size_t)nd.a * INV_NB, nn = (size_t)dm.M;
-            r.A = S + q0 * ld + q0;
+            r.A = F + q0 * ld + q0;
             r.B = F + q0 * ld + q0 + nn;
             r.C = F + q0 * ld + q0 + nn;
         } else if (nd.op == INV_ROW_UPDATE) {
@@ -479,9 +482,9 @@ __host__ __device__ inline void tn_k_range(const TnAttr &lp, int K, int m0, int 
     kb = 0;
     int ke = K;
     if (lp.mask_a == MASK_KEEP_K_GE || lp.mask_a == MASK_ZEROS_K_LT) kb = max(kb, m0);
-    if (lp.mask_a == MASK_KEEP_K_LE) ke = min(ke, m0 + BM);
+    if (lp.mask_a == MASK_KEEP_K_LE || lp.mask_a == MASK_ZEROS_K_GT) ke = min(ke, m0 + BM);
     if (lp.mask_b == MASK_KEEP_K_GE || lp.mask_b == MASK_ZEROS_K_LT) kb = max(kb, n0);
-    if (lp.mask_b == MASK_KEEP_K_LE) ke = min(ke, n0 + BN);
+    if (lp.mask_b == MASK_KEEP_K_LE || lp.mask_b == MASK_ZEROS_K_GT) ke = min(ke, n0 + BN);
     kb = (kb / BK) * BK;
     nslab = ke > kb ? (ke - kb + BK - 1) / BK : 0;
 }
