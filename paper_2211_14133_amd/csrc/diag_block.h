@@ -163,8 +163,8 @@ __device__ inline int sb_factor_invert(float (*X)[LDT], float *wd, int o, int la
 }
 
 // In:  F block = current (already updated) diagonal block, upper triangle.
-// Out: S block upper triangle = W = U_kk^-1 (U_kk^T U_kk = block), S block strict lower triangle = W^T;
-//      F block = W with zeros below the diagonal.
+// Out: S block = W = U_kk^-1 (U_kk^T U_kk = block) with zeros below the diagonal;
+//      F block = W^T with zeros above the diagonal.
 // The block is handled in LDS as 4 x 4 sub-blocks of 32 with the same blocked
 // algorithm as the whole matrix: wave-level factorisation of a diagonal
 // sub-block, MFMA products for the panel solve, the trailing update and the
@@ -254,8 +254,8 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*X)[L
         }
         __syncthreads();
     }
-    // S block: W above the diagonal (read transposed), its diagonal, W^T below.  F block: W with zeros below
-    // the diagonal, for the panel solve (U_jj, which was there, is not needed again).
+    // S block: W (read transposed from below the diagonal of X) with zeros below its diagonal; F block: W^T with
+    // zeros above (U_jj, which was there, is not needed again).
     {
         const int c4 = (tid & 31) << 2, r0 = tid >> 5;
 #pragma unroll
@@ -265,19 +265,24 @@ __device__ __forceinline__ void diag_block_body(const DiagItem &it, float (*X)[L
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int c = c4 + t;
-                e[t] = (r > c) ? X[r][c] : ((r == c) ? wd[r] : X[c][r]);
+                e[t] = (r > c) ? X[r][c] : ((r == c) ? wd[r] : X[c][r]);  // W^T where r >= c, W where r <= c
+            }
+            float w[4], wt[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                w[t] = r > c4 + t ? 0.f : e[t];
+                wt[t] = r < c4 + t ? 0.f : e[t];
             }
             if (n == NB) {
-                *reinterpret_cast<float4 *>(&it.S[(size_t)r * it.lds + c4]) = make_float4(e[0], e[1], e[2], e[3]);
-                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) =
-                    make_float4(r > c4 ? 0.f : e[0], r > c4 + 1 ? 0.f : e[1], r > c4 + 2 ? 0.f : e[2], r > c4 + 3 ? 0.f : e[3]);
+                *reinterpret_cast<float4 *>(&it.S[(size_t)r * it.lds + c4]) = make_float4(w[0], w[1], w[2], w[3]);
+                *reinterpret_cast<float4 *>(&it.F[(size_t)r * it.ldf + c4]) = make_float4(wt[0], wt[1], wt[2], wt[3]);
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int c = c4 + t;
                     if (r < n && c < n) {
-                        it.S[(size_t)r * it.lds + c] = e[t];
-                        it.F[(size_t)r * it.ldf + c] = r > c ? 0.f : e[t];
+                        it.S[(size_t)r * it.lds + c] = w[t];
+                        it.F[(size_t)r * it.ldf + c] = wt[t];
                     }
                 }
             }
@@ -348,22 +353,6 @@ __global__ void invert_clear_info_kernel(const PrepLaunch pl, int count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) *pl.it[i].info = 0;
-}
-
-// Zeroes what lies above the diagonal inside the NB x NB diagonal blocks of dst (one workgroup per block:
-// blockIdx.x = block, blockIdx.y = matrix).  After the triangular inverse those blocks hold W_jj above and its
-// mirror below the diagonal; the final product reads the mirror, and with zeros above it needs no masks.
-__global__ __launch_bounds__(256) void invert_clear_upper_kernel(const PrepLaunch pl)
-{
-    const PrepItem &it = pl.it[blockIdx.y];
-    const int b0 = blockIdx.x * NB;
-    if (b0 >= it.d) return;
-    const int n = min(NB, it.d - b0);
-    float *blk = it.dst + (size_t)b0 * it.ldd + b0;
-    for (int i = threadIdx.x; i < n * n; i += 256) {
-        const int r = i / n, c = i % n;
-        if (c > r) blk[(size_t)r * it.ldd + c] = 0.f;
-    }
 }
 
 // dst = src + damping * I (full copy); a non-finite element of the upper triangle sets info = -1.

@@ -67,7 +67,6 @@ struct Emitter {
     virtual ~Emitter() {}
     const char *label = "";  // what the next launches do (static string; kept with recorded steps)
     virtual void prep(const PrepLaunch &pl, int count, int grid_x) = 0;
-    virtual void clear_upper(const PrepLaunch &pl, int count, int blocks) = 0;
     virtual void inv(const InvLaunch &lp, int grid, bool with_diag, double flops) = 0;
     virtual void tn(const TnLaunch &lp, int grid, int tiles, double flops) = 0;
     virtual void wwt(const WwtLaunch &lp, int grid, double flops) = 0;
@@ -77,11 +76,6 @@ void launch_prep(hipStream_t s, const PrepLaunch &pl, int count, int grid_x)
 {
     hipLaunchKernelGGL(invert_clear_info_kernel, dim3(1), dim3(128), 0, s, pl, count);
     hipLaunchKernelGGL(invert_prepare_kernel, dim3(grid_x, (unsigned)count), dim3(256), 0, s, pl);
-}
-
-void launch_clear_upper(hipStream_t s, const PrepLaunch &pl, int count, int blocks)
-{
-    hipLaunchKernelGGL(invert_clear_upper_kernel, dim3((unsigned)blocks, (unsigned)count), dim3(256), 0, s, pl);
 }
 
 void launch_inv(hipStream_t s, const InvLaunch &lp, int grid, bool with_diag)
@@ -107,7 +101,6 @@ struct StreamEmitter : Emitter {
     hipStream_t s;
     explicit StreamEmitter(hipStream_t st) : s(st) {}
     void prep(const PrepLaunch &pl, int count, int grid_x) override { launch_prep(s, pl, count, grid_x); }
-    void clear_upper(const PrepLaunch &pl, int count, int blocks) override { launch_clear_upper(s, pl, count, blocks); }
     void inv(const InvLaunch &lp, int grid, bool with_diag, double) override { launch_inv(s, lp, grid, with_diag); }
     void tn(const TnLaunch &lp, int grid, int tiles, double) override { launch_tn(s, lp, grid, tiles); }
     void wwt(const WwtLaunch &lp, int grid, double) override { launch_wwt(s, lp, grid); }
@@ -127,10 +120,6 @@ struct RecordEmitter : Emitter {
     void prep(const PrepLaunch &pl, int count, int grid_x) override
     {
         steps.push_back(PlanStep{[pl, count, grid_x](hipStream_t s) { launch_prep(s, pl, count, grid_x); }, 0.0, label});
-    }
-    void clear_upper(const PrepLaunch &pl, int count, int blocks) override
-    {
-        steps.push_back(PlanStep{[pl, count, blocks](hipStream_t s) { launch_clear_upper(s, pl, count, blocks); }, 0.0, label});
     }
     void inv(const InvLaunch &lp, int grid, bool with_diag, double flops) override
     {
@@ -914,24 +903,8 @@ kfac_status invert_emit(const kfac_invert_item *items, int64_t count, float damp
     }
     if (!sch.finish_all()) return KFAC_ERR_HIP;
 
-    // 3. inv = W W^T, read through the mirror: inv[i][j] = sum_{k >= max(i,j)} S[k][i] S[k][j].  Below its
-    //    diagonal blocks S holds W^T; inside them, W_jj above the diagonal, which nothing needs any more: it is
-    //    zeroed, so that the product only clips its K ranges and runs without operand masks.
-    for (size_t i0 = 0; i0 < mats.size(); i0 += PREP_MAX_ITEMS) {
-        const size_t n = std::min<size_t>(PREP_MAX_ITEMS, mats.size() - i0);
-        PrepLaunch pl;
-        std::memset(&pl, 0, sizeof(pl));
-        int bmax = 0;
-        for (size_t i = 0; i < n; ++i) {
-            const InvMat &m = mats[i0 + i];
-            pl.it[i].dst = m.S;
-            pl.it[i].d = m.d;
-            pl.it[i].ldd = m.ld;
-            bmax = std::max(bmax, m.nblk);
-        }
-        em.label = "zeros above the diagonal of W^T's diagonal blocks";
-        em.clear_upper(pl, (int)n, bmax);
-    }
+    // 3. inv = W W^T = (W^T)^T (W^T): inv[i][j] = sum_{k >= max(i,j)} F[k][i] F[k][j], W^T read from the diagonal
+    //    blocks of F and below (zeros above the diagonal inside them: the product only clips its K ranges).
     // One launch for the whole batch (more only when it has more than WWT_MAX_NODES bands): a node is a band of
     // eight tile rows of one matrix; the bands go by decreasing length of their tiles (the first band of every
     // large matrix, then the second ones, ..., the small matrices last).

@@ -157,18 +157,20 @@ constexpr int INV_MAX_MATS = 72;
 constexpr int INV_MAX_NODES = 216;
 constexpr int INV_DIAG_COST = 40;  // a diagonal-block node takes about as long as a tile of 36 slabs
 
-// Working storage of matrix `mat`: F = working copy, then the factor U in the blocks above the diagonal, in
-// the diagonal blocks W_jj = U_jj^-1 with zeros below its diagonal (what the panel solve multiplies with;
-// U_jj itself is not needed again), and the blocks below the diagonal are scratch of the triangular inverse;
-// S = W = U^-1 above the diagonal and its mirror W^T below.
+// Working storage of matrix `mat`, two d x d arrays.  F = working copy; then, block by block, the factor U in
+// the blocks above the diagonal and W^T = U^-T in the diagonal blocks and below (U_jj itself is not needed
+// again once W_jj is there).  S = W = U^-1 in the diagonal blocks and above; its blocks below the diagonal
+// are scratch of the triangular inverse (Y^T).  Inside the diagonal blocks both arrays hold explicit zeros on
+// the other side of the diagonal, so a product that reads a triangular operand from them only clips its K
+// range (MASK_ZEROS_*): no element is masked and every aligned tile takes the direct loop.
 enum InvOp : int {
     INV_PANEL_SOLVE = 0,  // a = block row j:                  U[j, j+1:] = W_jj^T M[j, j+1:]
     INV_ROW_UPDATE = 1,   // a = s, b = block row j, c = e:    M[j, j:] -= U[s:e, j]^T U[s:e, j:]
                           // (r0 = 1: without the diagonal tile, M[j, j+1:] only)
     // Triangular inverse of the block range [a, a+b+c) from its two inverted parts (b blocks, then c):
     //   [U11 U12; 0 U22]^-1 = [W11, -W11 U12 W22; 0, W22].
-    INV_MERGE_YT = 2,     // Y^T = (W11 U12)^T, kept where the mirror of U12 would be (below the diagonal of F)
-    INV_MERGE_W = 3,      // W12 = -Y W22, written to S together with its mirror
+    INV_MERGE_YT = 2,     // Y^T = (W11 U12)^T, kept below the diagonal of S
+    INV_MERGE_W = 3,      // W12 = -Y W22, written to S and, transposed, to F
     INV_DIAG = 4          // a = block row j: factor the diagonal block and invert its factor (diag_block.h);
                           // c = 1: first bring it up to date, M[j, j] -= U[b:j, j]^T U[b:j, j] (the diagonal tile
                           // that a row update with r0 = 1 leaves out); only in launches of invert_diag_gemm_kernel
@@ -273,10 +275,9 @@ struct InvLaunch {
     {
         TnAttr t;
         t.tile_mode = TILE_FULL;
-        t.mask_a = (op == INV_PANEL_SOLVE) ? MASK_ZEROS_K_GT : MASK_NONE;  // W_jj, upper triangular, as the diagonal-block
-                                                                           // kernel leaves it in F: zeros below the diagonal
-        t.mask_b = (op == INV_MERGE_YT) ? MASK_KEEP_K_GE                  // W11 read through its mirror
-                 : (op == INV_MERGE_W) ? MASK_KEEP_K_LE : MASK_NONE;      // W22 upper triangular
+        t.mask_a = (op == INV_PANEL_SOLVE) ? MASK_ZEROS_K_GT : MASK_NONE;  // W_jj, upper triangular (S)
+        t.mask_b = (op == INV_MERGE_YT) ? MASK_ZEROS_K_LT                  // W11^T, lower triangular (F)
+                 : (op == INV_MERGE_W) ? MASK_ZEROS_K_GT : MASK_NONE;      // W22, upper triangular (S)
         t.reverse_cols = (op == INV_MERGE_W) ? 1 : 0;                     // K grows with the tile column
         t.alpha = (op == INV_ROW_UPDATE || op == INV_MERGE_W) ? -1.f : 1.f;
         t.beta = (op == INV_ROW_UPDATE) ? 1.f : 0.f;
@@ -298,7 +299,7 @@ struct InvLaunch {
         r.Ct = nullptr;
         if (nd.op == INV_PANEL_SOLVE || nd.op == INV_DIAG) {
             const size_t q0 = (size_t)nd.a * INV_NB, nn = (size_t)dm.M;
-            r.A = F + q0 * ld + q0;
+            r.A = S + q0 * ld + q0;
             r.B = F + q0 * ld + q0 + nn;
             r.C = F + q0 * ld + q0 + nn;
         } else if (nd.op == INV_ROW_UPDATE) {
@@ -313,14 +314,14 @@ struct InvLaunch {
             if (nd.op == INV_MERGE_YT) {
                 inv_row_range(b2, nd.r0, nd.rn, first, count);
                 r.A = F + q0 * ld + c1 + first;          // U12: K = b1 rows, its columns are the rows of Y^T
-                r.B = S + q0 * ld + q0;                  // mirror of W11: element (k, n) = W11[n][k], k >= n
-                r.C = F + (c1 + first) * ld + q0;        // Y^T, b2 x b1
+                r.B = F + q0 * ld + q0;                  // W11^T: element (k, n) = W11[n][k], zero for k < n
+                r.C = S + (c1 + first) * ld + q0;        // Y^T, b2 x b1
             } else {
                 inv_row_range(b1, nd.r0, nd.rn, first, count);
-                r.A = F + c1 * ld + q0 + first;          // Y^T: K = b2 rows, its columns are the rows of W12
-                r.B = S + c1 * ld + c1;                  // W22
+                r.A = S + c1 * ld + q0 + first;          // Y^T: K = b2 rows, its columns are the rows of W12
+                r.B = S + c1 * ld + c1;                  // W22, zero for k > n
                 r.C = S + (q0 + first) * ld + c1;        // W12
-                r.Ct = S + c1 * ld + q0 + first;         // and its mirror
+                r.Ct = F + c1 * ld + q0 + first;         // and its transpose
             }
         }
         return r;
@@ -335,7 +336,7 @@ constexpr int WWT_MAX_NODES = 160;
 struct WwtMat {
     float *inv;      // output, ldi
     const int *info; // stores are skipped when *info != 0
-    unsigned f_off;  // as in InvMatDesc: S follows F in the workspace
+    unsigned f_off;  // as in InvMatDesc
     unsigned short d, ld;
     int ldi;
 };
@@ -364,11 +365,9 @@ struct WwtLaunch {
     {
         const WwtNode &nd = n[i];
         const WwtMat &mt = m[nd.mat];
-        float *F = ws + (size_t)mt.f_off * 64;
-        const size_t bytes = ((size_t)mt.d * mt.ld * sizeof(float) + 255) / 256 * 256;
-        const float *S = F + bytes / sizeof(float);
+        const float *F = ws + (size_t)mt.f_off * 64;  // W^T in its diagonal blocks and below
         TnProblem r;
-        r.A = S; r.B = S; r.C = mt.inv; r.Ct = mt.inv; r.guard = mt.info;
+        r.A = F; r.B = F; r.C = mt.inv; r.Ct = mt.inv; r.guard = mt.info;
         r.M = r.N = r.K = mt.d;
         r.lda = r.ldb = mt.ld; r.ldc = r.ldct = mt.ldi;
         // the node's tiles are the band's part of the matrix's own tile order
