@@ -37,11 +37,11 @@ inline bool ws_ok(const void *ws, size_t have, size_t need)
     return ws != nullptr && have >= need && (reinterpret_cast<uintptr_t>(ws) % WS_ALIGN) == 0;
 }
 
-// Kept elements of a masked operand: K rows, W columns, column c keeps the rows k >= c or k <= c.
+// Non-zero elements of a triangular operand: K rows, W columns, column c holds the rows k >= c or k <= c.
 inline double kept_elements(int mask, double K, double W)
 {
-    if (mask == MASK_KEEP_K_LE || mask == MASK_ZEROS_K_GT) return W <= K ? W * (W + 1) / 2 : K * (K + 1) / 2 + (W - K) * K;
-    return W <= K ? W * K - W * (W - 1) / 2 : K * (K + 1) / 2;  // MASK_KEEP_K_GE, MASK_ZEROS_K_LT
+    if (mask == MASK_ZEROS_K_GT) return W <= K ? W * (W + 1) / 2 : K * (K + 1) / 2 + (W - K) * K;
+    return W <= K ? W * K - W * (W - 1) / 2 : K * (K + 1) / 2;  // MASK_ZEROS_K_LT
 }
 
 // Useful multiply-adds x 2 of a problem: a triangular operand only counts with the elements it keeps; two

@@ -6,7 +6,7 @@
 //   curvature    X^T X                     (tokens are rows of X)
 //   precondition G^T B^-1, then T^T A^-1   (B^-1, A^-1 symmetric)
 //   inversion    the updates of an upper Cholesky factorisation M = U^T U,
-//                the triangular inverse and the product W W^T, with mirrored
+//                the triangular inverse and the product W W^T, with transposed
 //                copies kept so that each left operand can be read row-wise.
 // so one main loop serves all of them: rows of both operands are contiguous,
 // loads are 512-byte coalesced and go to LDS without a transpose.
@@ -14,8 +14,8 @@
 // Tiling: a 256-thread workgroup (4 wave64) owns a 128 x 128 tile of C; each
 // wave owns 64 x 64 as 2 x 2 MFMA 32x32x2 blocks (64 accumulator registers).
 // K advances in slabs of 16 through a ring of LDS stages: straight from global
-// memory into LDS for aligned unmasked tiles (tn_mainloop_direct), through staging
-// registers with a fix-up for ragged or masked ones (tn_mainloop).
+// memory into LDS for aligned tiles (tn_mainloop_direct), through staging
+// registers with a zero fix-up for ragged ones (tn_mainloop).
 // The token sum is folded into a second accumulator every TN_CHUNK_SLABS slabs, so
 // the fp32 rounding error grows with the chunk length, not with K.
 #pragma once
@@ -39,12 +39,11 @@ constexpr int TN_CHUNK_SLABS = 16;  // fold the running sum every 16 * 16 = 256 
 constexpr int SUPER_ROWS = 8;      // tiles of 8 consecutive tile-rows are scheduled together
 
 enum TileMode : int { TILE_FULL = 0, TILE_LOWER = 1, TILE_UPPER = 2 };
-// Element (k, m) of an operand is kept if ... (MASK_KEEP_*: the other elements are read and replaced by zero).
-// MASK_ZEROS_K_LT / MASK_ZEROS_K_GT: the caller guarantees that the operand already holds zeros where k < m
-// (k > m), so the K range of a tile is clipped as for MASK_KEEP_K_GE (MASK_KEEP_K_LE) and no element needs a
-// mask: such tiles take the unmasked loops.
-enum OperandMask : int { MASK_NONE = 0, MASK_KEEP_K_GE = 1, MASK_KEEP_K_LE = 2, MASK_ZEROS_K_LT = 3, MASK_ZEROS_K_GT = 4 };
-__host__ __device__ inline bool tn_mask_elements(int mask) { return mask == MASK_KEEP_K_GE || mask == MASK_KEEP_K_LE; }
+// Triangular operands.  MASK_ZEROS_K_LT / MASK_ZEROS_K_GT: the caller guarantees that the operand holds zeros
+// where k < m (k > m) inside the 128 x 128 block on its diagonal; what lies beyond that block on the zero side
+// may hold anything and is never read, because the K range of a tile is clipped to start (end) at its own
+// diagonal block.  No element is masked: such tiles take the same loops as every other.
+enum OperandMask : int { MASK_NONE = 0, MASK_ZEROS_K_LT = 3, MASK_ZEROS_K_GT = 4 };
 
 struct TnProblem {
     const float *A;    // K x M, lda
@@ -99,7 +98,6 @@ struct TnCommon {
 // General launch: up to TN_MAX_PROBLEMS arbitrary problems.
 struct TnLaunch {
     static constexpr bool kPackedBf16 = false;
-    static constexpr bool kAllowMask = true;
     TnProblem p[TN_MAX_PROBLEMS];
     TnCommon c;
     static constexpr bool kHasDiag = false;
@@ -126,7 +124,6 @@ struct SyrkProblem {
 template <bool PACKED>
 struct SyrkLaunchT {
     static constexpr bool kPackedBf16 = PACKED;
-    static constexpr bool kAllowMask = false;
     static constexpr bool kHasDiag = false;
     SyrkProblem p[SYRK_MAX_PROBLEMS];
     TnCommon c;
@@ -234,7 +231,6 @@ __host__ __device__ inline InvDims inv_dims(int op, int d, int a, int b, int c, 
 
 struct InvLaunch {
     static constexpr bool kPackedBf16 = false;
-    static constexpr bool kAllowMask = true;
     static constexpr bool kHasDiag = true;
     InvMatDesc m[INV_MAX_MATS];
     InvNode n[INV_MAX_NODES];
@@ -352,7 +348,6 @@ __host__ __device__ inline int wwt_band_first_tile(int band, int nt)
 }
 struct WwtLaunch {
     static constexpr bool kPackedBf16 = false;
-    static constexpr bool kAllowMask = true;
     static constexpr bool kHasDiag = false;
     WwtMat m[INV_MAX_MATS];
     WwtNode n[WWT_MAX_NODES];
@@ -480,10 +475,10 @@ __host__ __device__ inline void tn_k_range(const TnAttr &lp, int K, int m0, int 
 {
     kb = 0;
     int ke = K;
-    if (lp.mask_a == MASK_KEEP_K_GE || lp.mask_a == MASK_ZEROS_K_LT) kb = max(kb, m0);
-    if (lp.mask_a == MASK_KEEP_K_LE || lp.mask_a == MASK_ZEROS_K_GT) ke = min(ke, m0 + BM);
-    if (lp.mask_b == MASK_KEEP_K_GE || lp.mask_b == MASK_ZEROS_K_LT) kb = max(kb, n0);
-    if (lp.mask_b == MASK_KEEP_K_LE || lp.mask_b == MASK_ZEROS_K_GT) ke = min(ke, n0 + BN);
+    if (lp.mask_a == MASK_ZEROS_K_LT) kb = max(kb, m0);
+    if (lp.mask_a == MASK_ZEROS_K_GT) ke = min(ke, m0 + BM);
+    if (lp.mask_b == MASK_ZEROS_K_LT) kb = max(kb, n0);
+    if (lp.mask_b == MASK_ZEROS_K_GT) ke = min(ke, n0 + BN);
     kb = (kb / BK) * BK;
     nslab = ke > kb ? (ke - kb + BK - 1) / BK : 0;
 }
@@ -731,8 +726,8 @@ __device__ inline float4 tn_load4(const float *P, int k, int c, int ld, int K, i
     return v;
 }
 
-template <bool FAST, bool MASKED>
-__device__ inline float4 tn_fix4(float4 v, int k, int c, int K, int W, int mask)
+template <bool FAST>
+__device__ inline float4 tn_fix4(float4 v, int k, int c, int K, int W)
 {
     // branch-free on purpose: the K loop must stay one basic block
     const bool kz = k >= K;
@@ -742,13 +737,6 @@ __device__ inline float4 tn_fix4(float4 v, int k, int c, int K, int W, int mask)
         z1 |= (c + 1 >= W);
         z2 |= (c + 2 >= W);
         z3 |= (c + 3 >= W);
-    }
-    if (MASKED) {
-        const bool ge = (mask == MASK_KEEP_K_GE), le = (mask == MASK_KEEP_K_LE);
-        z0 |= (ge & (k < c + 0)) | (le & (k > c + 0));
-        z1 |= (ge & (k < c + 1)) | (le & (k > c + 1));
-        z2 |= (ge & (k < c + 2)) | (le & (k > c + 2));
-        z3 |= (ge & (k < c + 3)) | (le & (k > c + 3));
     }
     v.x = z0 ? 0.f : v.x;
     v.y = z1 ? 0.f : v.y;
@@ -785,7 +773,7 @@ constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_W
 // which every wave finished reading before the previous barrier.  Loads past
 // the end of the K range are clamped to valid rows and their data is never
 // used, which keeps the loop body free of branches.
-template <bool FAST, bool MASKED>
+template <bool FAST>
 __device__ __forceinline__ void tn_mainloop(const TnAttr &lp, const TnProblem &pr, const TnTile &tl,
                                    float (&As)[TN_LDS_STAGES][BK][BM], float (&Bs)[TN_LDS_STAGES][BK][BN],
                                    floatx16 (&sum)[2][2])
@@ -795,7 +783,6 @@ __device__ __forceinline__ void tn_mainloop(const TnAttr &lp, const TnProblem &p
     const float *__restrict__ A = pr.A;
     const float *__restrict__ B = pr.B;
     const int lda = pr.lda, ldb = pr.ldb;
-    const int mask_a = lp.mask_a, mask_b = lp.mask_b;
 
     const int lrow = tid >> 5;         // 0..7 (and +8)
     const int lcol = (tid & 31) << 2;  // 0..124
@@ -829,10 +816,10 @@ __device__ __forceinline__ void tn_mainloop(const TnAttr &lp, const TnProblem &p
     } while (0)
 #define TN_W(st, set)                                                                                                  \
     do {                                                                                                               \
-        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(ra[set][0], kw, ca, K, M, mask_a);     \
-        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(ra[set][1], kw + 8, ca, K, M, mask_a); \
-        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST, MASKED>(rb[set][0], kw, cb, K, N, mask_b);     \
-        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST, MASKED>(rb[set][1], kw + 8, cb, K, N, mask_b); \
+        *reinterpret_cast<float4 *>(&As[st][lrow][lcol]) = tn_fix4<FAST>(ra[set][0], kw, ca, K, M);     \
+        *reinterpret_cast<float4 *>(&As[st][lrow + 8][lcol]) = tn_fix4<FAST>(ra[set][1], kw + 8, ca, K, M); \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow][lcol]) = tn_fix4<FAST>(rb[set][0], kw, cb, K, N);     \
+        *reinterpret_cast<float4 *>(&Bs[st][lrow + 8][lcol]) = tn_fix4<FAST>(rb[set][1], kw + 8, cb, K, N); \
         kw += BK;                                                                                                      \
     } while (0)
     // lane (li, lh) feeds rows 2*li, 2*li+1 of the wave tile at k = 2*step + lh
@@ -953,8 +940,8 @@ __device__ inline void tn_dma16_s(const float *sbase, unsigned voff, unsigned ld
                  : "memory", "m0");
 }
 
-// K loop for the common case (fp32 operands, aligned full-width tiles, no
-// masks, K range a multiple of BK): slabs go from global memory straight into
+// K loop for the common case (fp32 operands, aligned full-width tiles, K range
+// a multiple of BK): slabs go from global memory straight into
 // LDS (global_load_lds_dwordx4: lane l's 16 bytes land at base + 16*l, so one
 // wave instruction fills two 512-byte rows), without staging registers, LDS
 // stores or fix-up arithmetic.  Four LDS stages:
@@ -1365,7 +1352,6 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
 #pragma unroll
             for (int r = 0; r < 16; ++r) sum[i][j][r] = 0.f;
 
-    const bool masked = L::kAllowMask && (tn_mask_elements(at.mask_a) || tn_mask_elements(at.mask_b));
     bool done = false;
     if constexpr (L::kPackedBf16) {
         tn_mainloop_bf16_packed(pr, tl, As, Bs, sum);
@@ -1374,10 +1360,10 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
     // (the direct loop addresses a slab with 32-bit byte offsets from its first row)
     const bool direct_ok = (pr.K % BK) == 0 && pr.lda < (1 << 25) && pr.ldb < (1 << 25);
     // diagonal tile of a triangular launch: the wave whose 64 x 64 quarter lies wholly on the mirrored side
-    // has nothing to compute (its stores are all masked); in the direct loop it only helps to move the slabs,
+    // has nothing to compute (none of it is stored); in the direct loop it only helps to move the slabs,
     // which leaves its share of the matrix core to the co-resident workgroup and saves power
     const bool idle_wave = tl.diag && ((at.tile_mode == TILE_LOWER && wn > wm) || (at.tile_mode == TILE_UPPER && wm > wn));
-    if (!done && fast_a && fast_b && !masked && direct_ok) {
+    if (!done && fast_a && fast_b && direct_ok) {
         if (idle_wave)
             tn_mainloop_direct<true>(pr, tl, As, Bs, sum);
         else
@@ -1385,52 +1371,10 @@ __device__ __forceinline__ void tn_tile_work(const L &ll, const TnProblem &pr, c
         done = true;
     }
     if (!done) {
-        if constexpr (L::kAllowMask) {
-            if (masked) {
-                if (fast_a && fast_b) {
-                    // A triangular operand is only partly kept where K runs through the tile's own
-                    // diagonal block (at most BM rows of K per masked operand); outside of it the
-                    // clipped K range holds whole rows.  Those slabs take the direct loop, which is
-                    // faster than the masked one; short remainders are not worth its start-up.
-                    int p0 = pr.K, p1 = 0;  // hull of the partly kept K rows
-                    if (tn_mask_elements(at.mask_a)) { p0 = min(p0, tl.m0); p1 = max(p1, tl.m0 + BM); }
-                    if (tn_mask_elements(at.mask_b)) { p0 = min(p0, tl.n0); p1 = max(p1, tl.n0 + BN); }
-                    int s0 = max(tl.kt0, min(tl.kt1, (p0 - tl.kbase) / BK));             // first masked slab
-                    int s1 = max(s0, min(tl.kt1, (p1 - tl.kbase + BK - 1) / BK));        // one past the last
-                    constexpr int MIN_DIRECT = 8;
-                    if (!direct_ok || s0 - tl.kt0 < MIN_DIRECT) s0 = tl.kt0;
-                    if (!direct_ok || tl.kt1 - s1 < MIN_DIRECT) s1 = tl.kt1;
-                    TnTile seg = tl;
-                    if (s0 > tl.kt0) {
-                        seg.kt0 = tl.kt0; seg.kt1 = s0;
-                        if (idle_wave)
-                            tn_mainloop_direct<true>(pr, seg, As, Bs, sum);
-                        else
-                            tn_mainloop_direct<false>(pr, seg, As, Bs, sum);
-                        __syncthreads();
-                    }
-                    seg.kt0 = s0; seg.kt1 = s1;
-                    tn_mainloop<true, true>(at, pr, seg, As, Bs, sum);
-                    if (s1 < tl.kt1) {
-                        __syncthreads();
-                        seg.kt0 = s1; seg.kt1 = tl.kt1;
-                        if (idle_wave)
-                            tn_mainloop_direct<true>(pr, seg, As, Bs, sum);
-                        else
-                            tn_mainloop_direct<false>(pr, seg, As, Bs, sum);
-                    }
-                } else {
-                    tn_mainloop<false, true>(at, pr, tl, As, Bs, sum);
-                }
-                done = true;
-            }
-        }
-        if (!done) {
-            if (fast_a && fast_b)
-                tn_mainloop<true, false>(at, pr, tl, As, Bs, sum);
-            else
-                tn_mainloop<false, false>(at, pr, tl, As, Bs, sum);
-        }
+        if (fast_a && fast_b)
+            tn_mainloop<true>(at, pr, tl, As, Bs, sum);
+        else
+            tn_mainloop<false>(at, pr, tl, As, Bs, sum);
     }
 
     // Accumulator layout of MFMA 32x32: register r of lane (li, lh) is row
