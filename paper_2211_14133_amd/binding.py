@@ -131,7 +131,7 @@ def _workspace(nbytes, like, workspace, stream=None):
         if stream is not None:
             workspace.record_stream(stream)
     ptr = (workspace.data_ptr() + 255) // 256 * 256
-    avail = workspace.numel() - (ptr - workspace.data_ptr())
+    avail = workspace.numel() * workspace.element_size() - (ptr - workspace.data_ptr())
     return ctypes.c_void_p(ptr), avail, workspace
 
 

@@ -355,7 +355,9 @@ __global__ void invert_clear_info_kernel(const PrepLaunch pl, int count)
     if (i < count) *pl.it[i].info = 0;
 }
 
-// dst = src + damping * I (full copy); a non-finite element of the upper triangle sets info = -1.
+// dst = src + damping * I for the upper triangle (column >= row): only that is input, and nothing reads the
+// rest of the working copy before the inversion has written it (what a product reads and discards there, the
+// lower part of a diagonal block, may hold anything).  A non-finite element of the upper triangle sets info = -1.
 __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl)
 {
     const PrepItem &it = pl.it[blockIdx.y];
@@ -366,7 +368,7 @@ __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl
         const float *src = it.src + (size_t)r * it.lds_;
         float *dst = it.dst + (size_t)r * it.ldd;
         if (vec) {
-            for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+            for (int c = (r & ~3) + threadIdx.x * 4; c < d; c += blockDim.x * 4) {
                 float4 v;
                 if (c + 3 < d) {
                     v = *reinterpret_cast<const float4 *>(src + c);
@@ -376,7 +378,6 @@ __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl
                     v.z = (c + 2 < d) ? src[c + 2] : 0.f;
                     v.w = 0.f;
                 }
-                // only the upper triangle (column >= row) is input; what lies below it is copied but never used
                 if ((c + 0 >= r && !(fabsf(v.x) <= 3.0e38f)) || (c + 1 >= r && !(fabsf(v.y) <= 3.0e38f)) ||
                     (c + 2 >= r && !(fabsf(v.z) <= 3.0e38f)) || (c + 3 >= r && !(fabsf(v.w) <= 3.0e38f)))
                     bad = true;
@@ -389,7 +390,7 @@ __global__ __launch_bounds__(256) void invert_prepare_kernel(const PrepLaunch pl
                 *reinterpret_cast<float4 *>(dst + c) = v;  // ld of the working copy is a multiple of 32 >= d
             }
         } else {
-            for (int c = threadIdx.x; c < d; c += blockDim.x) {
+            for (int c = r + threadIdx.x; c < d; c += blockDim.x) {
                 float v = src[c];
                 if (c >= r && !(fabsf(v) <= 3.0e38f)) bad = true;
                 if (r == c) v += pl.damping;

@@ -253,6 +253,29 @@ def test_invert_batched_mixed_sizes(k, oracle):
         assert np.array_equal(single, host(inv))
 
 
+def test_invert_result_does_not_depend_on_what_the_workspace_holds(k, oracle):
+    """The working copy is only filled where the algorithm reads it: whatever else the caller's workspace holds
+    (zeros, NaNs, infinities, the remains of another call) must not change a single bit of the result."""
+    ds = [257, 513, 1024, 96, 640]
+    fs = [oracle.curvature(synth.activations(2, 3, i, 0, 2 * d + 8, d)).astype(np.float32) for i, d in enumerate(ds)]
+    fd = [dev(f) for f in fs]
+    need = k.kfac_invert_batched_workspace(fd, [torch.empty_like(f) for f in fd])
+    results = []
+    for fill in (0.0, float("nan"), float("inf"), -1.0e30):
+        ws = torch.full((need // 4 + 64,), fill, dtype=torch.float32, device="cuda")
+        invs = [torch.zeros(d, d, device="cuda") for d in ds]
+        infos = k.kfac_invert_batched(fd, 1e-3, invs, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.all(host(infos) == 0), fill
+        results.append([host(i) for i in invs])
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert np.array_equal(a, b)
+    for f, inv in zip(fs, results[0]):
+        want, _ = oracle.invert(f.astype(np.float64), 1e-3)
+        assert oracle.rel_fro(inv, want) <= 1e-4
+
+
 def test_invert_batch_larger_than_the_launch_descriptors(k, oracle):
     """90 matrices: more than the 72 one launch describes (the batch is run in slices), and in the first slice more
     row bands than one launch of the final product holds.  Every inverse must equal, bit for bit, what a call with
