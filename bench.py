@@ -24,7 +24,7 @@ PEAK_F32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
 PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 # HBM traffic of one curvature launch of the default workload, from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (None = not measured).
-CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 12.60e9  # profiles/curvature_syrk_pmc.txt: 11.51 GB fetched + 1.09 GB written
+CURVATURE_TRAFFIC_BYTES_PER_LAUNCH = 12.57e9  # profiles/curvature_syrk_pmc.txt: 11.48 GB fetched + 1.09 GB written
 
 
 def parse():
