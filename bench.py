@@ -45,6 +45,10 @@ def parse():
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="2: after the curvature, invert the small factors (and precondition the layers that only need "
                          "them) on one stream and the large factors on another (same results; default 1)")
+    ap.add_argument("--curvature", choices=["f32", "split_bf16"], default="f32",
+                    help="split_bf16: the float32 workloads' curvature as KFAC_F32_BF16X3 (every value as three bfloat16 "
+                         "terms, six bf16 MFMA products per product, fp32 accumulation) instead of the fp32 MFMA; the "
+                         "default line reports this variant's curvature time in its own block either way")
     ap.add_argument("--phase", choices=["all", "curvature", "inversion", "precondition"], default="all",
                     help="for profiling: after one full untimed step, time only this phase (prints a short JSON "
                          "line that is not the benchmark line)")
@@ -80,6 +84,11 @@ def main():
     cfg = synth.CONFIGS[args.config]
     bf16 = bool(cfg["bf16"])  # activations / errors in bfloat16 (the stress workload); everything else fp32
     in_dtype = binding.KFAC_BF16 if bf16 else binding.KFAC_F32
+    split = args.curvature == "split_bf16"
+    if split:
+        if bf16:
+            raise SystemExit("--curvature split_bf16 is a mode for the float32 workloads")
+        in_dtype = binding.KFAC_F32_BF16X3
     tokens, n_micro, blocks = cfg["tokens"], cfg["n_micro"], cfg["blocks"]
     damping = synth.DAMPING
     gen = torch.Generator(device=dev)
@@ -260,7 +269,9 @@ def main():
     b_inv = sum(2 * 4 * d * d for (di, do) in layers for d in (di, do))
     b_prec = sum(4 * (do * do + di * di + 2 * do * di) for (di, do) in layers)
     achieved = f_curv_launch / (launch_ms * 1e-3) / 1e12
-    peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_F32_MFMA_TFLOPS
+    peak = PEAK_BF16_MFMA_TFLOPS if (bf16 or split) else PEAK_F32_MFMA_TFLOPS
+    if split:
+        achieved *= 6.0  # six bf16 MFMA products per product of two float32 values; the pre-pass is part of the launch
 
     # what the matrix cores sustain on this chip with nothing else in the way (register-only MFMA loop)
     sink = torch.zeros(64, dtype=torch.float32, device=dev)
@@ -269,7 +280,7 @@ def main():
     for _ in range(4):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        check(lib.kfac_mfma_probe(in_dtype, 4000, ctypes.c_void_p(sink.data_ptr()),
+        check(lib.kfac_mfma_probe(binding.KFAC_BF16 if split else in_dtype, 4000, ctypes.c_void_p(sink.data_ptr()),
                                   ctypes.byref(probe_flops), sp))
         e1.record(stream)
         torch.cuda.synchronize()
@@ -287,7 +298,7 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if bf16 else "f32",
+        "dtype": "bf16" if bf16 else ("f32 as 3 x bf16" if split else "f32"),
         "data": "synthetic",
         "config": {
             "workload": "%s: %d blocks x %d linears, %d micro-batches x %d tokens, %s, damping %g"
@@ -317,19 +328,25 @@ def main():
             sum(2 * tokens * d * d for (di, do) in layers for d in (di, do)) * n_micro / (curv_ms * 1e-3) / 1e12, 2),
         "roofline": {
             "kernel": "%s (one launch = all %d factors of the stage for one micro-batch)"
-                      % ("curvature_syrk_bf16_256_rowmajor_kernel" if bf16 else "curvature_syrk_kernel", nfac),
+                      % ("curvature_syrk_bf16_256_rowmajor_kernel" if bf16 else
+                         ("split3_pack_kernel + curvature_syrk_split3_256_kernel, 6 bf16 products per fp32 product"
+                          if split else "curvature_syrk_kernel"), nfac),
             "bound": "mfma",
             "achieved": round(achieved, 2),
             "peak": peak,
             "unit": "TFLOP/s",
             "frac": round(achieved / peak, 4),
-            "traffic": CURVATURE_TRAFFIC_BYTES_PER_LAUNCH if args.config == 4 else None,
+            "traffic": CURVATURE_TRAFFIC_BYTES_PER_LAUNCH if (args.config == 4 and not split) else None,
             "measured_mfma_peak": round(measured_peak, 1),
             "frac_of_measured_peak": round(achieved / measured_peak, 4),
             "launch_ms": round(launch_ms, 4),
             "flops_per_launch": f_curv_launch,
         },
     }
+
+    if not bf16 and not split:
+        result["curvature_f32_as_3xbf16"] = split_curvature_variant(
+            torch, binding, lib, check, xs, facs, n_micro, alpha, sp, stream, curv_ms, inv_ms, prec_ms, f_curv)
 
     if args.streams == 2:
         # the two phases overlap: report their sum, and none of the blocks that need them separately
@@ -374,6 +391,52 @@ def main():
             result["cpu_baseline"] = cpu_baseline(cfg, xs, grads, layers, tokens, n_micro, damping,
                                                   f_curv, f_inv, f_prec)
     print(json.dumps(result))
+
+
+def split_curvature_variant(torch, binding, lib, check, xs, facs, n_micro, alpha, sp, stream, curv_ms, inv_ms, prec_ms, f_curv):
+    """The curvature of the same step computed as KFAC_F32_BF16X3 (float32 values as three bfloat16 terms on the
+    bf16 MFMA, pre-pass included), timed with HIP events, and how far its factors are from the fp32 MFMA path's."""
+    import ctypes
+
+    dt = binding.KFAC_F32_BF16X3
+    nfac = len(facs)
+    items = [binding._curv_items(xs[m], facs) for m in range(n_micro)]
+    need = lib.kfac_curvature_grouped_workspace(items[0], nfac, dt)
+    ws = torch.empty(need + 256, dtype=torch.uint8, device=facs[0].device)
+    wsp = ctypes.c_void_p((ws.data_ptr() + 255) // 256 * 256)
+    biggest = max(range(nfac), key=lambda i: facs[i].shape[0])
+    smallest = min(range(nfac), key=lambda i: facs[i].shape[0])
+    ref = [f.clone() for f in facs]  # what the timed steps left: the fp32 MFMA path's factors
+
+    def curvature():
+        for m in range(n_micro):
+            check(lib.kfac_curvature_grouped(items[m], nfac, dt, alpha, 0.0 if m == 0 else 1.0, wsp, need, sp))
+
+    curvature()
+    torch.cuda.synchronize()
+    reps = 3
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        curvature()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    diff = {i: float((facs[i].double() - ref[i].double()).norm() / ref[i].double().norm()) for i in (biggest, smallest)}
+    for f, r in zip(facs, ref):  # leave the buffers as the timed steps left them
+        f.copy_(r)
+    return {
+        "what": "curvature of the same step with --curvature split_bf16 (KFAC_F32_BF16X3): pre-pass + bf16 MFMA kernel, "
+                "fp32 accumulation; not part of `value`",
+        "curvature_ms": round(ms, 3),
+        "launch_ms": round(ms / n_micro, 4),
+        "speedup_over_fp32_mfma_curvature": round(curv_ms / ms, 3),
+        "step_ms_with_it": round(ms + inv_ms + prec_ms, 3),
+        "useful_tflops": round(f_curv / (ms * 1e-3) / 1e12, 2),
+        "bf16_mfma_tflops": round(6 * f_curv / (ms * 1e-3) / 1e12, 1),
+        "frac_of_bf16_mfma_peak": round(6 * f_curv / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
+        "rel_fro_difference_from_fp32_path": {"d=%d" % facs[i].shape[0]: float("%.3g" % diff[i]) for i in diff},
+    }
 
 
 def work_assignment(binding, lib, check, xs, facs, invs, infos, ws, wsp, ws_bytes, sp, in_dtype, alpha, damping, nlay,

@@ -56,7 +56,11 @@ typedef enum {
 
 typedef enum {
     KFAC_F32 = 0, /* float32 activations / errors */
-    KFAC_BF16 = 1 /* bfloat16 activations / errors, fp32 accumulation */
+    KFAC_BF16 = 1, /* bfloat16 activations / errors, fp32 accumulation */
+    /* float32 activations / errors, each value taken as the sum of three bfloat16 terms and each product as the
+     * six bf16 MFMA products that reach 2^-16 of it (the rest is below the rounding of one float32 operation),
+     * fp32 accumulation; curvature only.  Launches too small for this path are computed as KFAC_F32. */
+    KFAC_F32_BF16X3 = 2
 } kfac_dtype;
 
 /* ---------------------------------------------------------------- curvature

@@ -14,6 +14,7 @@ from . import build as _build
 KFAC_OK = 0
 KFAC_F32 = 0
 KFAC_BF16 = 1
+KFAC_F32_BF16X3 = 2
 
 _i64 = ctypes.c_int64
 _f32 = ctypes.c_float
@@ -107,9 +108,11 @@ def _stream(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def _dtype_code(t):
+def _dtype_code(t, split_bf16=False):
     if t.dtype == torch.float32:
-        return KFAC_F32
+        return KFAC_F32_BF16X3 if split_bf16 else KFAC_F32
+    if split_bf16:
+        raise KfacError("split_bf16 is a mode for float32 input (got %s)" % t.dtype)
     if t.dtype == torch.bfloat16:
         return KFAC_BF16
     raise KfacError("unsupported activation dtype %s" % t.dtype)
@@ -150,11 +153,13 @@ def _curv_items(xs, factors):
     return arr
 
 
-def kfac_curvature(x, factor, alpha, beta, workspace=None, stream=None):
-    """factor = beta * factor + alpha * x^T x  (one factor, one micro-batch)."""
+def kfac_curvature(x, factor, alpha, beta, workspace=None, stream=None, split_bf16=False):
+    """factor = beta * factor + alpha * x^T x  (one factor, one micro-batch).
+
+    split_bf16: float32 input computed as KFAC_F32_BF16X3 (three bfloat16 terms per value, bf16 MFMA)."""
     lib = load()
     _curv_items([x], [factor])
-    dt = _dtype_code(x)
+    dt = _dtype_code(x, split_bf16)
     need = lib.kfac_curvature_workspace(x.shape[0], x.shape[1], dt)
     ws, nbytes, keep = _workspace(need, x, workspace, stream)
     _check(lib.kfac_curvature(ctypes.c_void_p(x.data_ptr()), dt, x.shape[0], x.shape[1], x.stride(0),
@@ -163,16 +168,16 @@ def kfac_curvature(x, factor, alpha, beta, workspace=None, stream=None):
     return factor
 
 
-def kfac_curvature_grouped_workspace(xs, factors):
+def kfac_curvature_grouped_workspace(xs, factors, split_bf16=False):
     arr = _curv_items(xs, factors)
-    return int(load().kfac_curvature_grouped_workspace(arr, len(xs), _dtype_code(xs[0])))
+    return int(load().kfac_curvature_grouped_workspace(arr, len(xs), _dtype_code(xs[0], split_bf16)))
 
 
-def kfac_curvature_grouped(xs, factors, alpha, beta, workspace=None, stream=None):
+def kfac_curvature_grouped(xs, factors, alpha, beta, workspace=None, stream=None, split_bf16=False):
     """Many independent curvature items with a common alpha / beta."""
     lib = load()
     arr = _curv_items(xs, factors)
-    dt = _dtype_code(xs[0])
+    dt = _dtype_code(xs[0], split_bf16)
     need = lib.kfac_curvature_grouped_workspace(arr, len(xs), dt)
     ws, nbytes, keep = _workspace(need, xs[0], workspace, stream)
     _check(lib.kfac_curvature_grouped(arr, len(xs), dt, alpha, beta, ws, nbytes, _stream(stream)))

@@ -16,6 +16,7 @@
 
 #include "../../include/kfac.h"
 #include "bf16_syrk256.h"
+#include "split3_syrk256.h"
 #include "mfma_probe.h"
 #include "diag_block.h"
 #include "tn_gemm.h"
@@ -204,11 +205,11 @@ inline int choose_splits(int64_t tiles, int64_t K)
 struct CurvPlan {
     int splits;
     int64_t tiles;  // output tiles of all items
-    size_t pack;    // bytes of the repacked bf16 inputs (bf16 only), in front of the partial tiles
+    size_t pack;    // bytes of the repacked bf16 inputs (bf16, and float32 split into bf16 terms), in front of the partial tiles
     size_t ws;
 };
 
-inline int pack_groups(int64_t n) { return (int)align_up((size_t)((n + 7) / 8), BF_SLAB_GROUPS); }
+inline int pack_groups(int64_t n) { return (int)align_up((size_t)std::max<int64_t>(1, (n + 7) / 8), BF_SLAB_GROUPS); }
 inline int pack_cols(int64_t d) { return (int)align_up((size_t)d, B2_TILE); }
 inline size_t pack_bytes(int64_t n, int64_t d) { return align_up((size_t)pack_groups(n) * pack_cols(d) * 16, WS_ALIGN); }
 
@@ -227,6 +228,8 @@ bool curvature_plan(const kfac_curvature_item *items, int64_t count, kfac_dtype 
     pl.pack = 0;
     if (dtype == KFAC_BF16)
         for (int64_t i = 0; i < count; ++i) pl.pack += pack_bytes(items[i].n_tokens, items[i].d);
+    if (dtype == KFAC_F32_BF16X3)
+        for (int64_t i = 0; i < count; ++i) pl.pack += S3_PLANES * pack_bytes(items[i].n_tokens, items[i].d);
     pl.ws = pl.pack + (pl.splits > 1 ? align_up((size_t)tiles * pl.splits * BM * BN * sizeof(float), WS_ALIGN) : 0);
     return true;
 }
@@ -568,7 +571,7 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
 {
     if (count == 0) return KFAC_OK;
     if (items == nullptr || count < 0) return KFAC_ERR_ARG;
-    if (dtype != KFAC_F32 && dtype != KFAC_BF16) return KFAC_ERR_ARG;
+    if (dtype != KFAC_F32 && dtype != KFAC_BF16 && dtype != KFAC_F32_BF16X3) return KFAC_ERR_ARG;
     for (int64_t i = 0; i < count; ++i) {
         const kfac_curvature_item &it = items[i];
         if (it.x == nullptr || it.factor == nullptr) return KFAC_ERR_ARG;
@@ -577,7 +580,7 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         if ((reinterpret_cast<uintptr_t>(it.x) & (dtype == KFAC_BF16 ? 1 : 3)) || (reinterpret_cast<uintptr_t>(it.factor) & 3))
             return KFAC_ERR_ARG;
     }
-    if (dtype == KFAC_BF16)
+    if (dtype != KFAC_F32)
         for (int64_t i = 0; i < count; ++i)
             if (items[i].d > (1 << 26)) return KFAC_ERR_UNSUPPORTED;  // packed rows are addressed with 32-bit byte offsets
     CurvPlan pl;
@@ -595,6 +598,49 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         std::memset(&lp, 0, sizeof(lp));
         PackLaunch pk;
         if (dtype == KFAC_BF16) std::memset(&pk, 0, sizeof(pk));
+        int tiles256_f32 = 0;
+        if (dtype == KFAC_F32_BF16X3)
+            for (int64_t i = 0; i < n; ++i) tiles256_f32 += b2_tiles((int)items[done + i].d);
+        if (dtype == KFAC_F32_BF16X3 && tiles256_f32 >= 192) {
+            // float32 input as three bfloat16 terms on the bf16 MFMA (split3_syrk256.h); launches too small to
+            // occupy the chip with 256 x 256 tiles take the fp32 path below
+            Split3Launch sp;
+            Syrk256Launch l2;
+            std::memset(&sp, 0, sizeof(sp));
+            std::memset(&l2, 0, sizeof(l2));
+            int tb = 0, gm = 0, cm = 0;
+            for (int64_t i = 0; i < n; ++i) {
+                const kfac_curvature_item &it = items[done + i];
+                Split3Item &si = sp.it[i];
+                si.x = static_cast<const float *>(it.x);
+                si.dst = reinterpret_cast<unsigned short *>(pack);
+                si.n = (int)it.n_tokens;
+                si.d = (int)it.d;
+                si.ldx = (int)it.ldx;
+                si.dp = pack_cols(it.d);
+                si.gp = pack_groups(it.n_tokens);
+                SyrkProblem &q = l2.p[i];
+                q.x = pack;
+                q.factor = it.factor;
+                q.n = si.gp * BF_KG;
+                q.d = si.d;
+                q.ldx = si.dp;
+                q.ldf = (int)it.ldf;
+                q.tile_begin = tb;
+                tb += b2_tiles(si.d);
+                pack += S3_PLANES * pack_bytes(it.n_tokens, it.d);
+                gm = std::max(gm, si.gp);
+                cm = std::max(cm, si.dp);
+            }
+            l2.count = (int)n;
+            l2.alpha = alpha;
+            l2.beta = beta;
+            hipLaunchKernelGGL(split3_pack_kernel, dim3((cm + S3P_COLS - 1) / S3P_COLS, (gm + S3P_GROUPS - 1) / S3P_GROUPS, (unsigned)n), dim3(256), 0, st, sp);
+            hipLaunchKernelGGL(curvature_syrk_split3_256_kernel, dim3(tb), dim3(256), 0, st, l2);
+            if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
+            done += n;
+            continue;
+        }
         int tiles = 0, gmax = 0, cmax = 0;
         for (int64_t i = 0; i < n; ++i) {
             const kfac_curvature_item &it = items[done + i];

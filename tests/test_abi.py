@@ -89,6 +89,22 @@ def test_bf16_is_reported_unsupported_or_supported_consistently():
     assert st == 1  # null factor is an argument error whatever the dtype
 
 
+def test_split_bf16_dtype_workspace_and_header_value():
+    """KFAC_F32_BF16X3: the header's value is the binding's; its workspace holds three packed bfloat16 planes
+    (2 bytes per element each, padded to 32 tokens and 256 columns), i.e. three times what KFAC_BF16 needs."""
+    lib = binding.load()
+    header = open(os.path.join(ROOT, "include", "kfac.h")).read()
+    assert "KFAC_F32_BF16X3 = %d" % binding.KFAC_F32_BF16X3 in header
+    for n, d in [(4096, 4096), (600, 5000), (1, 3584)]:
+        need = lib.kfac_curvature_workspace(n, d, binding.KFAC_F32_BF16X3)
+        plane = -(-n // 32) * 32 * (-(-d // 256) * 256) * 2
+        assert need >= 3 * plane
+        assert need == 3 * lib.kfac_curvature_workspace(n, d, binding.KFAC_BF16)
+    dummy = ctypes.c_void_p(0x1000)
+    assert lib.kfac_curvature(dummy, 3, 64, 64, 64, 1.0, 0.0, dummy, 64, None, 0, None) == 1
+    assert lib.kfac_curvature(dummy, binding.KFAC_F32_BF16X3, 64, 4096, 4096, 1.0, 0.0, dummy, 4096, None, 0, None) == 3
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2211_14133_amd")
     for dirpath, _, files in os.walk(pkg):

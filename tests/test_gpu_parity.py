@@ -840,3 +840,76 @@ def test_stage_wise_errors_at_block_shapes(k, oracle):
               % (name, e_ai, cond, e_bi, e_p, cancel), flush=True)
         assert e_ai <= 2e-6 * cond + 1e-6 and e_bi <= 1e-5
         assert e_p <= 1e-6 * cancel + 1e-6  # two fp32 products with chunked accumulation: a few ulp of the terms
+
+
+# ---------------------------------------------- float32 input as three bfloat16 terms (KFAC_F32_BF16X3)
+
+SPLIT_FACTOR_TOL = 6e-7  # measured 3.3e-7 at 4096 tokens; the fp32 path is held to 5e-7
+
+
+@pytest.mark.parametrize("n,d", [(4096, 4096), (600, 5000), (77, 3600), (1, 3584), (4100, 3585)])
+def test_curvature_split_bf16_parity(k, oracle, n, d):
+    """Two factors with enough 256 x 256 tiles between them for the bf16-MFMA kernel (d >= 3584: 2 x 105),
+    ragged sizes, a row pitch larger than d, GELU inputs for the second."""
+    print("split curvature n=%d d=%d" % (n, d), flush=True)
+    xs = [synth.activations(6, 0, i, 0, n, d, gelu=(i == 1)) for i in range(2)]
+    bufs = [torch.zeros(n, d + 12, device="cuda") for _ in xs]
+    for b, x in zip(bufs, xs):
+        b[:, :d] = dev(x)
+    fs = [torch.full((d, d), 7.0, device="cuda") for _ in xs]
+    k.kfac_curvature_grouped([b[:, :d] for b in bufs], fs, 1.0 / n, 0.0, split_bf16=True)
+    for x, f in zip(xs, fs):
+        err = oracle.rel_fro(host(f), oracle.curvature(x))
+        print("  rel_fro %.3g" % err, flush=True)
+        assert err <= FACTOR_TOL and err <= SPLIT_FACTOR_TOL
+        assert np.array_equal(host(f), host(f).T)
+
+
+def test_curvature_split_bf16_accumulates_and_has_no_bias(k, oracle):
+    """Two micro-batches (beta = 0, then 1) at the BERT-Large sizes; the diagonal (a sum of squares, where a
+    matrix core that cuts off low bits would show) must not be systematically low."""
+    n, d, cnt = 4096, 1024, 24  # 24 x 10 = 240 tiles
+    xs = [[synth.activations(6, 1, i, m, n, d) for i in range(cnt)] for m in range(2)]
+    fs = [torch.empty(d, d, device="cuda") for _ in range(cnt)]
+    for m in range(2):
+        k.kfac_curvature_grouped([dev(x) for x in xs[m]], fs, 1.0 / (2 * n), float(m), split_bf16=True)
+    bias = []
+    for i in (0, 7, 23):
+        want = oracle.curvature([xs[0][i], xs[1][i]])
+        got = host(fs[i])
+        err = oracle.rel_fro(got, want)
+        bias.append(float(np.mean((np.diag(got).astype(np.float64) - np.diag(want)) / np.diag(want))))
+        print("  factor %d rel_fro %.3g diagonal bias %.3g" % (i, err, bias[-1]), flush=True)
+        assert err <= SPLIT_FACTOR_TOL
+        assert np.array_equal(got, got.T)
+    assert max(abs(b) for b in bias) <= 2e-7
+
+
+def test_curvature_split_bf16_small_launch_takes_the_fp32_path(k, oracle):
+    """Launches with too few 256 x 256 tiles are computed exactly as KFAC_F32: same bits."""
+    n, d = 300, 200
+    x = dev(synth.activations(6, 2, 0, 0, n, d))
+    f1, f2 = torch.empty(d, d, device="cuda"), torch.empty(d, d, device="cuda")
+    k.kfac_curvature(x, f1, 1.0 / n, 0.0, split_bf16=True)
+    k.kfac_curvature(x, f2, 1.0 / n, 0.0)
+    assert torch.equal(f1, f2)
+    with pytest.raises(k.KfacError):
+        k.kfac_curvature(x.to(torch.bfloat16), f1, 1.0 / n, 0.0, split_bf16=True)
+
+
+def test_curvature_split_bf16_exact_cases_and_determinism(k):
+    """Values that are exact in bfloat16 give the exact factor (the m and l planes are zero); two runs agree
+    bit for bit."""
+    n, d = 512, 3840
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    x = torch.randint(-3, 4, (n, d), device="cuda", generator=g).float()
+    fs = [torch.empty(d, d, device="cuda") for _ in range(2)]
+    k.kfac_curvature_grouped([x, x], fs, 1.0, 0.0, split_bf16=True)
+    want = x.double().t() @ x.double()
+    assert torch.equal(fs[0].double(), want) and torch.equal(fs[0], fs[1])
+    y = torch.randn(n, d, device="cuda", generator=g)
+    f3, f4 = torch.empty(d, d, device="cuda"), torch.empty(d, d, device="cuda")
+    k.kfac_curvature_grouped([y, x], [f3, fs[0]], 0.5, 0.0, split_bf16=True)
+    k.kfac_curvature_grouped([y, x], [f4, fs[1]], 0.5, 0.0, split_bf16=True)
+    assert torch.equal(f3, f4)
