@@ -608,7 +608,8 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
             Syrk256Launch l2;
             std::memset(&sp, 0, sizeof(sp));
             std::memset(&l2, 0, sizeof(l2));
-            int tb = 0, gm = 0, cm = 0;
+            int tb = 0;
+            int64_t wgs = 0;
             for (int64_t i = 0; i < n; ++i) {
                 const kfac_curvature_item &it = items[done + i];
                 Split3Item &si = sp.it[i];
@@ -629,13 +630,16 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
                 q.tile_begin = tb;
                 tb += b2_tiles(si.d);
                 pack += S3_PLANES * pack_bytes(it.n_tokens, it.d);
-                gm = std::max(gm, si.gp);
-                cm = std::max(cm, si.dp);
+                sp.first_wg[i] = (int)wgs;
+                wgs += (int64_t)(si.dp / S3P_COLS) * (si.gp / S3P_GROUPS);
+                if (wgs > INT32_MAX) return KFAC_ERR_UNSUPPORTED;  // more workgroups than a grid holds
             }
+            sp.first_wg[n] = (int)wgs;
+            sp.count = (int)n;
             l2.count = (int)n;
             l2.alpha = alpha;
             l2.beta = beta;
-            hipLaunchKernelGGL(split3_pack_kernel, dim3((cm + S3P_COLS - 1) / S3P_COLS, (gm + S3P_GROUPS - 1) / S3P_GROUPS, (unsigned)n), dim3(256), 0, st, sp);
+            hipLaunchKernelGGL(split3_pack_kernel, dim3((unsigned)wgs), dim3(256), 0, st, sp);
             hipLaunchKernelGGL(curvature_syrk_split3_256_kernel, dim3(tb), dim3(256), 0, st, l2);
             if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
             done += n;

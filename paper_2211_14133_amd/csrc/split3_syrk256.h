@@ -33,13 +33,15 @@ struct Split3Item {
 };
 struct Split3Launch {
     Split3Item it[PACK_MAX_ITEMS];
+    int first_wg[PACK_MAX_ITEMS + 1];  // workgroups of item i: first_wg[i] .. first_wg[i+1]-1 (column blocks of 256 x k-groups)
+    int count;
 };
 
-// One thread takes one column of two k-groups (16 tokens): sixteen 4-byte reads (a wave reads 256-byte runs
-// of a token row), the split in registers, and per plane and k-group the eight tokens as one 16-byte packed
-// write (a wave writes 1 KB runs): no LDS, every request of a thread in flight at once.
+// One thread takes one column of a k-group (8 tokens): eight 4-byte reads (a wave reads 256-byte runs of a
+// token row), the split in registers, and per plane the eight tokens as one 16-byte packed write (a wave
+// writes 1 KB runs): no LDS, every request of a thread in flight at once.
 constexpr int S3P_COLS = 256;  // columns per workgroup: one per thread
-constexpr int S3P_GROUPS = 2;  // k-groups per workgroup
+constexpr int S3P_GROUPS = 1;  // k-groups per workgroup (measured on the BERT-Large stage: 1: 1.1 ms, 2: 1.28, 4: 1.35)
 
 __device__ inline unsigned s3_bf16_bits(float v)
 {
@@ -52,9 +54,17 @@ __device__ inline float s3_bf16_value(unsigned b)
 
 __global__ __launch_bounds__(256) void split3_pack_kernel(const Split3Launch pl)
 {
-    const Split3Item &it = pl.it[blockIdx.z];
-    const int col = blockIdx.x * S3P_COLS + threadIdx.x, g0 = blockIdx.y * S3P_GROUPS;
-    if (col >= it.dp || g0 >= it.gp) return;  // gp is a multiple of 4: both k-groups exist
+    int i = 0, hi = pl.count;
+    while (hi - i > 1) {
+        const int mid = (i + hi) >> 1;
+        if (pl.first_wg[mid] <= (int)blockIdx.x)
+            i = mid;
+        else
+            hi = mid;
+    }
+    const Split3Item &it = pl.it[i];
+    const int w = blockIdx.x - pl.first_wg[i], cb = it.dp / S3P_COLS;  // column blocks vary fastest
+    const int col = (w % cb) * S3P_COLS + threadIdx.x, g0 = (w / cb) * S3P_GROUPS;
     constexpr int ROWS = S3P_GROUPS * BF_KG;
     float v[ROWS];
     const float *src = it.x + (size_t)g0 * BF_KG * it.ldx + col;
