@@ -913,3 +913,33 @@ def test_curvature_split_bf16_exact_cases_and_determinism(k):
     k.kfac_curvature_grouped([y, x], [f3, fs[0]], 0.5, 0.0, split_bf16=True)
     k.kfac_curvature_grouped([y, x], [f4, fs[1]], 0.5, 0.0, split_bf16=True)
     assert torch.equal(f3, f4)
+
+
+def test_chain_config3_feed_forward_layers_with_split_bf16_curvature(k, oracle):
+    """The worst-conditioned factors of the configurations (FFN2's A: d = tokens = 4096, GELU inputs, smallest
+    eigenvalue about the damping) built by the bf16-MFMA path, then inverted and applied: the preconditioned
+    gradient stays inside its tolerance."""
+    c = synth.CONFIGS[3]
+    n = c["tokens"]
+    lay = [(li, l) for li, l in enumerate(c["layers"]) if l[0] in ("ffn1", "ffn2")]
+    assert len(lay) == 2
+    xs, es, gs = [], [], []
+    for li, (name, d_in, d_out, gelu) in lay:
+        xs.append(synth.activations(3, 0, li, 0, n, d_in, gelu=gelu))
+        es.append(synth.errors(3, 0, li, 0, n, d_out))
+        gs.append(synth.weight_gradient([es[-1]], [xs[-1]]))
+    ins = [dev(x) for x in xs] + [dev(e) for e in es]
+    facs = [torch.empty(t.shape[1], t.shape[1], device="cuda") for t in ins]
+    k.kfac_curvature_grouped(ins, facs, 1.0 / n, 0.0, split_bf16=True)
+    invs = [torch.empty_like(f) for f in facs]
+    infos = k.kfac_invert_batched(facs, synth.DAMPING, invs)
+    assert int(infos.abs().max()) == 0
+    for i, (li, (name, d_in, d_out, gelu)) in enumerate(lay):
+        p = torch.empty(d_out, d_in, device="cuda")
+        k.kfac_precondition(invs[2 + i], invs[i], dev(gs[i]), p)
+        oa, ob, oai, obi, op = oracle.kfac_chain([xs[i]], [es[i]], gs[i], synth.DAMPING)
+        ea, eb = oracle.rel_fro(host(facs[i]), oa), oracle.rel_fro(host(facs[2 + i]), ob)
+        eai, ep = oracle.rel_fro(host(invs[i]), oai), oracle.rel_fro(host(p), op)
+        print("cfg 3 %-5s split curvature: A %.2e B %.2e A^-1 %.2e P %.2e" % (name, ea, eb, eai, ep), flush=True)
+        assert ea <= SPLIT_FACTOR_TOL and eb <= SPLIT_FACTOR_TOL
+        assert ep <= PRECOND_TOL
