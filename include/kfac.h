@@ -79,7 +79,10 @@ typedef enum {
  * added up, so the rounding error does not grow with n_tokens (float32 input;
  * the bfloat16 variant keeps one fp32 accumulation level per call).
  * bfloat16 input is first repacked into the workspace (its size is part of
- * what the workspace query returns).  Limits: sizes must fit in 31 bits;
+ * what the workspace query returns).  KFAC_F32_BF16X3 takes float32 input,
+ * writes its three bfloat16 terms into the workspace (6 bytes per element) and
+ * accumulates the six bf16 MFMA products of every product in fp32, the five
+ * small ones before the large one; non-finite inputs give NaN.  Limits: sizes must fit in 31 bits;
  * d <= 2^26 for bfloat16 input (KFAC_ERR_UNSUPPORTED beyond).
  */
 kfac_status kfac_curvature(const void *x, kfac_dtype dtype, int64_t n_tokens, int64_t d, int64_t ldx,
