@@ -113,6 +113,102 @@ __device__ inline void b2_store(const floatx16 (&acc)[4][4], const SyrkProblem &
         }
 }
 
+// The same epilogue with the reads batched: when the call accumulates, the old values of eight
+// 32 x 32 blocks (128 registers: the operand registers of the K loop are free by now) are all requested
+// before the first is used: two memory latencies per tile instead of one per element (the launches that
+// accumulate over micro-batches are the common case here).  One instance per block, written out: as loops
+// the sixteen blocks exceed what the compiler unrolls, and the accumulators would leave the registers.
+struct B2Out {
+    float *C;
+    size_t ldf;
+    int d, mw, nw;  // first row / column of the wave's quarter, plus the lane's share (4 lh, li)
+    float alpha, beta;
+    bool diag, vec_t;
+};
+
+template <int BI, int BJ>
+__device__ __forceinline__ void b2_load_block(float (&old)[16], const B2Out &o)
+{
+    const int n = o.nw + 32 * BJ, mb = o.mw + 32 * BI;
+    const bool accumulate = o.beta != 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int m = mb + 8 * (r >> 2) + (r & 3);
+        old[r] = 0.f;
+        if (accumulate && m < o.d && n < o.d && (!o.diag || n <= m)) old[r] = o.C[(size_t)m * o.ldf + n];
+    }
+}
+
+template <int BI, int BJ>
+__device__ __forceinline__ void b2_store_block(const floatx16 &acc, const float (&old)[16], const B2Out &o)
+{
+    const int d = o.d;
+    const int n = o.nw + 32 * BJ, mb = o.mw + 32 * BI;
+    float *__restrict__ C = o.C;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int mq = mb + 8 * q;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int m = mq + e;
+            v[e] = o.alpha * acc[4 * q + e] + o.beta * old[4 * q + e];
+            if (m < d && n < d && (!o.diag || n <= m)) C[(size_t)m * o.ldf + n] = v[e];
+        }
+        // mirror: four consecutive rows of C are four consecutive columns of the transposed tile
+        if (n < d) {
+            if (!o.diag && mq + 3 < d && o.vec_t) {
+                *reinterpret_cast<float4 *>(C + (size_t)n * o.ldf + mq) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int m = mq + e;
+                    if (m < d && (!o.diag || n < m)) C[(size_t)n * o.ldf + m] = v[e];
+                }
+            }
+        }
+    }
+}
+
+template <int B0>
+__device__ __forceinline__ void b2_store_half(const floatx16 (&acc)[4][4], const B2Out &o)
+{
+    float old[8][16];
+#define B2_LOAD2(k, bi)                                \
+    b2_load_block<bi, 0>(old[4 * (k) + 0], o);         \
+    b2_load_block<bi, 1>(old[4 * (k) + 1], o);         \
+    b2_load_block<bi, 2>(old[4 * (k) + 2], o);         \
+    b2_load_block<bi, 3>(old[4 * (k) + 3], o)
+#define B2_STORE2(k, bi)                                           \
+    b2_store_block<bi, 0>(acc[bi][0], old[4 * (k) + 0], o);        \
+    b2_store_block<bi, 1>(acc[bi][1], old[4 * (k) + 1], o);        \
+    b2_store_block<bi, 2>(acc[bi][2], old[4 * (k) + 2], o);        \
+    b2_store_block<bi, 3>(acc[bi][3], old[4 * (k) + 3], o)
+    B2_LOAD2(0, B0);
+    B2_LOAD2(1, B0 + 1);
+    B2_STORE2(0, B0);
+    B2_STORE2(1, B0 + 1);
+#undef B2_LOAD2
+#undef B2_STORE2
+}
+
+__device__ __forceinline__ void b2_store_batched(const floatx16 (&acc)[4][4], const SyrkProblem &pr, float alpha, float beta,
+                                         int m0, int n0, int wm, int wn, int li, int lh, bool diag)
+{
+    B2Out o;
+    o.C = pr.factor;
+    o.ldf = (size_t)pr.ldf;
+    o.d = pr.d;
+    o.mw = m0 + wm + 4 * lh;
+    o.nw = n0 + wn + li;
+    o.alpha = alpha;
+    o.beta = beta;
+    o.diag = diag;
+    o.vec_t = ((pr.ldf & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.factor) & 15) == 0);
+    b2_store_half<0>(acc, o);
+    b2_store_half<2>(acc, o);
+}
+
 __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const Syrk256Launch lp)
 {
     __shared__ __attribute__((aligned(16))) char lds_a[B2_STAGES * B2_STAGE_BYTES];
@@ -267,7 +363,10 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_kernel(const S
 #undef B2_PIN
 #undef B2_ITER
 
-    b2_store(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
+    if (lp.beta == 0.f)
+        b2_store(acc, pr, lp.alpha, 0.f, m0, n0, wm, wn, li, lh, bt.diag);
+    else
+        b2_store_batched(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
 }
 
 // ---------------------------------------------------------------------------
@@ -451,7 +550,10 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_rowmajor_kerne
 #undef R2_PIN
 #undef R2_ITER
 
-    b2_store(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
+    if (lp.beta == 0.f)
+        b2_store(acc, pr, lp.alpha, 0.f, m0, n0, wm, wn, li, lh, bt.diag);
+    else
+        b2_store_batched(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
 }
 
 }  // namespace kfac

@@ -98,102 +98,6 @@ __global__ __launch_bounds__(256) void split3_pack_kernel(const Split3Launch pl)
     }
 }
 
-// Epilogue of a wave's 128 x 128 quarter, as b2_store, but when the call accumulates the old values of eight
-// 32 x 32 blocks (128 registers: the operand registers of the K loop are free by now) are all requested
-// before the first is used: two memory latencies per tile instead of one per element (the launches that
-// accumulate over micro-batches are the common case here).  One instance per block, written out: as loops
-// the sixteen blocks exceed what the compiler unrolls, and the accumulators would leave the registers.
-struct S3Out {
-    float *C;
-    size_t ldf;
-    int d, mw, nw;  // first row / column of the wave's quarter, plus the lane's share (4 lh, li)
-    float alpha, beta;
-    bool diag, vec_t;
-};
-
-template <int BI, int BJ>
-__device__ __forceinline__ void s3_load_block(float (&old)[16], const S3Out &o)
-{
-    const int n = o.nw + 32 * BJ, mb = o.mw + 32 * BI;
-    const bool accumulate = o.beta != 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int m = mb + 8 * (r >> 2) + (r & 3);
-        old[r] = 0.f;
-        if (accumulate && m < o.d && n < o.d && (!o.diag || n <= m)) old[r] = o.C[(size_t)m * o.ldf + n];
-    }
-}
-
-template <int BI, int BJ>
-__device__ __forceinline__ void s3_store_block(const floatx16 &acc, const float (&old)[16], const S3Out &o)
-{
-    const int d = o.d;
-    const int n = o.nw + 32 * BJ, mb = o.mw + 32 * BI;
-    float *__restrict__ C = o.C;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int mq = mb + 8 * q;
-        float v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int m = mq + e;
-            v[e] = o.alpha * acc[4 * q + e] + o.beta * old[4 * q + e];
-            if (m < d && n < d && (!o.diag || n <= m)) C[(size_t)m * o.ldf + n] = v[e];
-        }
-        // mirror: four consecutive rows of C are four consecutive columns of the transposed tile
-        if (n < d) {
-            if (!o.diag && mq + 3 < d && o.vec_t) {
-                *reinterpret_cast<float4 *>(C + (size_t)n * o.ldf + mq) = make_float4(v[0], v[1], v[2], v[3]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int m = mq + e;
-                    if (m < d && (!o.diag || n < m)) C[(size_t)n * o.ldf + m] = v[e];
-                }
-            }
-        }
-    }
-}
-
-template <int B0>
-__device__ __forceinline__ void s3_store_half(const floatx16 (&acc)[4][4], const S3Out &o)
-{
-    float old[8][16];
-#define S3_LOAD2(k, bi)                                \
-    s3_load_block<bi, 0>(old[4 * (k) + 0], o);         \
-    s3_load_block<bi, 1>(old[4 * (k) + 1], o);         \
-    s3_load_block<bi, 2>(old[4 * (k) + 2], o);         \
-    s3_load_block<bi, 3>(old[4 * (k) + 3], o)
-#define S3_STORE2(k, bi)                                           \
-    s3_store_block<bi, 0>(acc[bi][0], old[4 * (k) + 0], o);        \
-    s3_store_block<bi, 1>(acc[bi][1], old[4 * (k) + 1], o);        \
-    s3_store_block<bi, 2>(acc[bi][2], old[4 * (k) + 2], o);        \
-    s3_store_block<bi, 3>(acc[bi][3], old[4 * (k) + 3], o)
-    S3_LOAD2(0, B0);
-    S3_LOAD2(1, B0 + 1);
-    S3_STORE2(0, B0);
-    S3_STORE2(1, B0 + 1);
-#undef S3_LOAD2
-#undef S3_STORE2
-}
-
-__device__ __forceinline__ void s3_store(const floatx16 (&acc)[4][4], const SyrkProblem &pr, float alpha, float beta,
-                                         int m0, int n0, int wm, int wn, int li, int lh, bool diag)
-{
-    S3Out o;
-    o.C = pr.factor;
-    o.ldf = (size_t)pr.ldf;
-    o.d = pr.d;
-    o.mw = m0 + wm + 4 * lh;
-    o.nw = n0 + wn + li;
-    o.alpha = alpha;
-    o.beta = beta;
-    o.diag = diag;
-    o.vec_t = ((pr.ldf & 3) == 0) && ((reinterpret_cast<uintptr_t>(pr.factor) & 15) == 0);
-    s3_store_half<0>(acc, o);
-    s3_store_half<2>(acc, o);
-}
-
 // ---------------------------------------------------------------------------
 // The MFMA kernel.  Descriptor as for the bf16 kernels: x = the three planes, n = padded tokens,
 // ldx = padded columns.
@@ -588,7 +492,7 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_split3_256_kernel(const
         return;
     }
     s3_mainloop<false>(pr, m0, n0, lds_a, lds_b, acc);
-    s3_store(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
+    b2_store_batched(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
 }
 
 }  // namespace kfac
