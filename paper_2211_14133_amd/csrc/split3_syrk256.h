@@ -120,12 +120,17 @@ __global__ __launch_bounds__(256) void split3_pack_kernel(const Split3Launch pl)
 // a body reads only the slot of stage s+1; of the other two slots one receives stage s+2 (requested one body
 // earlier) and one, free since the barrier, stage s+3: two bodies of memory latency are covered.
 //
-// IDLE: the wave takes part in the loads and barriers of the tile but computes nothing (the upper right
-// quarter of a diagonal tile is only stored as the mirror of the lower left one).
-template <bool IDLE>
+// What a wave computes of its 128 x 128 quarter.  On a diagonal tile the upper right quarter is only stored as
+// the mirror of the lower left one: its wave takes part in the loads and barriers and computes nothing; the two
+// quarters on the diagonal leave out their six 32 x 32 blocks above the diagonal (the chip is power-limited
+// under this kernel: MFMAs that are not issued let the others run at a higher clock).
+enum S3WaveMode : int { S3_WAVE_FULL = 0, S3_WAVE_IDLE = 1, S3_WAVE_LOWER = 2 };
+
+template <int MODE>
 __device__ __forceinline__ void s3_pass_small(const SyrkProblem &pr, int m0, int n0, const char *lds_a, const char *lds_b,
                                               floatx16 (&acc)[4][4])
 {
+    constexpr bool IDLE = MODE == S3_WAVE_IDLE, LOWER = MODE == S3_WAVE_LOWER;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lh = lane >> 5;
@@ -182,7 +187,7 @@ __device__ __forceinline__ void s3_pass_small(const SyrkProblem &pr, int m0, int
     } while (0)
 #define S3_M4(fa, fb, bi)                                                                                      \
     do {                                                                                                       \
-        if (!IDLE) _Pragma("unroll") for (int bj = 0; bj < 4; ++bj)                                            \
+        if (!IDLE) _Pragma("unroll") for (int bj = 0; bj < (LOWER ? (bi) + 1 : 4); ++bj)                       \
             acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                             \
                 __builtin_bit_cast(bf16x8, fa[bi]), __builtin_bit_cast(bf16x8, fb[bj]), acc[bi][bj], 0, 0, 0); \
     } while (0)
@@ -324,10 +329,11 @@ __device__ __forceinline__ void s3_pass_small(const SyrkProblem &pr, int m0, int
 
 // Pass 2: acc += h^T h over the h plane, the K loop of curvature_syrk_bf16_256_kernel (slabs of 32 tokens,
 // 16 KB per operand, in a 4-stage ring; the caller has made sure nothing of pass 1 is still using LDS).
-template <bool IDLE>
+template <int MODE>
 __device__ __forceinline__ void s3_pass_large(const SyrkProblem &pr, int m0, int n0, const char *lds_a, const char *lds_b,
                                               floatx16 (&acc)[4][4])
 {
+    constexpr bool IDLE = MODE == S3_WAVE_IDLE, LOWER = MODE == S3_WAVE_LOWER;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lh = lane >> 5;
@@ -375,7 +381,7 @@ __device__ __forceinline__ void s3_pass_large(const SyrkProblem &pr, int m0, int
     } while (0)
 #define H2_MG(set, bi)                                                                                         \
     do {                                                                                                       \
-        if (!IDLE) _Pragma("unroll") for (int bj = 0; bj < 4; ++bj)                                            \
+        if (!IDLE) _Pragma("unroll") for (int bj = 0; bj < (LOWER ? (bi) + 1 : 4); ++bj)                       \
             acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                             \
                 __builtin_bit_cast(bf16x8, fa[set][bi]), __builtin_bit_cast(bf16x8, fb[set][bj]),              \
                 acc[bi][bj], 0, 0, 0);                                                                         \
@@ -455,13 +461,13 @@ __device__ __forceinline__ void s3_pass_large(const SyrkProblem &pr, int m0, int
 #undef H2_ITER
 }
 
-template <bool IDLE>
+template <int MODE>
 __device__ __forceinline__ void s3_mainloop(const SyrkProblem &pr, int m0, int n0, const char *lds_a, const char *lds_b,
                                             floatx16 (&acc)[4][4])
 {
-    s3_pass_small<IDLE>(pr, m0, n0, lds_a, lds_b, acc);
+    s3_pass_small<MODE>(pr, m0, n0, lds_a, lds_b, acc);
     __syncthreads();  // every wave has read its last fragments of pass 1 (and waited for its own loads)
-    s3_pass_large<IDLE>(pr, m0, n0, lds_a, lds_b, acc);
+    s3_pass_large<MODE>(pr, m0, n0, lds_a, lds_b, acc);
 }
 
 __global__ __launch_bounds__(256, 1) void curvature_syrk_split3_256_kernel(const Syrk256Launch lp)
@@ -487,11 +493,15 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_split3_256_kernel(const
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    if (bt.diag && __builtin_amdgcn_readfirstlane(wave) == 1) {
-        s3_mainloop<true>(pr, m0, n0, lds_a, lds_b, acc);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    if (bt.diag && wave_s == 1) {
+        s3_mainloop<S3_WAVE_IDLE>(pr, m0, n0, lds_a, lds_b, acc);
         return;
     }
-    s3_mainloop<false>(pr, m0, n0, lds_a, lds_b, acc);
+    if (bt.diag && wave_s != 2)
+        s3_mainloop<S3_WAVE_LOWER>(pr, m0, n0, lds_a, lds_b, acc);
+    else
+        s3_mainloop<S3_WAVE_FULL>(pr, m0, n0, lds_a, lds_b, acc);
     b2_store_batched(acc, pr, lp.alpha, lp.beta, m0, n0, wm, wn, li, lh, bt.diag);
 }
 
