@@ -3,8 +3,8 @@
 // the 24 bits of a float32), and a product of two values as the six bf16 products that reach 2^-16 of it,
 //     x y  ~=  h h' + (h m' + m h') + (m m' + h l' + l h'),
 // what is left out (m l', l m', l l') being below 2^-24 |x y|, the rounding of one float32 operation.  All six
-// accumulate in float32 in the MFMA accumulator.  The bf16 MFMA has 16 times the rate of the fp32 one, so six
-// of its products cost 3/8 of one fp32 product.
+// accumulate in float32 in the MFMA accumulators (the five small ones first, see the kernel).  The bf16 MFMA
+// has 16 times the rate of the fp32 one, so six of its products cost 3/8 of one fp32 product.
 //
 // A pre-pass (split3_pack_kernel) writes the three terms as three planes in the k-interleaved layout of the
 // bf16 kernels (P[token / 8][column][token % 8], zero-padded to 32 tokens and 256 columns); the MFMA kernel
@@ -41,7 +41,7 @@ struct Split3Launch {
 // token row), the split in registers, and per plane the eight tokens as one 16-byte packed write (a wave
 // writes 1 KB runs): no LDS, every request of a thread in flight at once.
 constexpr int S3P_COLS = 256;  // columns per workgroup: one per thread
-constexpr int S3P_GROUPS = 1;  // k-groups per workgroup (measured on the BERT-Large stage: 1: 1.1 ms, 2: 1.28, 4: 1.35)
+constexpr int S3P_GROUPS = 1;  // k-groups per workgroup (whole launch of the BERT-Large stage with 1 / 2 / 4: 6.45 / 6.62 / 6.71 ms)
 
 __device__ inline unsigned s3_bf16_bits(float v)
 {
