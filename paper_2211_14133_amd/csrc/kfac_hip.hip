@@ -636,11 +636,33 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
             }
             sp.first_wg[n] = (int)wgs;
             sp.count = (int)n;
-            l2.count = (int)n;
-            l2.alpha = alpha;
-            l2.beta = beta;
             hipLaunchKernelGGL(split3_pack_kernel, dim3((unsigned)wgs), dim3(256), 0, st, sp);
-            hipLaunchKernelGGL(curvature_syrk_split3_256_kernel, dim3(tb), dim3(256), 0, st, l2);
+            // The MFMA kernel keeps one fp32 accumulation level, whose rounding error grows with the square
+            // root of the tokens: long inputs go in chunks of S3_CHUNK_GROUPS k-groups, each chunk added to the
+            // factor by its epilogue (the first with the caller's beta, the others with 1).
+            int gmax3 = 0;
+            for (int64_t i = 0; i < n; ++i) gmax3 = std::max(gmax3, sp.it[i].gp);
+            for (int g0 = 0; g0 < gmax3; g0 += S3_CHUNK_GROUPS) {
+                Syrk256Launch lc;
+                std::memset(&lc, 0, sizeof(lc));
+                int cnt = 0;
+                tb = 0;
+                for (int64_t i = 0; i < n; ++i) {
+                    const Split3Item &si = sp.it[i];
+                    if (si.gp <= g0) continue;  // this item's tokens are used up
+                    SyrkProblem &q = lc.p[cnt++];
+                    q = l2.p[i];
+                    q.x = static_cast<const char *>(l2.p[i].x) + (size_t)g0 * si.dp * 16;
+                    q.n = std::min(S3_CHUNK_GROUPS, si.gp - g0) * BF_KG;
+                    q.pad_ = si.gp;  // k-groups of a whole plane: the planes are that far apart
+                    q.tile_begin = tb;
+                    tb += b2_tiles(si.d);
+                }
+                lc.count = cnt;
+                lc.alpha = alpha;
+                lc.beta = g0 == 0 ? beta : 1.f;
+                hipLaunchKernelGGL(curvature_syrk_split3_256_kernel, dim3(tb), dim3(256), 0, st, lc);
+            }
             if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
             done += n;
             continue;

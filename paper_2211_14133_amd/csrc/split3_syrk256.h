@@ -23,6 +23,7 @@ constexpr int S3_PLANES = 3;
 constexpr int S3_GROUP_BYTES = B2_TILE * 16;                    // one k-group of one plane of one operand: 4 KB
 constexpr int S3_STAGE_BYTES = S3_PLANES * 2 * S3_GROUP_BYTES;  // 16 tokens: 24 KB per operand
 constexpr int S3_STAGES = 3;
+constexpr int S3_CHUNK_GROUPS = 1024;  // tokens / 8 that one launch of the MFMA kernel accumulates (a multiple of 4)
 
 // ---------------------------------------------------------------------------
 // Pre-pass: float32 [n, d] -> three packed bfloat16 planes, dst + plane * gp * dp * 8 elements.
@@ -99,8 +100,9 @@ __global__ __launch_bounds__(256) void split3_pack_kernel(const Split3Launch pl)
 }
 
 // ---------------------------------------------------------------------------
-// The MFMA kernel.  Descriptor as for the bf16 kernels: x = the three planes, n = padded tokens,
-// ldx = padded columns.
+// The MFMA kernel.  Descriptor as for the bf16 kernels: x = the first of the three planes (at the first k-group
+// of this launch's share of the tokens), n = padded tokens of the share, ldx = padded columns, pad_ = k-groups
+// of a whole plane.
 //
 // Two passes over K into the same accumulators.  The matrix core adds the sixteen products of an instruction
 // to the accumulator with the bits below the accumulator's last place cut off rather than rounded; for
@@ -137,7 +139,7 @@ __device__ __forceinline__ void s3_pass_small(const SyrkProblem &pr, int m0, int
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
     const size_t row_bytes = (size_t)pr.ldx * 16;  // one k-group of all columns of one plane
     const int groups = pr.n / BF_KG;
-    const size_t plane_bytes = (size_t)groups * row_bytes;
+    const size_t plane_bytes = (size_t)pr.pad_ * row_bytes;  // pad_: k-groups of a whole plane (groups: of this launch's share)
     const int niter = groups / 2;
     const char *xp = static_cast<const char *>(pr.x);
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);

@@ -943,3 +943,19 @@ def test_chain_config3_feed_forward_layers_with_split_bf16_curvature(k, oracle):
         print("cfg 3 %-5s split curvature: A %.2e B %.2e A^-1 %.2e P %.2e" % (name, ea, eb, eai, ep), flush=True)
         assert ea <= SPLIT_FACTOR_TOL and eb <= SPLIT_FACTOR_TOL
         assert ep <= PRECOND_TOL
+
+
+def test_curvature_split_bf16_long_inputs_go_in_chunks(k, oracle):
+    """More than 8192 tokens: the bf16-MFMA kernel runs once per chunk of 8192 and adds up through the factor, so
+    the error stays that of one chunk; items of different lengths drop out of the later launches."""
+    d = 3584
+    lens = [20000, 9000]
+    xs = [synth.activations(6, 3, i, 0, n, d, gelu=(i == 1)) for i, n in enumerate(lens)]
+    fs = [torch.zeros(d, d, device="cuda") for _ in xs]  # beta = 1 on zeros: the first chunk must honour beta too
+    want = [oracle.curvature(x) * (x.shape[0] * 1e-4) for x in xs]
+    k.kfac_curvature_grouped([dev(x) for x in xs], fs, 1e-4, 1.0, split_bf16=True)
+    for n, f, w in zip(lens, fs, want):
+        err = oracle.rel_fro(host(f), w)
+        print("  %d tokens rel_fro %.3g" % (n, err), flush=True)
+        assert err <= SPLIT_FACTOR_TOL
+        assert np.array_equal(host(f), host(f).T)
