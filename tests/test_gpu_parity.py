@@ -959,3 +959,18 @@ def test_curvature_split_bf16_long_inputs_go_in_chunks(k, oracle):
         print("  %d tokens rel_fro %.3g" % (n, err), flush=True)
         assert err <= SPLIT_FACTOR_TOL
         assert np.array_equal(host(f), host(f).T)
+
+
+def test_curvature_split_bf16_more_items_than_one_launch_describes(k, oracle):
+    """90 items: the first 80 fill a launch of the bf16-MFMA kernel, the other 10 are too few tiles for it and
+    take the fp32 path inside the same call."""
+    n, d, cnt = 64, 1024, 90
+    xs = [synth.activations(6, 4, i, 0, n, d) for i in range(cnt)]
+    fs = [torch.empty(d, d, device="cuda") for _ in xs]
+    k.kfac_curvature_grouped([dev(x) for x in xs], fs, 1.0 / n, 0.0, split_bf16=True)
+    worst = max(oracle.rel_fro(host(fs[i]), oracle.curvature(xs[i])) for i in (0, 41, 79, 80, 89))
+    print("  worst rel_fro %.3g" % worst, flush=True)
+    assert worst <= SPLIT_FACTOR_TOL
+    ref = torch.empty(d, d, device="cuda")
+    k.kfac_curvature(dev(xs[85]), ref, 1.0 / n, 0.0)
+    assert torch.equal(ref, fs[85])  # the fp32 path's bits
