@@ -397,18 +397,20 @@ __device__ inline b2_short4 b2_read_tr(const char *lds_ptr)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) b2_short4 *)lds_ptr);
 }
 
-__global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_rowmajor_kernel(const Syrk256Launch lp)
-{
-    __shared__ __attribute__((aligned(16))) char lds[B2_STAGES * B2R_STAGE_BYTES];
+// What a wave computes of its 128 x 128 quarter.  On a diagonal tile the upper right quarter is only stored as
+// the mirror of the lower left one: its wave takes part in the loads and barriers and computes nothing; the two
+// quarters on the diagonal leave out their six 32 x 32 blocks above the diagonal.  The tile takes as long as
+// its full quarter, but the chip is power-limited under the bf16 MFMA kernels: MFMAs that are not issued let
+// the others run at a higher clock.
+enum B2WaveMode : int { B2_WAVE_FULL = 0, B2_WAVE_IDLE = 1, B2_WAVE_LOWER = 2 };
 
+template <int MODE>
+__device__ __forceinline__ void b2r_mainloop(const SyrkProblem &pr, int m0, int n0, const char *lds, floatx16 (&acc)[4][4])
+{
+    constexpr bool IDLE = MODE == B2_WAVE_IDLE, LOWER = MODE == B2_WAVE_LOWER;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 31, lh = lane >> 5;
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
-
-    const B2Tile bt = b2_locate(lp);
-    const SyrkProblem &pr = lp.p[bt.pi];
-    const int m0 = bt.m0, n0 = bt.n0;
     const int K = pr.n;
     const int niter = K / B2R_SLAB_ROWS;
     const size_t row_pitch = (size_t)pr.ldx * 2;  // bytes per token row of x
@@ -418,14 +420,6 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_rowmajor_kerne
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const unsigned l0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(const __attribute__((address_space(3))) char *)lds) +
                         wave_s * (8 * B2R_ROW_BYTES);  // wave w fetches rows 8w .. 8w+7 of a slab
-
-    floatx16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     // transposing reads: group g = lane / 16 covers k half g / 2 and column half g % 2 of a 32-column block
     const int g = lane >> 4, s4 = (lane >> 2) & 3, q4 = lane & 3;
@@ -460,15 +454,15 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_rowmajor_kerne
     } while (0)
 #define R2_RA(st, t, set)                                                                  \
     do {                                                                                   \
-        _Pragma("unroll") for (int b = 0; b < 4; ++b) R2_R(fa[set][b], ra, st, t, b);      \
+        if (!IDLE) _Pragma("unroll") for (int b = 0; b < 4; ++b) R2_R(fa[set][b], ra, st, t, b); \
     } while (0)
 #define R2_RB(st, t, set)                                                                  \
     do {                                                                                   \
-        _Pragma("unroll") for (int b = 0; b < 4; ++b) R2_R(fb[set][b], rb, st, t, b);      \
+        if (!IDLE) _Pragma("unroll") for (int b = 0; b < 4; ++b) R2_R(fb[set][b], rb, st, t, b); \
     } while (0)
 #define R2_MG(set, bi)                                                                                        \
     do {                                                                                                      \
-        _Pragma("unroll") for (int bj = 0; bj < 4; ++bj)                                                      \
+        if (!IDLE) _Pragma("unroll") for (int bj = 0; bj < (LOWER ? (bi) + 1 : 4); ++bj)                      \
             acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                            \
                 __builtin_bit_cast(bf16x8, fa[set][bi]), __builtin_bit_cast(bf16x8, fb[set][bj]),             \
                 acc[bi][bj], 0, 0, 0);                                                                        \
@@ -550,6 +544,37 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_rowmajor_kerne
 #undef R2_PIN
 #undef R2_ITER
 
+}
+
+__global__ __launch_bounds__(256, 1) void curvature_syrk_bf16_256_rowmajor_kernel(const Syrk256Launch lp)
+{
+    __shared__ __attribute__((aligned(16))) char lds[B2_STAGES * B2R_STAGE_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+    const B2Tile bt = b2_locate(lp);
+    const SyrkProblem &pr = lp.p[bt.pi];
+    const int m0 = bt.m0, n0 = bt.n0;
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int mode_wave = __builtin_amdgcn_readfirstlane(wave);
+    if (bt.diag && mode_wave == 1) {
+        b2r_mainloop<B2_WAVE_IDLE>(pr, m0, n0, lds, acc);
+        return;
+    }
+    if (bt.diag && mode_wave != 2)
+        b2r_mainloop<B2_WAVE_LOWER>(pr, m0, n0, lds, acc);
+    else
+        b2r_mainloop<B2_WAVE_FULL>(pr, m0, n0, lds, acc);
     if (lp.beta == 0.f)
         b2_store(acc, pr, lp.alpha, 0.f, m0, n0, wm, wn, li, lh, bt.diag);
     else
