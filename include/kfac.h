@@ -313,6 +313,12 @@ const char *kfac_status_string(kfac_status status);
  * The launch is asynchronous on `stream`.  Errors: KFAC_ERR_ARG for null pointers, iters <= 0 or an
  * unknown dtype; KFAC_ERR_HIP if the launch fails. */
 kfac_status kfac_mfma_probe(kfac_dtype dtype, int64_t iters, void *sink, double *flops, void *stream);
+/* The same with a choice of operand data.  random_operands = 0: constant operands, as kfac_mfma_probe;
+ * otherwise operands with random sign and mantissa bits, four sets in rotation (iters is rounded up to a
+ * multiple of 4): what the matrix cores sustain when their inputs toggle as real data does, which on this
+ * chip is less, because it lowers its clock under the higher power draw. */
+kfac_status kfac_mfma_probe_data(kfac_dtype dtype, int random_operands, int64_t iters, void *sink, double *flops,
+                                 void *stream);
 
 /* Library version as major * 10000 + minor * 100 + patch. */
 int kfac_version(void);

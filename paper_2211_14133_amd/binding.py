@@ -66,6 +66,7 @@ SIGNATURES = {
     "kfac_perf_model": (ctypes.c_int, [ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double, _i64,
                                        ctypes.c_double, ctypes.c_double, ctypes.c_double, _dp]),
     "kfac_mfma_probe": (ctypes.c_int, [ctypes.c_int, _i64, _vp, _dp, _vp]),
+    "kfac_mfma_probe_data": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _i64, _vp, _dp, _vp]),
     "kfac_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "kfac_version": (ctypes.c_int, []),
 }
@@ -381,9 +382,9 @@ def kfac_perf_model(c_f, c_b, t_f, t_b, n_micro, t_curv, t_inv, t_prec):
     return {"t_pipe": out[0], "t_bubble": out[1], "t_kfac": out[2], "ratio": out[3], "t_step": out[4]}
 
 
-def kfac_mfma_probe(dtype, iters, sink, stream=None):
+def kfac_mfma_probe(dtype, iters, sink, stream=None, random_operands=False):
     """Enqueue the register-only MFMA loop; returns the flops it performs (time it with events)."""
     flops = ctypes.c_double(0.0)
-    _check(load().kfac_mfma_probe(int(dtype), int(iters), ctypes.c_void_p(sink.data_ptr()), ctypes.byref(flops),
-                                  _stream(stream)))
+    _check(load().kfac_mfma_probe_data(int(dtype), int(bool(random_operands)), int(iters),
+                                       ctypes.c_void_p(sink.data_ptr()), ctypes.byref(flops), _stream(stream)))
     return flops.value

@@ -539,11 +539,25 @@ const char *kfac_status_string(kfac_status s)
 
 kfac_status kfac_mfma_probe(kfac_dtype dtype, int64_t iters, void *sink, double *flops, void *stream)
 {
+    return kfac_mfma_probe_data(dtype, 0, iters, sink, flops, stream);
+}
+
+kfac_status kfac_mfma_probe_data(kfac_dtype dtype, int random_operands, int64_t iters, void *sink, double *flops, void *stream)
+{
     if (sink == nullptr || flops == nullptr || iters <= 0 || iters > INT32_MAX) return KFAC_ERR_ARG;
     if (dtype != KFAC_F32 && dtype != KFAC_BF16) return KFAC_ERR_ARG;
     constexpr int WORKGROUPS = 256 * 2 * 8;  // eight rounds of two workgroups per CU
     hipStream_t st = static_cast<hipStream_t>(stream);
     const double per_mfma = dtype == KFAC_F32 ? 4096.0 : 32768.0;
+    if (random_operands) {
+        const int outer = (int)((iters + PROBE_SETS - 1) / PROBE_SETS);  // every pass of the loop takes all operand sets
+        *flops = (double)WORKGROUPS * 4.0 * (double)outer * PROBE_SETS * PROBE_MFMA_PER_ITER * per_mfma;
+        if (dtype == KFAC_F32)
+            hipLaunchKernelGGL(mfma_probe_f32_random_kernel, dim3(WORKGROUPS), dim3(256), 0, st, outer, static_cast<float *>(sink));
+        else
+            hipLaunchKernelGGL(mfma_probe_bf16_random_kernel, dim3(WORKGROUPS), dim3(256), 0, st, outer, static_cast<float *>(sink));
+        return hipGetLastError() == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
+    }
     *flops = (double)WORKGROUPS * 4.0 * (double)iters * PROBE_MFMA_PER_ITER * per_mfma;
     if (dtype == KFAC_F32)
         hipLaunchKernelGGL(mfma_probe_f32_kernel, dim3(WORKGROUPS), dim3(256), 0, st, 1.0f, 2.0f, (int)iters,

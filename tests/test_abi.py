@@ -145,6 +145,8 @@ def test_mfma_probe_rejects_bad_arguments():
     assert lib.kfac_mfma_probe(binding.KFAC_F32, 10, fake, None, None) == 1
     assert lib.kfac_mfma_probe(binding.KFAC_F32, 0, fake, ctypes.byref(flops), None) == 1
     assert lib.kfac_mfma_probe(7, 10, fake, ctypes.byref(flops), None) == 1
+    assert lib.kfac_mfma_probe_data(binding.KFAC_BF16, 1, 10, None, ctypes.byref(flops), None) == 1
+    assert lib.kfac_mfma_probe_data(binding.KFAC_F32_BF16X3, 1, 10, fake, ctypes.byref(flops), None) == 1
 
 
 def test_header_is_plain_c_and_cxx():

@@ -804,6 +804,9 @@ def test_mfma_probe_reports_its_work(k):
         flops = k.kfac_mfma_probe(code, 50, sink)
         torch.cuda.synchronize()
         assert flops == 256 * 2 * 8 * 4 * 50 * 8 * per_mfma
+        flops = k.kfac_mfma_probe(code, 50, sink, random_operands=True)  # 50 rounded up to 52: 13 passes of 4 operand sets
+        torch.cuda.synchronize()
+        assert flops == 256 * 2 * 8 * 4 * 52 * 8 * per_mfma
     assert float(sink.abs().max()) == 0.0
 
 
