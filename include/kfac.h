@@ -60,7 +60,12 @@ typedef enum {
     /* float32 activations / errors, each value taken as the sum of three bfloat16 terms and each product as the
      * six bf16 MFMA products that reach 2^-16 of it (the rest is below the rounding of one float32 operation),
      * fp32 accumulation; curvature only.  Launches too small for this path are computed as KFAC_F32. */
-    KFAC_F32_BF16X3 = 2
+    KFAC_F32_BF16X3 = 2,
+    /* float32 activations / errors, each tensor scaled by a power of two so that its largest magnitude lies in
+     * [2^14, 2^15), each value then taken as the sum of two float16 terms and each product as the three f16 MFMA
+     * products that reach 2^-11 of it, fp32 accumulation; curvature only.  Elements below 2^-28 of the tensor's
+     * largest lose relative (not absolute) accuracy.  Launches too small for this path are computed as KFAC_F32. */
+    KFAC_F32_F16X2 = 3
 } kfac_dtype;
 
 /* ---------------------------------------------------------------- curvature

@@ -15,6 +15,7 @@ KFAC_OK = 0
 KFAC_F32 = 0
 KFAC_BF16 = 1
 KFAC_F32_BF16X3 = 2
+KFAC_F32_F16X2 = 3
 
 _i64 = ctypes.c_int64
 _f32 = ctypes.c_float
@@ -110,10 +111,13 @@ def _stream(stream):
 
 
 def _dtype_code(t, split_bf16=False):
+    """split_bf16: False, True / "bf16x3" (three bfloat16 terms) or "f16x2" (two float16 terms)."""
     if t.dtype == torch.float32:
-        return KFAC_F32_BF16X3 if split_bf16 else KFAC_F32
+        if not split_bf16:
+            return KFAC_F32
+        return KFAC_F32_F16X2 if split_bf16 == "f16x2" else KFAC_F32_BF16X3
     if split_bf16:
-        raise KfacError("split_bf16 is a mode for float32 input (got %s)" % t.dtype)
+        raise KfacError("the split modes are for float32 input (got %s)" % t.dtype)
     if t.dtype == torch.bfloat16:
         return KFAC_BF16
     raise KfacError("unsupported activation dtype %s" % t.dtype)

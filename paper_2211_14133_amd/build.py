@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkfac_mi355x.so")
 SOURCES = ["kfac_hip.hip", "bubble_fill.cpp"]
-HEADERS = ["tn_gemm.h", "diag_block.h", "bf16_syrk256.h", "split3_syrk256.h", "mfma_probe.h", os.path.join("..", "..", "include", "kfac.h")]
+HEADERS = ["tn_gemm.h", "diag_block.h", "bf16_syrk256.h", "split3_syrk256.h", "split2_syrk256.h", "mfma_probe.h", os.path.join("..", "..", "include", "kfac.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",

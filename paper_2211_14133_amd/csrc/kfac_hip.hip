@@ -17,6 +17,7 @@
 #include "../../include/kfac.h"
 #include "bf16_syrk256.h"
 #include "split3_syrk256.h"
+#include "split2_syrk256.h"
 #include "mfma_probe.h"
 #include "diag_block.h"
 #include "tn_gemm.h"
@@ -230,6 +231,10 @@ bool curvature_plan(const kfac_curvature_item *items, int64_t count, kfac_dtype 
         for (int64_t i = 0; i < count; ++i) pl.pack += pack_bytes(items[i].n_tokens, items[i].d);
     if (dtype == KFAC_F32_BF16X3)
         for (int64_t i = 0; i < count; ++i) pl.pack += S3_PLANES * pack_bytes(items[i].n_tokens, items[i].d);
+    if (dtype == KFAC_F32_F16X2) {
+        pl.pack += align_up((size_t)count * sizeof(unsigned), WS_ALIGN);  // the largest magnitude of every item
+        for (int64_t i = 0; i < count; ++i) pl.pack += S2_PLANES * pack_bytes(items[i].n_tokens, items[i].d);
+    }
     pl.ws = pl.pack + (pl.splits > 1 ? align_up((size_t)tiles * pl.splits * BM * BN * sizeof(float), WS_ALIGN) : 0);
     return true;
 }
@@ -585,7 +590,7 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
 {
     if (count == 0) return KFAC_OK;
     if (items == nullptr || count < 0) return KFAC_ERR_ARG;
-    if (dtype != KFAC_F32 && dtype != KFAC_BF16 && dtype != KFAC_F32_BF16X3) return KFAC_ERR_ARG;
+    if (dtype != KFAC_F32 && dtype != KFAC_BF16 && dtype != KFAC_F32_BF16X3 && dtype != KFAC_F32_F16X2) return KFAC_ERR_ARG;
     for (int64_t i = 0; i < count; ++i) {
         const kfac_curvature_item &it = items[i];
         if (it.x == nullptr || it.factor == nullptr) return KFAC_ERR_ARG;
@@ -605,6 +610,8 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
     // one launch per micro-batch); each launch gets its own slice of the partial buffer.
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *pack = static_cast<char *>(workspace);
+    unsigned *amax = reinterpret_cast<unsigned *>(workspace);  // KFAC_F32_F16X2: one word per item, in front of the planes
+    if (dtype == KFAC_F32_F16X2) pack += align_up((size_t)count * sizeof(unsigned), WS_ALIGN);
     float *part = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.pack);
     for (int64_t done = 0; done < count;) {
         const int64_t n = std::min<int64_t>(SYRK_MAX_PROBLEMS, count - done);
@@ -613,8 +620,72 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
         PackLaunch pk;
         if (dtype == KFAC_BF16) std::memset(&pk, 0, sizeof(pk));
         int tiles256_f32 = 0;
-        if (dtype == KFAC_F32_BF16X3)
+        if (dtype == KFAC_F32_BF16X3 || dtype == KFAC_F32_F16X2)
             for (int64_t i = 0; i < n; ++i) tiles256_f32 += b2_tiles((int)items[done + i].d);
+        if (dtype == KFAC_F32_F16X2 && tiles256_f32 >= 192) {
+            // float32 input as two float16 terms on the f16 MFMA (split2_syrk256.h); launches too small to occupy
+            // the chip with 256 x 256 tiles take the fp32 path below
+            Split2Launch sp;
+            Syrk256LaunchScaled ls;
+            std::memset(&sp, 0, sizeof(sp));
+            std::memset(&ls, 0, sizeof(ls));
+            int64_t wg_amax = 0, wg_pack = 0;
+            int first_pack[PACK_MAX_ITEMS + 1];
+            for (int64_t i = 0; i < n; ++i) {
+                const kfac_curvature_item &it = items[done + i];
+                Split2Item &si = sp.it[i];
+                si.x = static_cast<const float *>(it.x);
+                si.dst = reinterpret_cast<unsigned short *>(pack);
+                si.n = (int)it.n_tokens;
+                si.d = (int)it.d;
+                si.ldx = (int)it.ldx;
+                si.dp = pack_cols(it.d);
+                si.gp = pack_groups(it.n_tokens);
+                pack += S2_PLANES * pack_bytes(it.n_tokens, it.d);
+                sp.first_wg[i] = (int)wg_amax;
+                first_pack[i] = (int)wg_pack;
+                wg_amax += (int64_t)(si.dp / S2P_COLS) * ((si.gp + S2A_GROUPS - 1) / S2A_GROUPS);
+                wg_pack += (int64_t)(si.dp / S2P_COLS) * si.gp;
+                if (wg_pack > INT32_MAX) return KFAC_ERR_UNSUPPORTED;  // more workgroups than a grid holds
+            }
+            sp.first_wg[n] = (int)wg_amax;
+            first_pack[n] = (int)wg_pack;
+            sp.count = (int)n;
+            sp.amax = amax + done;
+            hipLaunchKernelGGL(split2_clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, sp.amax, (int)n);
+            hipLaunchKernelGGL(split2_amax_kernel, dim3((unsigned)wg_amax), dim3(256), 0, st, sp);
+            std::memcpy(sp.first_wg, first_pack, sizeof(int) * (size_t)(n + 1));
+            hipLaunchKernelGGL(split2_pack_kernel, dim3((unsigned)wg_pack), dim3(256), 0, st, sp);
+            // chunks of S3_CHUNK_GROUPS k-groups, as for the three-term split below
+            int gmax2 = 0;
+            for (int64_t i = 0; i < n; ++i) gmax2 = std::max(gmax2, sp.it[i].gp);
+            for (int g0 = 0; g0 < gmax2; g0 += S3_CHUNK_GROUPS) {
+                int cnt = 0, tb = 0;
+                for (int64_t i = 0; i < n; ++i) {
+                    const Split2Item &si = sp.it[i];
+                    if (si.gp <= g0) continue;  // this item's tokens are used up
+                    ls.amax_index[cnt] = (int)i;
+                    SyrkProblem &q = ls.l.p[cnt++];
+                    q.x = reinterpret_cast<const char *>(si.dst) + (size_t)g0 * si.dp * 16;
+                    q.factor = items[done + i].factor;
+                    q.n = std::min(S3_CHUNK_GROUPS, si.gp - g0) * BF_KG;
+                    q.d = si.d;
+                    q.ldx = si.dp;
+                    q.ldf = (int)items[done + i].ldf;
+                    q.pad_ = si.gp;  // k-groups of a whole plane: the planes are that far apart
+                    q.tile_begin = tb;
+                    tb += b2_tiles(si.d);
+                }
+                ls.l.count = cnt;
+                ls.l.alpha = alpha;
+                ls.l.beta = g0 == 0 ? beta : 1.f;
+                ls.amax = sp.amax;
+                hipLaunchKernelGGL(curvature_syrk_split2_256_kernel, dim3(tb), dim3(256), 0, st, ls);
+            }
+            if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
+            done += n;
+            continue;
+        }
         if (dtype == KFAC_F32_BF16X3 && tiles256_f32 >= 192) {
             // float32 input as three bfloat16 terms on the bf16 MFMA (split3_syrk256.h); launches too small to
             // occupy the chip with 256 x 256 tiles take the fp32 path below

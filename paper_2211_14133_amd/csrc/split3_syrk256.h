@@ -330,20 +330,22 @@ __device__ __forceinline__ void s3_pass_small(const SyrkProblem &pr, int m0, int
 }
 
 // Pass 2: acc += h^T h over the h plane, the K loop of curvature_syrk_bf16_256_kernel (slabs of 32 tokens,
-// 16 KB per operand, in a 4-stage ring; the caller has made sure nothing of pass 1 is still using LDS).
-template <int MODE>
-__device__ __forceinline__ void s3_pass_large(const SyrkProblem &pr, int m0, int n0, const char *lds_a, const char *lds_b,
-                                              floatx16 (&acc)[4][4])
+// 16 KB per operand, in a 4-stage ring; the caller has made sure nothing of pass 1 is still using LDS), written
+// for any pair of planes.
+typedef _Float16 s3_halfx8 __attribute__((ext_vector_type(8)));
+
+// xa, xb: the plane the row panel / the column panel is taken from (packed layout, `groups` k-groups of
+// `row_bytes`); F16: the planes hold float16 (MFMA 32x32x16 f16) instead of bfloat16.
+template <int MODE, bool F16>
+__device__ __forceinline__ void s3_pass_planes(const char *xa, const char *xb, size_t row_bytes, int groups, int m0, int n0,
+                                               const char *lds_a, const char *lds_b, floatx16 (&acc)[4][4])
 {
     constexpr bool IDLE = MODE == S3_WAVE_IDLE, LOWER = MODE == S3_WAVE_LOWER;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lh = lane >> 5;
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
-    const size_t row_bytes = (size_t)pr.ldx * 16;
-    const int groups = pr.n / BF_KG;
     const int niter = groups / BF_SLAB_GROUPS;
-    const char *xp = static_cast<const char *>(pr.x);  // plane 0
     const unsigned va = (unsigned)(((size_t)m0 + lane) * 16);
     const unsigned vb = (unsigned)(((size_t)n0 + lane) * 16);
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -360,20 +362,22 @@ __device__ __forceinline__ void s3_pass_large(const SyrkProblem &pr, int m0, int
 
     u32x4 fa[2][4], fb[2][4];  // [k step parity][block]
     int gd = 0;
-    const char *sbase = xp;
+    const char *sbase_a = xa, *sbase_b = xb;
     // wave w fetches k-group gd + w: the 256 columns of each operand in four 64-column pieces
 #define H2_DBASE()                                                                         \
     do {                                                                                   \
-        sbase = xp + (size_t)min(gd + wave_s, groups - 1) * row_bytes;                     \
+        const size_t o_ = (size_t)min(gd + wave_s, groups - 1) * row_bytes;                \
+        sbase_a = xa + o_;                                                                 \
+        sbase_b = xb + o_;                                                                 \
         gd += BF_SLAB_GROUPS;                                                              \
     } while (0)
 #define H2_D1(st, w)                                                                                           \
     do {                                                                                                       \
         if (((w) & 1) == 0)                                                                                    \
-            tn_dma16_s(reinterpret_cast<const float *>(sbase + ((w) >> 1) * 1024), va,                         \
+            tn_dma16_s(reinterpret_cast<const float *>(sbase_a + ((w) >> 1) * 1024), va,                       \
                        la0 + (st) * B2_STAGE_BYTES + ((w) >> 1) * 1024);                                       \
         else                                                                                                   \
-            tn_dma16_s(reinterpret_cast<const float *>(sbase + ((w) >> 1) * 1024), vb,                         \
+            tn_dma16_s(reinterpret_cast<const float *>(sbase_b + ((w) >> 1) * 1024), vb,                       \
                        lb0 + (st) * B2_STAGE_BYTES + ((w) >> 1) * 1024);                                       \
     } while (0)
 #define H2_R(set, base, st, t)                                                                                 \
@@ -383,10 +387,16 @@ __device__ __forceinline__ void s3_pass_large(const SyrkProblem &pr, int m0, int
     } while (0)
 #define H2_MG(set, bi)                                                                                         \
     do {                                                                                                       \
-        if (!IDLE) _Pragma("unroll") for (int bj = 0; bj < (LOWER ? (bi) + 1 : 4); ++bj)                       \
-            acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                             \
-                __builtin_bit_cast(bf16x8, fa[set][bi]), __builtin_bit_cast(bf16x8, fb[set][bj]),              \
-                acc[bi][bj], 0, 0, 0);                                                                         \
+        if (!IDLE) _Pragma("unroll") for (int bj = 0; bj < (LOWER ? (bi) + 1 : 4); ++bj) {                     \
+            if (F16)                                                                                           \
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(                                          \
+                    __builtin_bit_cast(s3_halfx8, fa[set][bi]), __builtin_bit_cast(s3_halfx8, fb[set][bj]),    \
+                    acc[bi][bj], 0, 0, 0);                                                                     \
+            else                                                                                               \
+                acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                         \
+                    __builtin_bit_cast(bf16x8, fa[set][bi]), __builtin_bit_cast(bf16x8, fb[set][bj]),          \
+                    acc[bi][bj], 0, 0, 0);                                                                     \
+        }                                                                                                      \
     } while (0)
 #define H2_PIN() __builtin_amdgcn_sched_barrier(0)
 #define H2_ITER(st0, st1, st3)                                                             \
@@ -469,7 +479,8 @@ __device__ __forceinline__ void s3_mainloop(const SyrkProblem &pr, int m0, int n
 {
     s3_pass_small<MODE>(pr, m0, n0, lds_a, lds_b, acc);
     __syncthreads();  // every wave has read its last fragments of pass 1 (and waited for its own loads)
-    s3_pass_large<MODE>(pr, m0, n0, lds_a, lds_b, acc);
+    const char *h = static_cast<const char *>(pr.x);  // plane 0
+    s3_pass_planes<MODE, false>(h, h, (size_t)pr.ldx * 16, pr.n / BF_KG, m0, n0, lds_a, lds_b, acc);
 }
 
 __global__ __launch_bounds__(256, 1) void curvature_syrk_split3_256_kernel(const Syrk256Launch lp)

@@ -100,8 +100,13 @@ def test_split_bf16_dtype_workspace_and_header_value():
         plane = -(-n // 32) * 32 * (-(-d // 256) * 256) * 2
         assert need >= 3 * plane
         assert need == 3 * lib.kfac_curvature_workspace(n, d, binding.KFAC_BF16)
+        # two float16 planes and one word per item for its largest magnitude
+        need2 = lib.kfac_curvature_workspace(n, d, binding.KFAC_F32_F16X2)
+        assert need2 == 2 * lib.kfac_curvature_workspace(n, d, binding.KFAC_BF16) + 256
+    assert "KFAC_F32_F16X2 = %d" % binding.KFAC_F32_F16X2 in header
     dummy = ctypes.c_void_p(0x1000)
-    assert lib.kfac_curvature(dummy, 3, 64, 64, 64, 1.0, 0.0, dummy, 64, None, 0, None) == 1
+    assert lib.kfac_curvature(dummy, 4, 64, 64, 64, 1.0, 0.0, dummy, 64, None, 0, None) == 1
+    assert lib.kfac_curvature(dummy, binding.KFAC_F32_F16X2, 64, 4096, 4096, 1.0, 0.0, dummy, 4096, None, 0, None) == 3
     assert lib.kfac_curvature(dummy, binding.KFAC_F32_BF16X3, 64, 4096, 4096, 1.0, 0.0, dummy, 4096, None, 0, None) == 3
 
 

@@ -845,22 +845,25 @@ def test_stage_wise_errors_at_block_shapes(k, oracle):
         assert e_p <= 1e-6 * cancel + 1e-6  # two fp32 products with chunked accumulation: a few ulp of the terms
 
 
-# ---------------------------------------------- float32 input as three bfloat16 terms (KFAC_F32_BF16X3)
+# ------- float32 input as three bfloat16 terms (KFAC_F32_BF16X3) or two float16 terms (KFAC_F32_F16X2)
+
+SPLIT_MODES = ["bf16x3", "f16x2"]
 
 SPLIT_FACTOR_TOL = 6e-7  # measured 3.3e-7 at 4096 tokens; the fp32 path is held to 5e-7
 
 
+@pytest.mark.parametrize("mode", SPLIT_MODES)
 @pytest.mark.parametrize("n,d", [(4096, 4096), (600, 5000), (77, 3600), (1, 3584), (4100, 3585)])
-def test_curvature_split_bf16_parity(k, oracle, n, d):
+def test_curvature_split_bf16_parity(k, oracle, n, d, mode):
     """Two factors with enough 256 x 256 tiles between them for the bf16-MFMA kernel (d >= 3584: 2 x 105),
     ragged sizes, a row pitch larger than d, GELU inputs for the second."""
-    print("split curvature n=%d d=%d" % (n, d), flush=True)
+    print("split curvature %s n=%d d=%d" % (mode, n, d), flush=True)
     xs = [synth.activations(6, 0, i, 0, n, d, gelu=(i == 1)) for i in range(2)]
     bufs = [torch.zeros(n, d + 12, device="cuda") for _ in xs]
     for b, x in zip(bufs, xs):
         b[:, :d] = dev(x)
     fs = [torch.full((d, d), 7.0, device="cuda") for _ in xs]
-    k.kfac_curvature_grouped([b[:, :d] for b in bufs], fs, 1.0 / n, 0.0, split_bf16=True)
+    k.kfac_curvature_grouped([b[:, :d] for b in bufs], fs, 1.0 / n, 0.0, split_bf16=mode)
     for x, f in zip(xs, fs):
         err = oracle.rel_fro(host(f), oracle.curvature(x))
         print("  rel_fro %.3g" % err, flush=True)
@@ -868,14 +871,15 @@ def test_curvature_split_bf16_parity(k, oracle, n, d):
         assert np.array_equal(host(f), host(f).T)
 
 
-def test_curvature_split_bf16_accumulates_and_has_no_bias(k, oracle):
+@pytest.mark.parametrize("mode", SPLIT_MODES)
+def test_curvature_split_bf16_accumulates_and_has_no_bias(k, oracle, mode):
     """Two micro-batches (beta = 0, then 1) at the BERT-Large sizes; the diagonal (a sum of squares, where a
     matrix core that cuts off low bits would show) must not be systematically low."""
     n, d, cnt = 4096, 1024, 24  # 24 x 10 = 240 tiles
     xs = [[synth.activations(6, 1, i, m, n, d) for i in range(cnt)] for m in range(2)]
     fs = [torch.empty(d, d, device="cuda") for _ in range(cnt)]
     for m in range(2):
-        k.kfac_curvature_grouped([dev(x) for x in xs[m]], fs, 1.0 / (2 * n), float(m), split_bf16=True)
+        k.kfac_curvature_grouped([dev(x) for x in xs[m]], fs, 1.0 / (2 * n), float(m), split_bf16=mode)
     bias = []
     for i in (0, 7, 23):
         want = oracle.curvature([xs[0][i], xs[1][i]])
@@ -888,19 +892,21 @@ def test_curvature_split_bf16_accumulates_and_has_no_bias(k, oracle):
     assert max(abs(b) for b in bias) <= 2e-7
 
 
-def test_curvature_split_bf16_small_launch_takes_the_fp32_path(k, oracle):
+@pytest.mark.parametrize("mode", SPLIT_MODES)
+def test_curvature_split_bf16_small_launch_takes_the_fp32_path(k, oracle, mode):
     """Launches with too few 256 x 256 tiles are computed exactly as KFAC_F32: same bits."""
     n, d = 300, 200
     x = dev(synth.activations(6, 2, 0, 0, n, d))
     f1, f2 = torch.empty(d, d, device="cuda"), torch.empty(d, d, device="cuda")
-    k.kfac_curvature(x, f1, 1.0 / n, 0.0, split_bf16=True)
+    k.kfac_curvature(x, f1, 1.0 / n, 0.0, split_bf16=mode)
     k.kfac_curvature(x, f2, 1.0 / n, 0.0)
     assert torch.equal(f1, f2)
     with pytest.raises(k.KfacError):
-        k.kfac_curvature(x.to(torch.bfloat16), f1, 1.0 / n, 0.0, split_bf16=True)
+        k.kfac_curvature(x.to(torch.bfloat16), f1, 1.0 / n, 0.0, split_bf16=mode)
 
 
-def test_curvature_split_bf16_exact_cases_and_determinism(k):
+@pytest.mark.parametrize("mode", SPLIT_MODES)
+def test_curvature_split_bf16_exact_cases_and_determinism(k, mode):
     """Values that are exact in bfloat16 give the exact factor (the m and l planes are zero); two runs agree
     bit for bit."""
     n, d = 512, 3840
@@ -908,17 +914,18 @@ def test_curvature_split_bf16_exact_cases_and_determinism(k):
     g.manual_seed(3)
     x = torch.randint(-3, 4, (n, d), device="cuda", generator=g).float()
     fs = [torch.empty(d, d, device="cuda") for _ in range(2)]
-    k.kfac_curvature_grouped([x, x], fs, 1.0, 0.0, split_bf16=True)
+    k.kfac_curvature_grouped([x, x], fs, 1.0, 0.0, split_bf16=mode)
     want = x.double().t() @ x.double()
     assert torch.equal(fs[0].double(), want) and torch.equal(fs[0], fs[1])
     y = torch.randn(n, d, device="cuda", generator=g)
     f3, f4 = torch.empty(d, d, device="cuda"), torch.empty(d, d, device="cuda")
-    k.kfac_curvature_grouped([y, x], [f3, fs[0]], 0.5, 0.0, split_bf16=True)
-    k.kfac_curvature_grouped([y, x], [f4, fs[1]], 0.5, 0.0, split_bf16=True)
+    k.kfac_curvature_grouped([y, x], [f3, fs[0]], 0.5, 0.0, split_bf16=mode)
+    k.kfac_curvature_grouped([y, x], [f4, fs[1]], 0.5, 0.0, split_bf16=mode)
     assert torch.equal(f3, f4)
 
 
-def test_chain_config3_feed_forward_layers_with_split_bf16_curvature(k, oracle):
+@pytest.mark.parametrize("mode", SPLIT_MODES)
+def test_chain_config3_feed_forward_layers_with_split_bf16_curvature(k, oracle, mode):
     """The worst-conditioned factors of the configurations (FFN2's A: d = tokens = 4096, GELU inputs, smallest
     eigenvalue about the damping) built by the bf16-MFMA path, then inverted and applied: the preconditioned
     gradient stays inside its tolerance."""
@@ -933,7 +940,7 @@ def test_chain_config3_feed_forward_layers_with_split_bf16_curvature(k, oracle):
         gs.append(synth.weight_gradient([es[-1]], [xs[-1]]))
     ins = [dev(x) for x in xs] + [dev(e) for e in es]
     facs = [torch.empty(t.shape[1], t.shape[1], device="cuda") for t in ins]
-    k.kfac_curvature_grouped(ins, facs, 1.0 / n, 0.0, split_bf16=True)
+    k.kfac_curvature_grouped(ins, facs, 1.0 / n, 0.0, split_bf16=mode)
     invs = [torch.empty_like(f) for f in facs]
     infos = k.kfac_invert_batched(facs, synth.DAMPING, invs)
     assert int(infos.abs().max()) == 0
@@ -948,7 +955,8 @@ def test_chain_config3_feed_forward_layers_with_split_bf16_curvature(k, oracle):
         assert ep <= PRECOND_TOL
 
 
-def test_curvature_split_bf16_long_inputs_go_in_chunks(k, oracle):
+@pytest.mark.parametrize("mode", SPLIT_MODES)
+def test_curvature_split_bf16_long_inputs_go_in_chunks(k, oracle, mode):
     """More than 8192 tokens: the bf16-MFMA kernel runs once per chunk of 8192 and adds up through the factor, so
     the error stays that of one chunk; items of different lengths drop out of the later launches."""
     d = 3584
@@ -956,7 +964,7 @@ def test_curvature_split_bf16_long_inputs_go_in_chunks(k, oracle):
     xs = [synth.activations(6, 3, i, 0, n, d, gelu=(i == 1)) for i, n in enumerate(lens)]
     fs = [torch.zeros(d, d, device="cuda") for _ in xs]  # beta = 1 on zeros: the first chunk must honour beta too
     want = [oracle.curvature(x) * (x.shape[0] * 1e-4) for x in xs]
-    k.kfac_curvature_grouped([dev(x) for x in xs], fs, 1e-4, 1.0, split_bf16=True)
+    k.kfac_curvature_grouped([dev(x) for x in xs], fs, 1e-4, 1.0, split_bf16=mode)
     for n, f, w in zip(lens, fs, want):
         err = oracle.rel_fro(host(f), w)
         print("  %d tokens rel_fro %.3g" % (n, err), flush=True)
@@ -964,16 +972,58 @@ def test_curvature_split_bf16_long_inputs_go_in_chunks(k, oracle):
         assert np.array_equal(host(f), host(f).T)
 
 
-def test_curvature_split_bf16_more_items_than_one_launch_describes(k, oracle):
+@pytest.mark.parametrize("mode", SPLIT_MODES)
+def test_curvature_split_bf16_more_items_than_one_launch_describes(k, oracle, mode):
     """90 items: the first 80 fill a launch of the bf16-MFMA kernel, the other 10 are too few tiles for it and
     take the fp32 path inside the same call."""
     n, d, cnt = 64, 1024, 90
     xs = [synth.activations(6, 4, i, 0, n, d) for i in range(cnt)]
     fs = [torch.empty(d, d, device="cuda") for _ in xs]
-    k.kfac_curvature_grouped([dev(x) for x in xs], fs, 1.0 / n, 0.0, split_bf16=True)
+    k.kfac_curvature_grouped([dev(x) for x in xs], fs, 1.0 / n, 0.0, split_bf16=mode)
     worst = max(oracle.rel_fro(host(fs[i]), oracle.curvature(xs[i])) for i in (0, 41, 79, 80, 89))
     print("  worst rel_fro %.3g" % worst, flush=True)
     assert worst <= SPLIT_FACTOR_TOL
     ref = torch.empty(d, d, device="cuda")
     k.kfac_curvature(dev(xs[85]), ref, 1.0 / n, 0.0)
     assert torch.equal(ref, fs[85])  # the fp32 path's bits
+
+
+def test_curvature_f16x2_dynamic_range_and_scaling(k, oracle):
+    """The two-float16-term path scales every tensor by a power of two from its largest magnitude: tensors of
+    very different sizes in one call (1e-6 .. 1e6), and a tensor with one outlier 10^4 times its typical value
+    (the bulk then sits 13 bits lower in the float16 range), keep the error of the ordinary case."""
+    n, d = 512, 3584
+    scales = [1e-6, 1.0, 1e6]
+    xs = [synth.activations(7, 0, i, 0, n, d) * np.float32(sc) for i, sc in enumerate(scales)]
+    out = synth.activations(7, 0, 3, 0, n, d).copy()
+    out[17, 1234] = 3.0e4
+    xs.append(out)
+    fs = [torch.empty(d, d, device="cuda") for _ in xs]
+    k.kfac_curvature_grouped([dev(x) for x in xs], fs, 1.0 / n, 0.0, split_bf16="f16x2")
+    for i, (x, f) in enumerate(zip(xs, fs)):
+        want = oracle.curvature(x)
+        got = host(f)
+        if i == 3:  # judge the bulk apart from the outlier's row and column, which dominate the norm
+            keep = np.ones(d, bool)
+            keep[1234] = False
+            err_bulk = oracle.rel_fro(got[np.ix_(keep, keep)], want[np.ix_(keep, keep)])
+            print("  outlier: bulk rel_fro %.3g" % err_bulk, flush=True)
+            assert err_bulk <= 5e-6
+        err = oracle.rel_fro(got, want)
+        print("  tensor %d rel_fro %.3g" % (i, err), flush=True)
+        assert err <= SPLIT_FACTOR_TOL
+
+
+def test_curvature_split_modes_propagate_non_finite_inputs(k):
+    """A NaN or an infinity in the input must not give finite numbers in its row and column of the factor."""
+    n, d = 64, 3584
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    for mode in SPLIT_MODES:
+        for bad in (float("nan"), float("inf")):
+            xs = [torch.randn(n, d, device="cuda", generator=g) for _ in range(2)]
+            xs[0][5, 100] = bad
+            fs = [torch.zeros(d, d, device="cuda") for _ in xs]
+            k.kfac_curvature_grouped(xs, fs, 1.0 / n, 0.0, split_bf16=mode)
+            assert not bool(torch.isfinite(fs[0][100, :]).any()) and not bool(torch.isfinite(fs[0][:, 100]).any())
+            assert bool(torch.isfinite(fs[1]).all())
