@@ -45,10 +45,12 @@ def parse():
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="2: after the curvature, invert the small factors (and precondition the layers that only need "
                          "them) on one stream and the large factors on another (same results; default 1)")
-    ap.add_argument("--curvature", choices=["f32", "split_bf16"], default="f32",
-                    help="split_bf16: the float32 workloads' curvature as KFAC_F32_BF16X3 (every value as three bfloat16 "
-                         "terms, six bf16 MFMA products per product, fp32 accumulation) instead of the fp32 MFMA; the "
-                         "default line reports this variant's curvature time in its own block either way")
+    ap.add_argument("--curvature", choices=["f32", "split_bf16", "split_f16"], default="f32",
+                    help="the float32 workloads' curvature on the 16-bit matrix core instead of the fp32 MFMA: split_bf16 = "
+                         "KFAC_F32_BF16X3 (every value as three bfloat16 terms, six bf16 MFMA products per product), split_f16 = "
+                         "KFAC_F32_F16X2 (every tensor scaled by a power of two, every value as two float16 terms, three f16 MFMA "
+                         "products per product); fp32 accumulation in both; the default line reports both variants' curvature "
+                         "times in blocks of their own either way")
     ap.add_argument("--phase", choices=["all", "curvature", "inversion", "precondition"], default="all",
                     help="for profiling: after one full untimed step, time only this phase (prints a short JSON "
                          "line that is not the benchmark line)")
@@ -84,11 +86,12 @@ def main():
     cfg = synth.CONFIGS[args.config]
     bf16 = bool(cfg["bf16"])  # activations / errors in bfloat16 (the stress workload); everything else fp32
     in_dtype = binding.KFAC_BF16 if bf16 else binding.KFAC_F32
-    split = args.curvature == "split_bf16"
+    split = args.curvature != "f32"
+    products = 6.0 if args.curvature == "split_bf16" else 3.0  # 16-bit MFMA products per product of two float32 values
     if split:
         if bf16:
-            raise SystemExit("--curvature split_bf16 is a mode for the float32 workloads")
-        in_dtype = binding.KFAC_F32_BF16X3
+            raise SystemExit("--curvature %s is a mode for the float32 workloads" % args.curvature)
+        in_dtype = binding.KFAC_F32_BF16X3 if args.curvature == "split_bf16" else binding.KFAC_F32_F16X2
     tokens, n_micro, blocks = cfg["tokens"], cfg["n_micro"], cfg["blocks"]
     damping = synth.DAMPING
     gen = torch.Generator(device=dev)
@@ -271,7 +274,7 @@ def main():
     achieved = f_curv_launch / (launch_ms * 1e-3) / 1e12
     peak = PEAK_BF16_MFMA_TFLOPS if (bf16 or split) else PEAK_F32_MFMA_TFLOPS
     if split:
-        achieved *= 6.0  # six bf16 MFMA products per product of two float32 values; the pre-pass is part of the launch
+        achieved *= products  # 16-bit MFMA products per product of two float32 values; the pre-passes are part of the launch
 
     # what the matrix cores sustain on this chip with nothing else in the way (register-only MFMA loop)
     sink = torch.zeros(64, dtype=torch.float32, device=dev)
@@ -310,7 +313,7 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if bf16 else ("f32 as 3 x bf16" if split else "f32"),
+        "dtype": "bf16" if bf16 else ({"split_bf16": "f32 as 3 x bf16", "split_f16": "f32 as 2 x f16"}[args.curvature] if split else "f32"),
         "data": "synthetic",
         "config": {
             "workload": "%s: %d blocks x %d linears, %d micro-batches x %d tokens, %s, damping %g"
@@ -341,7 +344,9 @@ def main():
         "roofline": {
             "kernel": "%s (one launch = all %d factors of the stage for one micro-batch)"
                       % ("curvature_syrk_bf16_256_rowmajor_kernel" if bf16 else
-                         ("split3_pack_kernel + curvature_syrk_split3_256_kernel, 6 bf16 products per fp32 product"
+                         ({"split_bf16": "split3_pack_kernel + curvature_syrk_split3_256_kernel, 6 bf16 products per fp32 product",
+                           "split_f16": "split2_amax_kernel + split2_pack_kernel + curvature_syrk_split2_256_kernel, "
+                                        "3 f16 products per fp32 product"}[args.curvature]
                           if split else "curvature_syrk_kernel"), nfac),
             "bound": "mfma",
             "achieved": round(achieved, 2),
@@ -360,7 +365,11 @@ def main():
 
     if not bf16 and not split:
         result["curvature_f32_as_3xbf16"] = split_curvature_variant(
-            torch, binding, lib, check, xs, facs, n_micro, alpha, sp, stream, curv_ms, inv_ms, prec_ms, f_curv)
+            torch, binding, lib, check, xs, facs, n_micro, alpha, sp, stream, curv_ms, inv_ms, prec_ms, f_curv,
+            binding.KFAC_F32_BF16X3)
+        result["curvature_f32_as_2xf16"] = split_curvature_variant(
+            torch, binding, lib, check, xs, facs, n_micro, alpha, sp, stream, curv_ms, inv_ms, prec_ms, f_curv,
+            binding.KFAC_F32_F16X2)
 
     if args.streams == 2:
         # the two phases overlap: report their sum, and none of the blocks that need them separately
@@ -407,12 +416,15 @@ def main():
     print(json.dumps(result))
 
 
-def split_curvature_variant(torch, binding, lib, check, xs, facs, n_micro, alpha, sp, stream, curv_ms, inv_ms, prec_ms, f_curv):
+def split_curvature_variant(torch, binding, lib, check, xs, facs, n_micro, alpha, sp, stream, curv_ms, inv_ms, prec_ms, f_curv,
+                            dt):
     """The curvature of the same step computed as KFAC_F32_BF16X3 (float32 values as three bfloat16 terms on the
-    bf16 MFMA, pre-pass included), timed with HIP events, and how far its factors are from the fp32 MFMA path's."""
+    bf16 MFMA) or KFAC_F32_F16X2 (two float16 terms on the f16 MFMA), pre-passes included, timed with HIP events,
+    and how far its factors are from the fp32 MFMA path's."""
     import ctypes
 
-    dt = binding.KFAC_F32_BF16X3
+    bf = dt == binding.KFAC_F32_BF16X3
+    products = 6 if bf else 3
     nfac = len(facs)
     items = [binding._curv_items(xs[m], facs) for m in range(n_micro)]
     need = lib.kfac_curvature_grouped_workspace(items[0], nfac, dt)
@@ -440,15 +452,18 @@ def split_curvature_variant(torch, binding, lib, check, xs, facs, n_micro, alpha
     for f, r in zip(facs, ref):  # leave the buffers as the timed steps left them
         f.copy_(r)
     return {
-        "what": "curvature of the same step with --curvature split_bf16 (KFAC_F32_BF16X3): pre-pass + bf16 MFMA kernel, "
-                "fp32 accumulation; not part of `value`",
+        "what": ("curvature of the same step with --curvature split_bf16 (KFAC_F32_BF16X3): pre-pass + bf16 MFMA kernel, "
+                 "fp32 accumulation; not part of `value`") if bf else
+                ("curvature of the same step with --curvature split_f16 (KFAC_F32_F16X2): largest-magnitude pass + pre-pass + "
+                 "f16 MFMA kernel, fp32 accumulation; not part of `value`"),
         "curvature_ms": round(ms, 3),
         "launch_ms": round(ms / n_micro, 4),
         "speedup_over_fp32_mfma_curvature": round(curv_ms / ms, 3),
         "step_ms_with_it": round(ms + inv_ms + prec_ms, 3),
         "useful_tflops": round(f_curv / (ms * 1e-3) / 1e12, 2),
-        "bf16_mfma_tflops": round(6 * f_curv / (ms * 1e-3) / 1e12, 1),
-        "frac_of_bf16_mfma_peak": round(6 * f_curv / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
+        "mfma_products_per_product": products,
+        "mfma_16bit_tflops": round(products * f_curv / (ms * 1e-3) / 1e12, 1),
+        "frac_of_16bit_mfma_peak": round(products * f_curv / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
         "rel_fro_difference_from_fp32_path": {"d=%d" % facs[i].shape[0]: float("%.3g" % diff[i]) for i in diff},
     }
 
