@@ -87,8 +87,9 @@ typedef enum {
  * what the workspace query returns).  KFAC_F32_BF16X3 takes float32 input,
  * writes its three bfloat16 terms into the workspace (6 bytes per element) and
  * accumulates the six bf16 MFMA products of every product in fp32, the five
- * small ones before the large one, 8192 tokens at a time; non-finite inputs
- * give NaN.  Limits: sizes must fit in 31 bits;
+ * small ones before the large one, 8192 tokens at a time; KFAC_F32_F16X2
+ * likewise with two float16 terms (4 bytes per element and one word per item)
+ * and three products.  Non-finite inputs give NaN in both.  Limits: sizes must fit in 31 bits;
  * d <= 2^26 for bfloat16 input (KFAC_ERR_UNSUPPORTED beyond).
  */
 kfac_status kfac_curvature(const void *x, kfac_dtype dtype, int64_t n_tokens, int64_t d, int64_t ldx,
