@@ -244,6 +244,15 @@ kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64
                                       void *workspace, size_t workspace_bytes, void *stream);
 size_t kfac_precondition_grouped_workspace(const kfac_precondition_item *items, int64_t count);
 
+/* The same on the f16 matrix core (the method's un-hidden step, section 3.1, made shorter): each of the four
+ * operands (G, B^-1; then T^T, A^-1) is scaled by a power of two from its largest magnitude and taken as two
+ * float16 terms, each product as three f16 MFMA products, fp32 accumulation (see KFAC_F32_F16X2).  Same
+ * arguments, results to the same tolerance; the workspace is larger (T^T, and 4 bytes per element of every
+ * operand).  out must not alias the inputs.  Non-finite inputs give NaN. */
+kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items, int64_t count,
+                                            void *workspace, size_t workspace_bytes, void *stream);
+size_t kfac_precondition_grouped_f16x2_workspace(const kfac_precondition_item *items, int64_t count);
+
 /* ------------------------------------------- bubble filling (host side only)
  * Section 3.1 "Automatic Work Assignments": K-FAC work is taken from a queue
  * and put into the first pipeline bubble that is long enough and lies after the

@@ -54,6 +54,8 @@ SIGNATURES = {
     "kfac_precondition_workspace": (_sz, [_i64, _i64]),
     "kfac_precondition_grouped": (ctypes.c_int, [ctypes.POINTER(PreconditionItem), _i64, _vp, _sz, _vp]),
     "kfac_precondition_grouped_workspace": (_sz, [ctypes.POINTER(PreconditionItem), _i64]),
+    "kfac_precondition_grouped_f16x2": (ctypes.c_int, [ctypes.POINTER(PreconditionItem), _i64, _vp, _sz, _vp]),
+    "kfac_precondition_grouped_f16x2_workspace": (_sz, [ctypes.POINTER(PreconditionItem), _i64]),
     "kfac_invert_plan_create": (ctypes.c_int, [ctypes.POINTER(InvertItem), _i64, _f32, _vp, _sz, ctypes.POINTER(_vp)]),
     "kfac_invert_plan_steps": (_i64, [_vp]),
     "kfac_invert_plan_position": (_i64, [_vp]),
@@ -269,18 +271,22 @@ def kfac_precondition(b_inv, a_inv, grad, out, workspace=None, stream=None):
     return out
 
 
-def kfac_precondition_grouped_workspace(b_invs, a_invs, grads, outs):
+def kfac_precondition_grouped_workspace(b_invs, a_invs, grads, outs, f16x2=False):
     arr = _prec_items(b_invs, a_invs, grads, outs)
-    return int(load().kfac_precondition_grouped_workspace(arr, len(grads)))
+    lib = load()
+    query = lib.kfac_precondition_grouped_f16x2_workspace if f16x2 else lib.kfac_precondition_grouped_workspace
+    return int(query(arr, len(grads)))
 
 
-def kfac_precondition_grouped(b_invs, a_invs, grads, outs, workspace=None, stream=None):
-    """All layers of a stage in two launches."""
+def kfac_precondition_grouped(b_invs, a_invs, grads, outs, workspace=None, stream=None, f16x2=False):
+    """All layers of a stage in two launches (f16x2: operands as two float16 terms on the f16 MFMA)."""
     lib = load()
     arr = _prec_items(b_invs, a_invs, grads, outs)
-    need = lib.kfac_precondition_grouped_workspace(arr, len(grads))
+    query = lib.kfac_precondition_grouped_f16x2_workspace if f16x2 else lib.kfac_precondition_grouped_workspace
+    run = lib.kfac_precondition_grouped_f16x2 if f16x2 else lib.kfac_precondition_grouped
+    need = query(arr, len(grads))
     ws, nbytes, keep = _workspace(need, grads[0], workspace, stream)
-    _check(lib.kfac_precondition_grouped(arr, len(grads), ws, nbytes, _stream(stream)))
+    _check(run(arr, len(grads), ws, nbytes, _stream(stream)))
     return outs
 
 

@@ -214,6 +214,30 @@ inline int pack_groups(int64_t n) { return (int)align_up((size_t)std::max<int64_
 inline int pack_cols(int64_t d) { return (int)align_up((size_t)d, B2_TILE); }
 inline size_t pack_bytes(int64_t n, int64_t d) { return align_up((size_t)pack_groups(n) * pack_cols(d) * 16, WS_ALIGN); }
 
+// The three launches that turn float32 tensors into their two float16 planes (split2_syrk256.h): sp.it[0 .. count),
+// sp.count and sp.amax are filled in by the caller.
+kfac_status split2_prepass(hipStream_t st, Split2Launch &sp)
+{
+    int64_t wg_amax = 0, wg_pack = 0;
+    int first_pack[PACK_MAX_ITEMS + 1];
+    const int n = sp.count;
+    for (int i = 0; i < n; ++i) {
+        const Split2Item &si = sp.it[i];
+        sp.first_wg[i] = (int)wg_amax;
+        first_pack[i] = (int)wg_pack;
+        wg_amax += (int64_t)(si.dp / S2P_COLS) * ((si.gp + S2A_GROUPS - 1) / S2A_GROUPS);
+        wg_pack += (int64_t)(si.dp / S2P_COLS) * si.gp;
+        if (wg_pack > INT32_MAX) return KFAC_ERR_UNSUPPORTED;  // more workgroups than a grid holds
+    }
+    sp.first_wg[n] = (int)wg_amax;
+    first_pack[n] = (int)wg_pack;
+    hipLaunchKernelGGL(split2_clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, sp.amax, n);
+    hipLaunchKernelGGL(split2_amax_kernel, dim3((unsigned)wg_amax), dim3(256), 0, st, sp);
+    std::memcpy(sp.first_wg, first_pack, sizeof(int) * (size_t)(n + 1));
+    hipLaunchKernelGGL(split2_pack_kernel, dim3((unsigned)wg_pack), dim3(256), 0, st, sp);
+    return hipGetLastError() == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
+}
+
 bool curvature_plan(const kfac_curvature_item *items, int64_t count, kfac_dtype dtype, CurvPlan &pl)
 {
     int64_t tiles = 0, kmin = INT64_MAX;
@@ -629,8 +653,6 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
             Syrk256LaunchScaled ls;
             std::memset(&sp, 0, sizeof(sp));
             std::memset(&ls, 0, sizeof(ls));
-            int64_t wg_amax = 0, wg_pack = 0;
-            int first_pack[PACK_MAX_ITEMS + 1];
             for (int64_t i = 0; i < n; ++i) {
                 const kfac_curvature_item &it = items[done + i];
                 Split2Item &si = sp.it[i];
@@ -642,20 +664,11 @@ kfac_status kfac_curvature_grouped(const kfac_curvature_item *items, int64_t cou
                 si.dp = pack_cols(it.d);
                 si.gp = pack_groups(it.n_tokens);
                 pack += S2_PLANES * pack_bytes(it.n_tokens, it.d);
-                sp.first_wg[i] = (int)wg_amax;
-                first_pack[i] = (int)wg_pack;
-                wg_amax += (int64_t)(si.dp / S2P_COLS) * ((si.gp + S2A_GROUPS - 1) / S2A_GROUPS);
-                wg_pack += (int64_t)(si.dp / S2P_COLS) * si.gp;
-                if (wg_pack > INT32_MAX) return KFAC_ERR_UNSUPPORTED;  // more workgroups than a grid holds
             }
-            sp.first_wg[n] = (int)wg_amax;
-            first_pack[n] = (int)wg_pack;
             sp.count = (int)n;
             sp.amax = amax + done;
-            hipLaunchKernelGGL(split2_clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, sp.amax, (int)n);
-            hipLaunchKernelGGL(split2_amax_kernel, dim3((unsigned)wg_amax), dim3(256), 0, st, sp);
-            std::memcpy(sp.first_wg, first_pack, sizeof(int) * (size_t)(n + 1));
-            hipLaunchKernelGGL(split2_pack_kernel, dim3((unsigned)wg_pack), dim3(256), 0, st, sp);
+            const kfac_status pre = split2_prepass(st, sp);
+            if (pre != KFAC_OK) return pre;
             // chunks of S3_CHUNK_GROUPS k-groups, as for the three-term split below
             int gmax2 = 0;
             for (int64_t i = 0; i < n; ++i) gmax2 = std::max(gmax2, sp.it[i].gp);
@@ -1351,6 +1364,153 @@ kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64
             if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
             done += n;
         }
+    }
+    return KFAC_OK;
+}
+
+// Workspace of the two-float16-term precondition: one word per operand for its largest magnitude (four per
+// layer), T^T in float32, then the planes of G, B^-1, A^-1 and T^T of every layer.
+namespace {
+struct PrecSplitPlan {
+    size_t amax_bytes, t_bytes, ws;
+};
+inline size_t planes2_bytes(int64_t rows, int64_t cols) { return S2_PLANES * pack_bytes(rows, cols); }
+bool precondition_split_plan(const kfac_precondition_item *items, int64_t count, PrecSplitPlan &pl)
+{
+    pl.amax_bytes = align_up((size_t)count * 4 * sizeof(unsigned), WS_ALIGN);
+    pl.t_bytes = 0;
+    size_t planes = 0;
+    for (int64_t i = 0; i < count; ++i) {
+        const int64_t dout = items[i].d_out, din = items[i].d_in;
+        if (!fits_int(dout) || !fits_int(din) || dout <= 0 || din <= 0) return false;
+        pl.t_bytes += align_up((size_t)din * dout * sizeof(float), WS_ALIGN);
+        planes += planes2_bytes(dout, din) + planes2_bytes(dout, dout) + planes2_bytes(din, din) + planes2_bytes(din, dout);
+    }
+    pl.ws = pl.amax_bytes + pl.t_bytes + planes;
+    return true;
+}
+}  // namespace
+
+size_t kfac_precondition_grouped_f16x2_workspace(const kfac_precondition_item *items, int64_t count)
+{
+    if (items == nullptr || count <= 0) return 0;
+    PrecSplitPlan pl;
+    if (!precondition_split_plan(items, count, pl)) return 0;
+    return pl.ws;
+}
+
+kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items, int64_t count,
+                                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count == 0) return KFAC_OK;
+    if (items == nullptr || count < 0) return KFAC_ERR_ARG;
+    for (int64_t i = 0; i < count; ++i) {
+        const kfac_precondition_item &it = items[i];
+        if (!it.b_inv || !it.a_inv || !it.grad || !it.out) return KFAC_ERR_ARG;
+        if (!fits_int(it.d_out) || !fits_int(it.d_in) || it.d_out <= 0 || it.d_in <= 0) return KFAC_ERR_ARG;
+        if (it.ldb < it.d_out || it.lda < it.d_in || it.ldg < it.d_in || it.ldo < it.d_in) return KFAC_ERR_ARG;
+        if (!fits_int(it.ldb) || !fits_int(it.lda) || !fits_int(it.ldg) || !fits_int(it.ldo)) return KFAC_ERR_ARG;
+        if ((reinterpret_cast<uintptr_t>(it.b_inv) & 3) || (reinterpret_cast<uintptr_t>(it.a_inv) & 3) ||
+            (reinterpret_cast<uintptr_t>(it.grad) & 3) || (reinterpret_cast<uintptr_t>(it.out) & 3))
+            return KFAC_ERR_ARG;
+        if (it.d_out > (1 << 26) || it.d_in > (1 << 26)) return KFAC_ERR_UNSUPPORTED;  // 32-bit byte offsets in packed rows
+    }
+    PrecSplitPlan pl;
+    if (!precondition_split_plan(items, count, pl)) return KFAC_ERR_ARG;
+    if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned *amax = static_cast<unsigned *>(workspace);
+    char *tcur = static_cast<char *>(workspace) + pl.amax_bytes;
+    char *pcur = tcur + pl.t_bytes;
+
+    // layers in groups of 40: two operands per layer and product fill one pre-pass launch (80 items)
+    constexpr int64_t GROUP = PACK_MAX_ITEMS / 2;
+    static_assert(GROUP <= GEMM2_MAX_PROBLEMS, "a group of layers is one launch of the product kernel");
+    for (int64_t done = 0; done < count; done += GROUP) {
+        const int n = (int)std::min<int64_t>(GROUP, count - done);
+        unsigned *am = amax + 4 * done;  // per layer: G, B^-1, T^T, A^-1
+        float *tt[GROUP];
+        const char *pl_g[GROUP], *pl_b[GROUP], *pl_a[GROUP], *pl_t[GROUP];
+        auto item = [](Split2Item &si, const float *x, int64_t rows, int64_t cols, int64_t ld, char *dst) {
+            si.x = x;
+            si.dst = reinterpret_cast<unsigned short *>(dst);
+            si.n = (int)rows;
+            si.d = (int)cols;
+            si.ldx = (int)ld;
+            si.dp = pack_cols(cols);
+            si.gp = pack_groups(rows);
+        };
+        // T^T = G^T B^-1  (d_in x d_out): contraction over the rows of G and of B^-1
+        Split2Launch sp;
+        Gemm2Launch gl;
+        std::memset(&sp, 0, sizeof(sp));
+        std::memset(&gl, 0, sizeof(gl));
+        int tiles = 0;
+        for (int i = 0; i < n; ++i) {
+            const kfac_precondition_item &it = items[done + i];
+            const int64_t dout = it.d_out, din = it.d_in;
+            tt[i] = reinterpret_cast<float *>(tcur);
+            tcur += align_up((size_t)din * dout * sizeof(float), WS_ALIGN);
+            pl_g[i] = pcur; pcur += planes2_bytes(dout, din);
+            pl_b[i] = pcur; pcur += planes2_bytes(dout, dout);
+            pl_a[i] = pcur; pcur += planes2_bytes(din, din);
+            pl_t[i] = pcur; pcur += planes2_bytes(din, dout);
+            item(sp.it[2 * i], it.grad, dout, din, it.ldg, const_cast<char *>(pl_g[i]));
+            item(sp.it[2 * i + 1], it.b_inv, dout, dout, it.ldb, const_cast<char *>(pl_b[i]));
+            Gemm2Problem &q = gl.p[i];
+            q.xa = pl_g[i];
+            q.xb = pl_b[i];
+            q.c = tt[i];
+            q.m = (int)din;
+            q.n = (int)dout;
+            q.groups = pack_groups(dout);
+            q.dpa = pack_cols(din);
+            q.dpb = pack_cols(dout);
+            q.ldc = (int)dout;
+            q.tile_begin = tiles;
+            q.amax_a = 2 * i;
+            q.amax_b = 2 * i + 1;
+            tiles += gemm2_tiles(q.m, q.n);
+        }
+        sp.count = 2 * n;
+        sp.amax = am;
+        kfac_status pre = split2_prepass(st, sp);
+        if (pre != KFAC_OK) return pre;
+        gl.count = n;
+        gl.amax = am;
+        hipLaunchKernelGGL(gemm_tn_split2_256_kernel, dim3(tiles), dim3(256), 0, st, gl);
+        // out = (T^T)^T A^-1  (d_out x d_in): contraction over the rows of T^T and of A^-1
+        std::memset(&sp, 0, sizeof(sp));
+        std::memset(&gl, 0, sizeof(gl));
+        tiles = 0;
+        for (int i = 0; i < n; ++i) {
+            const kfac_precondition_item &it = items[done + i];
+            const int64_t dout = it.d_out, din = it.d_in;
+            item(sp.it[2 * i], tt[i], din, dout, dout, const_cast<char *>(pl_t[i]));
+            item(sp.it[2 * i + 1], it.a_inv, din, din, it.lda, const_cast<char *>(pl_a[i]));
+            Gemm2Problem &q = gl.p[i];
+            q.xa = pl_t[i];
+            q.xb = pl_a[i];
+            q.c = it.out;
+            q.m = (int)dout;
+            q.n = (int)din;
+            q.groups = pack_groups(din);
+            q.dpa = pack_cols(dout);
+            q.dpb = pack_cols(din);
+            q.ldc = (int)it.ldo;
+            q.tile_begin = tiles;
+            q.amax_a = 2 * i;
+            q.amax_b = 2 * i + 1;
+            tiles += gemm2_tiles(q.m, q.n);
+        }
+        sp.count = 2 * n;
+        sp.amax = am + 2 * n;
+        pre = split2_prepass(st, sp);
+        if (pre != KFAC_OK) return pre;
+        gl.count = n;
+        gl.amax = am + 2 * n;
+        hipLaunchKernelGGL(gemm_tn_split2_256_kernel, dim3(tiles), dim3(256), 0, st, gl);
+        if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
     }
     return KFAC_OK;
 }

@@ -169,9 +169,9 @@ __device__ __forceinline__ void s2_mainloop(const SyrkProblem &pr, int m0, int n
     const int groups = pr.n / BF_KG;
     const char *pa = static_cast<const char *>(pr.x);
     const char *pb = pa + (size_t)pr.pad_ * row_bytes;
-    s3_pass_planes<MODE, true>(pa, pb, row_bytes, groups, m0, n0, lds_a, lds_b, acc);  // a b'
+    s3_pass_planes<MODE, true>(pa, pb, row_bytes, row_bytes, groups, m0, n0, lds_a, lds_b, acc);  // a b'
     __syncthreads();
-    s3_pass_planes<MODE, true>(pb, pa, row_bytes, groups, m0, n0, lds_a, lds_b, acc);  // b a'
+    s3_pass_planes<MODE, true>(pb, pa, row_bytes, row_bytes, groups, m0, n0, lds_a, lds_b, acc);  // b a'
     if (MODE != S3_WAVE_IDLE) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -181,7 +181,7 @@ __device__ __forceinline__ void s2_mainloop(const SyrkProblem &pr, int m0, int n
                 for (int r = 0; r < 16; ++r) acc[i][j][r] *= 1.f / (float)(1 << S2_LOW_SHIFT);
     }
     __syncthreads();
-    s3_pass_planes<MODE, true>(pa, pa, row_bytes, groups, m0, n0, lds_a, lds_b, acc);  // a a'
+    s3_pass_planes<MODE, true>(pa, pa, row_bytes, row_bytes, groups, m0, n0, lds_a, lds_b, acc);  // a a'
 }
 
 __global__ __launch_bounds__(256, 1) void curvature_syrk_split2_256_kernel(const Syrk256LaunchScaled ls)
@@ -218,6 +218,94 @@ __global__ __launch_bounds__(256, 1) void curvature_syrk_split2_256_kernel(const
     const float s = split2_scale(ls.amax[ls.amax_index[bt.pi]]);
     const float inv_s2 = (1.f / s) * (1.f / s);  // exact: s is a power of two
     b2_store_batched(acc, pr, ls.l.alpha * inv_s2, ls.l.beta, m0, n0, wm, wn, li, lh, bt.diag);
+}
+
+// ---------------------------------------------------------------------------
+// General product C = A^T B on operands split the same way (both [K, columns] row-major before the split:
+// the layout the precondition's two products have), for kfac_precondition_grouped_f16x2.  256 x 256 tiles of
+// the full output, the same three sweeps, C = acc / (s_A s_B).
+struct Gemm2Problem {
+    const void *xa, *xb;  // plane a of each operand; plane b follows `groups` k-groups later
+    float *c;             // [m, n], ldc
+    int m, n, groups;     // groups: padded K / 8
+    int dpa, dpb;         // padded columns of the operands
+    int ldc;
+    int tile_begin;
+    int amax_a, amax_b;   // index of each operand's largest magnitude
+    int pad_;
+};
+constexpr int GEMM2_MAX_PROBLEMS = 48;
+struct Gemm2Launch {
+    Gemm2Problem p[GEMM2_MAX_PROBLEMS];
+    const unsigned *amax;
+    int count;
+};
+
+__host__ __device__ inline int gemm2_tiles(int m, int n) { return ((m + B2_TILE - 1) / B2_TILE) * ((n + B2_TILE - 1) / B2_TILE); }
+
+__global__ __launch_bounds__(256, 1) void gemm_tn_split2_256_kernel(const Gemm2Launch lp)
+{
+    __shared__ __attribute__((aligned(16))) char lds_a[B2_STAGES * B2_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char lds_b[B2_STAGES * B2_STAGE_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+    const int t = tn_logical_tile(blockIdx.x, gridDim.x);
+    int pi = 0, hi = lp.count;
+    while (hi - pi > 1) {
+        const int mid = (pi + hi) >> 1;
+        if (lp.p[mid].tile_begin <= t)
+            pi = mid;
+        else
+            hi = mid;
+    }
+    const Gemm2Problem &pr = lp.p[pi];
+    const int tn = (pr.n + B2_TILE - 1) / B2_TILE;
+    const int local = t - pr.tile_begin;
+    const int m0 = (local / tn) * B2_TILE, n0 = (local % tn) * B2_TILE;
+
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const size_t rba = (size_t)pr.dpa * 16, rbb = (size_t)pr.dpb * 16;
+    const char *aa = static_cast<const char *>(pr.xa), *ab = aa + (size_t)pr.groups * rba;
+    const char *ba = static_cast<const char *>(pr.xb), *bb = ba + (size_t)pr.groups * rbb;
+    s3_pass_planes<S3_WAVE_FULL, true>(aa, bb, rba, rbb, pr.groups, m0, n0, lds_a, lds_b, acc);
+    __syncthreads();
+    s3_pass_planes<S3_WAVE_FULL, true>(ab, ba, rba, rbb, pr.groups, m0, n0, lds_a, lds_b, acc);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] *= 1.f / (float)(1 << S2_LOW_SHIFT);
+    __syncthreads();
+    s3_pass_planes<S3_WAVE_FULL, true>(aa, ba, rba, rbb, pr.groups, m0, n0, lds_a, lds_b, acc);
+
+    const float sa = split2_scale(lp.amax[pr.amax_a]), sb = split2_scale(lp.amax[pr.amax_b]);
+    const float inv = (1.f / sa) * (1.f / sb);  // exact: powers of two
+    float *__restrict__ C = pr.c;
+    const size_t ldc = (size_t)pr.ldc;
+    // accumulator register r of lane (li, lh) in block (bi, bj): row 32 bi + 8 (r/4) + 4 lh + r%4, column 32 bj + li
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 4; ++bj) {
+            const int n = n0 + wn + 32 * bj + li;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm + 32 * bi + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (m < pr.m && n < pr.n) C[(size_t)m * ldc + n] = inv * acc[bi][bj][r];
+            }
+        }
 }
 
 }  // namespace kfac

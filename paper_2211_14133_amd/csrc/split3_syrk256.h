@@ -335,10 +335,10 @@ __device__ __forceinline__ void s3_pass_small(const SyrkProblem &pr, int m0, int
 typedef _Float16 s3_halfx8 __attribute__((ext_vector_type(8)));
 
 // xa, xb: the plane the row panel / the column panel is taken from (packed layout, `groups` k-groups of
-// `row_bytes`); F16: the planes hold float16 (MFMA 32x32x16 f16) instead of bfloat16.
+// `row_bytes_a` / `row_bytes_b`); F16: the planes hold float16 (MFMA 32x32x16 f16) instead of bfloat16.
 template <int MODE, bool F16>
-__device__ __forceinline__ void s3_pass_planes(const char *xa, const char *xb, size_t row_bytes, int groups, int m0, int n0,
-                                               const char *lds_a, const char *lds_b, floatx16 (&acc)[4][4])
+__device__ __forceinline__ void s3_pass_planes(const char *xa, const char *xb, size_t row_bytes_a, size_t row_bytes_b, int groups,
+                                               int m0, int n0, const char *lds_a, const char *lds_b, floatx16 (&acc)[4][4])
 {
     constexpr bool IDLE = MODE == S3_WAVE_IDLE, LOWER = MODE == S3_WAVE_LOWER;
     const int tid = threadIdx.x;
@@ -366,9 +366,9 @@ __device__ __forceinline__ void s3_pass_planes(const char *xa, const char *xb, s
     // wave w fetches k-group gd + w: the 256 columns of each operand in four 64-column pieces
 #define H2_DBASE()                                                                         \
     do {                                                                                   \
-        const size_t o_ = (size_t)min(gd + wave_s, groups - 1) * row_bytes;                \
-        sbase_a = xa + o_;                                                                 \
-        sbase_b = xb + o_;                                                                 \
+        const size_t g_ = (size_t)min(gd + wave_s, groups - 1);                            \
+        sbase_a = xa + g_ * row_bytes_a;                                                   \
+        sbase_b = xb + g_ * row_bytes_b;                                                   \
         gd += BF_SLAB_GROUPS;                                                              \
     } while (0)
 #define H2_D1(st, w)                                                                                           \
@@ -480,7 +480,7 @@ __device__ __forceinline__ void s3_mainloop(const SyrkProblem &pr, int m0, int n
     s3_pass_small<MODE>(pr, m0, n0, lds_a, lds_b, acc);
     __syncthreads();  // every wave has read its last fragments of pass 1 (and waited for its own loads)
     const char *h = static_cast<const char *>(pr.x);  // plane 0
-    s3_pass_planes<MODE, false>(h, h, (size_t)pr.ldx * 16, pr.n / BF_KG, m0, n0, lds_a, lds_b, acc);
+    s3_pass_planes<MODE, false>(h, h, (size_t)pr.ldx * 16, (size_t)pr.ldx * 16, pr.n / BF_KG, m0, n0, lds_a, lds_b, acc);
 }
 
 __global__ __launch_bounds__(256, 1) void curvature_syrk_split3_256_kernel(const Syrk256Launch lp)

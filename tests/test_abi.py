@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "kfac.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(kfac_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(kfac_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported_and_bound():
@@ -76,6 +76,9 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.kfac_precondition(None, 8, 8, fake, 4, 4, fake, 4, fake, 4, fake, 1 << 20, None) == ERR_ARG
     assert lib.kfac_precondition(fake, 8, 8, fake, 4, 4, fake, 3, fake, 4, fake, 1 << 20, None) == ERR_ARG
     assert lib.kfac_precondition(fake, 8, 8, fake, 4, 4, fake, 4, fake, 4, None, 0, None) == ERR_WS
+    assert lib.kfac_precondition_grouped_f16x2(None, 1, fake, 1 << 20, None) == ERR_ARG
+    assert lib.kfac_precondition_grouped_f16x2(None, 0, None, 0, None) == 0
+    assert lib.kfac_precondition_grouped_f16x2_workspace(None, 0) == 0
     # empty groups are fine
     assert lib.kfac_curvature_grouped(None, 0, 0, 1.0, 0.0, None, 0, None) == 0
     assert lib.kfac_invert_batched(None, 0, 0.1, None, 0, None) == 0

@@ -1027,3 +1027,71 @@ def test_curvature_split_modes_propagate_non_finite_inputs(k):
             k.kfac_curvature_grouped(xs, fs, 1.0 / n, 0.0, split_bf16=mode)
             assert not bool(torch.isfinite(fs[0][100, :]).any()) and not bool(torch.isfinite(fs[0][:, 100]).any())
             assert bool(torch.isfinite(fs[1]).all())
+
+
+# ------------------------------------- precondition with operands as two float16 terms (f16 MFMA)
+
+@pytest.mark.parametrize("d_out,d_in", [(64, 64), (2, 3), (5, 7), (130, 257), (768, 300), (256, 1024), (1024, 1024), (1100, 2300)])
+def test_precondition_f16x2_parity(k, oracle, d_out, d_in):
+    print("precondition f16x2 %dx%d" % (d_out, d_in), flush=True)
+    rng = np.random.default_rng(d_out * 7 + d_in)
+    b = rng.standard_normal((d_out, d_out)).astype(np.float32)
+    b = (b + b.T) / 2
+    a = rng.standard_normal((d_in, d_in)).astype(np.float32)
+    a = (a + a.T) / 2
+    g = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    buf = torch.full((d_out, d_in + 5), 7.0, device="cuda")
+    out = buf[:, :d_in]
+    k.kfac_precondition_grouped([dev(b)], [dev(a)], [dev(g)], [out], f16x2=True)
+    want = oracle.precondition(b, g, a)
+    err = oracle.rel_fro(host(out), want)
+    print("  rel_fro", err, flush=True)
+    assert err <= 2e-6
+    assert float(buf[:, d_in:].min()) == 7.0  # nothing written past the row
+
+
+def test_precondition_f16x2_many_ragged_problems_and_scales(k, oracle):
+    """More layers than one group of launches takes (40), ragged sizes, operands of very different magnitude
+    (inverses of order 1e3 next to gradients of order 1e-6)."""
+    shapes = [(1000, 1300), (700, 2100), (384, 520)] + [(130, 257), (65, 129), (257, 130)] * 14
+    rng = np.random.default_rng(4)
+    bs, as_, gs = [], [], []
+    for i, (do, di) in enumerate(shapes):
+        b = rng.standard_normal((do, do)).astype(np.float32)
+        a = rng.standard_normal((di, di)).astype(np.float32)
+        bs.append(((b + b.T) / 2 * np.float32(1e3)).astype(np.float32))
+        as_.append(((a + a.T) / 2 * np.float32(10.0 ** (i % 5 - 2))).astype(np.float32))
+        gs.append((rng.standard_normal((do, di)) * 1e-6).astype(np.float32))
+    outs = [torch.full((do, di), 7.0, device="cuda") for do, di in shapes]
+    k.kfac_precondition_grouped([dev(b) for b in bs], [dev(a) for a in as_], [dev(g) for g in gs], outs, f16x2=True)
+    worst = 0.0
+    for b, a, g, o in zip(bs, as_, gs, outs):
+        worst = max(worst, oracle.rel_fro(host(o), oracle.precondition(b, g, a)))
+    print("  %d problems, worst rel_fro %.2e" % (len(shapes), worst), flush=True)
+    assert worst <= 2e-6
+
+
+def test_chain_config3_with_f16x2_curvature_and_precondition(k, oracle):
+    """The feed-forward layers of the BERT-Large block through both float16-term paths: factors, fp32 inversion,
+    preconditioned gradient against the oracle's chain."""
+    c = synth.CONFIGS[3]
+    n = c["tokens"]
+    lay = [(li, l) for li, l in enumerate(c["layers"]) if l[0] in ("ffn1", "ffn2")]
+    xs, es, gs = [], [], []
+    for li, (name, d_in, d_out, gelu) in lay:
+        xs.append(synth.activations(3, 0, li, 0, n, d_in, gelu=gelu))
+        es.append(synth.errors(3, 0, li, 0, n, d_out))
+        gs.append(synth.weight_gradient([es[-1]], [xs[-1]]))
+    ins = [dev(x) for x in xs] + [dev(e) for e in es]
+    facs = [torch.empty(t.shape[1], t.shape[1], device="cuda") for t in ins]
+    k.kfac_curvature_grouped(ins, facs, 1.0 / n, 0.0, split_bf16="f16x2")
+    invs = [torch.empty_like(f) for f in facs]
+    infos = k.kfac_invert_batched(facs, synth.DAMPING, invs)
+    assert int(infos.abs().max()) == 0
+    ps = [torch.empty(l[1][2], l[1][1], device="cuda") for l in lay]
+    k.kfac_precondition_grouped([invs[2], invs[3]], [invs[0], invs[1]], [dev(g) for g in gs], ps, f16x2=True)
+    for i, (li, (name, d_in, d_out, gelu)) in enumerate(lay):
+        op = oracle.kfac_chain([xs[i]], [es[i]], gs[i], synth.DAMPING)[4]
+        ep = oracle.rel_fro(host(ps[i]), op)
+        print("cfg 3 %-5s f16x2 curvature and precondition: P %.2e" % (name, ep), flush=True)
+        assert ep <= PRECOND_TOL
