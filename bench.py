@@ -51,6 +51,10 @@ def parse():
                          "KFAC_F32_F16X2 (every tensor scaled by a power of two, every value as two float16 terms, three f16 MFMA "
                          "products per product); fp32 accumulation in both; the default line reports both variants' curvature "
                          "times in blocks of their own either way")
+    ap.add_argument("--precondition", choices=["f32", "split_f16"], default="f32",
+                    help="split_f16: the precondition with its operands as two float16 terms on the f16 MFMA "
+                         "(kfac_precondition_grouped_f16x2) instead of the fp32 MFMA; the default line reports this variant's "
+                         "time in a block of its own either way")
     ap.add_argument("--phase", choices=["all", "curvature", "inversion", "precondition"], default="all",
                     help="for profiling: after one full untimed step, time only this phase (prints a short JSON "
                          "line that is not the benchmark line)")
@@ -129,9 +133,14 @@ def main():
     inv_items = binding._inv_items(facs, invs, infos)
     prec_items = binding._prec_items(b_invs, a_invs, grads, outs)
     nfac, nlay = len(facs), len(grads)
+    prec_split = args.precondition == "split_f16"
+    if prec_split and args.streams == 2:
+        raise SystemExit("--precondition split_f16 is measured on one stream")
+    prec_call = lib.kfac_precondition_grouped_f16x2 if prec_split else lib.kfac_precondition_grouped
+    prec_ws = lib.kfac_precondition_grouped_f16x2_workspace if prec_split else lib.kfac_precondition_grouped_workspace
     ws_bytes = max(lib.kfac_curvature_grouped_workspace(curv_items[0], nfac, in_dtype),
                    lib.kfac_invert_batched_workspace(inv_items, nfac),
-                   lib.kfac_precondition_grouped_workspace(prec_items, nlay))
+                   prec_ws(prec_items, nlay))
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
     ws_ptr = (ws.data_ptr() + 255) // 256 * 256
     import ctypes
@@ -196,7 +205,7 @@ def main():
         check(lib.kfac_invert_batched(inv_items, nfac, damping, wsp, ws_bytes, sp))
         if events is not None:
             events["t2"].record(stream)
-        check(lib.kfac_precondition_grouped(prec_items, nlay, wsp, ws_bytes, sp))
+        check(prec_call(prec_items, nlay, wsp, ws_bytes, sp))
         if events is not None:
             events["t3"].record(stream)
 
@@ -208,7 +217,7 @@ def main():
         elif which == "inversion":
             check(lib.kfac_invert_batched(inv_items, nfac, damping, wsp, ws_bytes, sp))
         else:
-            check(lib.kfac_precondition_grouped(prec_items, nlay, wsp, ws_bytes, sp))
+            check(prec_call(prec_items, nlay, wsp, ws_bytes, sp))
 
     if args.phase != "all":
         step()  # every buffer the phase reads holds real data
@@ -371,6 +380,10 @@ def main():
             torch, binding, lib, check, xs, facs, n_micro, alpha, sp, stream, curv_ms, inv_ms, prec_ms, f_curv,
             binding.KFAC_F32_F16X2)
 
+    if not prec_split and args.streams == 1:
+        result["precondition_f32_as_2xf16"] = split_precondition_variant(
+            torch, lib, check, prec_items, outs, nlay, sp, stream, prec_ms, f_prec)
+
     if args.streams == 2:
         # the two phases overlap: report their sum, and none of the blocks that need them separately
         both = inv_ms + prec_ms
@@ -385,14 +398,28 @@ def main():
     # run here): they are the stage's forward GEMM flops at the rate this engine reaches on the
     # precondition products, and twice that.
     f_fwd = sum(2 * tokens * di * do for (di, do) in layers)
-    t_f = f_fwd / (f_prec / (prec_ms * 1e-3)) * 1e3
+    prec_ms_fp32 = prec_ms
+    if prec_split:
+        # the assumed forward / backward passes stay fp32 GEMMs: time the fp32 precondition for their rate
+        need = lib.kfac_precondition_grouped_workspace(prec_items, nlay)
+        if need > ws_bytes:
+            raise RuntimeError("the workspace of the step is smaller than the fp32 precondition's")
+        check(lib.kfac_precondition_grouped(prec_items, nlay, wsp, ws_bytes, sp))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(3):
+            check(lib.kfac_precondition_grouped(prec_items, nlay, wsp, ws_bytes, sp))
+        e1.record(stream)
+        torch.cuda.synchronize()
+        prec_ms_fp32 = e0.elapsed_time(e1) / 3
+    t_f = f_fwd / (f_prec / (prec_ms_fp32 * 1e-3)) * 1e3
     t_b = 2.0 * t_f
     depth = 4
     c = n_micro + depth - 1
     model = binding.kfac_perf_model(c, c, t_f, t_b, n_micro, curv_ms / n_micro, inv_ms, prec_ms)
     result["pipefisher_model"] = {
         "assumed": "GPipe, depth %d, %d micro-batches (C_f = C_b = %d); T_f = forward GEMM flops of the stage / "
-                   "measured precondition rate, T_b = 2 T_f (not measured)" % (depth, n_micro, c),
+                   "measured rate of the fp32 precondition, T_b = 2 T_f (not measured)" % (depth, n_micro, c),
         "t_f_ms": round(t_f, 3), "t_b_ms": round(t_b, 3),
         "t_pipe_ms": round(model["t_pipe"], 3), "t_bubble_ms": round(model["t_bubble"], 3),
         "t_kfac_ms": round(model["t_kfac"], 3),
@@ -465,6 +492,38 @@ def split_curvature_variant(torch, binding, lib, check, xs, facs, n_micro, alpha
         "mfma_16bit_tflops": round(products * f_curv / (ms * 1e-3) / 1e12, 1),
         "frac_of_16bit_mfma_peak": round(products * f_curv / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
         "rel_fro_difference_from_fp32_path": {"d=%d" % facs[i].shape[0]: float("%.3g" % diff[i]) for i in diff},
+    }
+
+
+def split_precondition_variant(torch, lib, check, prec_items, outs, nlay, sp, stream, prec_ms, f_prec):
+    """The precondition of the same step with its operands as two float16 terms on the f16 MFMA
+    (kfac_precondition_grouped_f16x2), timed with HIP events, and how far its result is from the fp32 MFMA path's."""
+    import ctypes
+
+    need = lib.kfac_precondition_grouped_f16x2_workspace(prec_items, nlay)
+    ws = torch.empty(need + 256, dtype=torch.uint8, device=outs[0].device)
+    wsp = ctypes.c_void_p((ws.data_ptr() + 255) // 256 * 256)
+    ref = [o.clone() for o in outs]  # what the timed steps left
+    check(lib.kfac_precondition_grouped_f16x2(prec_items, nlay, wsp, need, sp))
+    torch.cuda.synchronize()
+    reps = 5
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        check(lib.kfac_precondition_grouped_f16x2(prec_items, nlay, wsp, need, sp))
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    diff = max(float((o.double() - r.double()).norm() / r.double().norm()) for o, r in zip(outs, ref))
+    for o, r in zip(outs, ref):
+        o.copy_(r)
+    return {
+        "what": "precondition of the same step with --precondition split_f16 (kfac_precondition_grouped_f16x2): operands as two "
+                "float16 terms, three f16 MFMA products per product, fp32 accumulation; not part of `value`",
+        "precondition_ms": round(ms, 3),
+        "speedup_over_fp32_mfma_precondition": round(prec_ms / ms, 3),
+        "useful_tflops": round(f_prec / (ms * 1e-3) / 1e12, 2),
+        "largest_rel_fro_difference_from_fp32_path": float("%.3g" % diff),
     }
 
 
