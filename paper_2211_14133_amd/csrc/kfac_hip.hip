@@ -1391,6 +1391,20 @@ bool precondition_split_plan(const kfac_precondition_item *items, int64_t count,
 }
 }  // namespace
 
+namespace {
+// Problems by decreasing K (stable), tile ranges renumbered: see gemm2_tile_of.
+void gemm2_order(Gemm2Launch &gl)
+{
+    std::stable_sort(gl.p, gl.p + gl.count, [](const Gemm2Problem &a, const Gemm2Problem &b) { return a.groups > b.groups; });
+    int tiles = 0;
+    for (int i = 0; i < gl.count; ++i) {
+        gl.p[i].tile_begin = tiles;
+        tiles += gemm2_tiles(gl.p[i].m, gl.p[i].n);
+    }
+    gl.total_tiles = tiles;
+}
+}  // namespace
+
 size_t kfac_precondition_grouped_f16x2_workspace(const kfac_precondition_item *items, int64_t count)
 {
     if (items == nullptr || count <= 0) return 0;
@@ -1478,7 +1492,8 @@ kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items,
         if (pre != KFAC_OK) return pre;
         gl.count = n;
         gl.amax = am;
-        hipLaunchKernelGGL(gemm_tn_split2_256_kernel, dim3(tiles), dim3(256), 0, st, gl);
+        gemm2_order(gl);
+        hipLaunchKernelGGL(gemm_tn_split2_256_kernel, dim3(gemm2_grid(gl)), dim3(256), 0, st, gl);
         // out = (T^T)^T A^-1  (d_out x d_in): contraction over the rows of T^T and of A^-1
         std::memset(&sp, 0, sizeof(sp));
         std::memset(&gl, 0, sizeof(gl));
@@ -1509,7 +1524,8 @@ kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items,
         if (pre != KFAC_OK) return pre;
         gl.count = n;
         gl.amax = am + 2 * n;
-        hipLaunchKernelGGL(gemm_tn_split2_256_kernel, dim3(tiles), dim3(256), 0, st, gl);
+        gemm2_order(gl);
+        hipLaunchKernelGGL(gemm_tn_split2_256_kernel, dim3(gemm2_grid(gl)), dim3(256), 0, st, gl);
         if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
     }
     return KFAC_OK;

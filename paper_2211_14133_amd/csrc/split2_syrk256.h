@@ -238,8 +238,47 @@ constexpr int GEMM2_MAX_PROBLEMS = 48;
 struct Gemm2Launch {
     Gemm2Problem p[GEMM2_MAX_PROBLEMS];
     const unsigned *amax;
-    int count;
+    int count, total_tiles;
 };
+
+// Which tile a workgroup takes: XCD x (workgroups go round the eight XCDs) takes an eighth of the tiles of every
+// problem, problem after problem, the eighth rotating from problem to problem.  The problems differ in K (the
+// layer's width), so every XCD gets the same mix, and with the problems sorted by decreasing K on the host
+// each starts its long tiles first.  -1: surplus workgroup (the grid is 8 x the longest XCD share).
+__host__ __device__ inline int gemm2_share(int n, int xcd, int p, int &lo)
+{
+    const int part = (xcd + p) & 7;
+    lo = (int)((long long)n * part / 8);
+    return (int)((long long)n * (part + 1) / 8) - lo;
+}
+__device__ inline int gemm2_tile_of(const Gemm2Launch &lp, int bid)
+{
+    const int xcd = bid & 7;
+    int q = bid >> 3;
+    for (int p = 0; p < lp.count; ++p) {
+        const int b = lp.p[p].tile_begin;
+        const int n = (p + 1 < lp.count ? lp.p[p + 1].tile_begin : lp.total_tiles) - b;
+        int lo;
+        const int share = gemm2_share(n, xcd, p, lo);
+        if (q < share) return b + lo + q;
+        q -= share;
+    }
+    return -1;
+}
+inline int gemm2_grid(const Gemm2Launch &lp)
+{
+    int longest = 0;
+    for (int x = 0; x < 8; ++x) {
+        int have = 0;
+        for (int p = 0; p < lp.count; ++p) {
+            const int n = (p + 1 < lp.count ? lp.p[p + 1].tile_begin : lp.total_tiles) - lp.p[p].tile_begin;
+            int lo;
+            have += gemm2_share(n, x, p, lo);
+        }
+        longest = have > longest ? have : longest;
+    }
+    return 8 * longest;
+}
 
 __host__ __device__ inline int gemm2_tiles(int m, int n) { return ((m + B2_TILE - 1) / B2_TILE) * ((n + B2_TILE - 1) / B2_TILE); }
 
@@ -253,7 +292,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_split2_256_kernel(const Gemm2L
     const int li = lane & 31, lh = lane >> 5;
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
 
-    const int t = tn_logical_tile(blockIdx.x, gridDim.x);
+    const int t = gemm2_tile_of(lp, blockIdx.x);
+    if (t < 0) return;  // the whole workgroup leaves
     int pi = 0, hi = lp.count;
     while (hi - pi > 1) {
         const int mid = (pi + hi) >> 1;
