@@ -146,6 +146,40 @@ def test_stage_full_size_against_oracle(stage, oracle, capsys, block):
         assert errs["Ainv"] <= 1e-4 and errs["Binv"] <= 1e-5, (li, name, errs)
 
 
+@pytest.mark.parametrize("mode", ["bf16x3", "f16x2"])
+def test_stage_full_size_on_the_16_bit_matrix_cores(stage, mode):
+    """The variants that take the float32 inputs as bfloat16 / float16 terms, at the benchmark's full size and in
+    the launch configuration bench.py times them in, against the fp32-MFMA results of the same stage (which the
+    tests above and below hold against the oracle): every factor, and with the float16 terms every preconditioned
+    gradient (through the variant's own factors and the fp32 inversion)."""
+    import paper_2211_14133_amd as k
+
+    st = stage
+    facs = [torch.empty_like(f) for f in st.facs]
+    for m in range(st.n_micro):
+        k.kfac_curvature_grouped(st.xs[m], facs, st.alpha, 0.0 if m == 0 else 1.0, split_bf16=mode)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for f, r in zip(facs, st.facs):
+        worst = max(worst, float((f.double() - r.double()).norm() / r.double().norm()))
+        assert torch.equal(f, f.t())
+    print("%s: factors differ from the fp32 path's by at most %.3g" % (mode, worst), flush=True)
+    assert worst <= 6e-7
+    if mode != "f16x2":
+        return
+    invs = [torch.empty_like(f) for f in facs]
+    infos = k.kfac_invert_batched(facs, st.lam, invs)
+    outs = [torch.empty_like(g) for g in st.grads]
+    k.kfac_precondition_grouped(invs[1::2], invs[0::2], st.grads, outs, f16x2=True)
+    torch.cuda.synchronize()
+    assert int(infos.abs().max()) == 0
+    worst = 0.0
+    for o, r in zip(outs, st.outs):
+        worst = max(worst, float((o.double() - r.double()).norm() / r.double().norm()))
+    print("%s: preconditioned gradients differ from the fp32 path's by at most %.3g" % (mode, worst), flush=True)
+    assert worst <= 5e-5  # the fp32 path itself is within 7.3e-6 of the oracle on this stage
+
+
 def test_curvature_long_sequence(oracle):
     """The longest micro-batch of the paper's performance-model table (32 x 2048 = 65,536 tokens) at the
     BERT-Large factor sizes: the whole 1024-dimensional factor against the oracle, sampled entries
