@@ -1095,3 +1095,58 @@ def test_chain_config3_with_f16x2_curvature_and_precondition(k, oracle):
         ep = oracle.rel_fro(host(ps[i]), op)
         print("cfg 3 %-5s f16x2 curvature and precondition: P %.2e" % (name, ep), flush=True)
         assert ep <= PRECOND_TOL
+
+
+def test_f16x2_paths_can_be_captured_in_a_graph(k):
+    """The float16-term curvature and precondition enqueue only kernels too (the largest magnitudes are cleared
+    by a kernel and raised with atomics): captured with the fp32 inversion between them, every replay on fresh
+    inputs must equal the eager result bit for bit."""
+    n, d = 256, 3584  # two factors of 105 tiles of 256 x 256: the bf16/f16 path, not the fp32 fallback
+    x = torch.empty(n, d, device="cuda")
+    e = torch.empty(n, d, device="cuda")
+    g = torch.empty(d, d, device="cuda")
+    a, b = torch.empty(d, d, device="cuda"), torch.empty(d, d, device="cuda")
+    ai, bi, p = torch.empty_like(a), torch.empty_like(b), torch.empty_like(g)
+    infos = torch.zeros(2, dtype=torch.int32, device="cuda")
+    need = max(k.kfac_curvature_grouped_workspace([x, e], [a, b], split_bf16="f16x2"),
+               k.kfac_invert_batched_workspace([a, b], [ai, bi]),
+               k.kfac_precondition_grouped_workspace([bi], [ai], [g], [p], f16x2=True))
+    ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+
+    def chain(stream):
+        k.kfac_curvature_grouped([x, e], [a, b], 1.0 / n, 0.0, workspace=ws, stream=stream, split_bf16="f16x2")
+        k.kfac_invert_batched([a, b], synth.DAMPING, [ai, bi], infos=infos, workspace=ws, stream=stream)
+        k.kfac_precondition_grouped([bi], [ai], [g], [p], workspace=ws, stream=stream, f16x2=True)
+
+    gen = torch.Generator(device="cuda")
+
+    def fill(mb):
+        gen.manual_seed(100 + mb)
+        # the scale changes from replay to replay (modestly: n < d, so the damping alone bounds the condition number)
+        x.copy_(torch.randn(n, d, device="cuda", generator=gen) * (1.0, 2.0, 0.5)[mb])
+        e.copy_(torch.randn(n, d, device="cuda", generator=gen) * 1e-3)
+        g.copy_((e.t() @ x) / n)
+
+    fill(0)
+    chain(None)  # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain(torch.cuda.current_stream())
+    for mb in range(3):
+        fill(mb)
+        chain(None)
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (a, b, ai, bi, p)]
+        for t in (a, b, ai, bi, p):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for w, t in zip(want, (a, b, ai, bi, p)):
+            assert torch.equal(w, t)
+        assert int(infos.abs().max()) == 0
+    # (with fewer tokens than features G lies in A's range while A^-1 is largest on its null space: the product
+    # cancels 10^4-fold and no fp32 product is accurate to better than 5e-3 here, on either path; the accuracy
+    # of the paths is the business of the tests above, this one is about replays)
+    assert bool(torch.isfinite(p).all())
