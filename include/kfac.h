@@ -253,6 +253,21 @@ kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items,
                                             void *workspace, size_t workspace_bytes, void *stream);
 size_t kfac_precondition_grouped_f16x2_workspace(const kfac_precondition_item *items, int64_t count);
 
+/* The inverses only change when they are refreshed (every few steps under the schedule of section 3.1), the
+ * gradient every step: their float16 planes can be made once per refresh and used by every precondition until
+ * the next.  kfac_precondition_f16x2_prepare reads b_inv and a_inv of every item (grad and out are ignored) and
+ * fills `prepared` (device memory of the caller, kfac_precondition_f16x2_prepared_bytes, 256-byte aligned);
+ * kfac_precondition_grouped_f16x2_prepared then computes what kfac_precondition_grouped_f16x2 computes, bit for
+ * bit, from `prepared` (made for the same items in the same order), grad and out; its workspace is smaller
+ * (kfac_precondition_grouped_f16x2_prepared_workspace).  `prepared` is only read by it. */
+kfac_status kfac_precondition_f16x2_prepare(const kfac_precondition_item *items, int64_t count,
+                                            void *prepared, size_t prepared_bytes, void *stream);
+size_t kfac_precondition_f16x2_prepared_bytes(const kfac_precondition_item *items, int64_t count);
+kfac_status kfac_precondition_grouped_f16x2_prepared(const kfac_precondition_item *items, int64_t count,
+                                                     const void *prepared, size_t prepared_bytes,
+                                                     void *workspace, size_t workspace_bytes, void *stream);
+size_t kfac_precondition_grouped_f16x2_prepared_workspace(const kfac_precondition_item *items, int64_t count);
+
 /* ------------------------------------------- bubble filling (host side only)
  * Section 3.1 "Automatic Work Assignments": K-FAC work is taken from a queue
  * and put into the first pipeline bubble that is long enough and lies after the

@@ -56,6 +56,10 @@ SIGNATURES = {
     "kfac_precondition_grouped_workspace": (_sz, [ctypes.POINTER(PreconditionItem), _i64]),
     "kfac_precondition_grouped_f16x2": (ctypes.c_int, [ctypes.POINTER(PreconditionItem), _i64, _vp, _sz, _vp]),
     "kfac_precondition_grouped_f16x2_workspace": (_sz, [ctypes.POINTER(PreconditionItem), _i64]),
+    "kfac_precondition_f16x2_prepare": (ctypes.c_int, [ctypes.POINTER(PreconditionItem), _i64, _vp, _sz, _vp]),
+    "kfac_precondition_f16x2_prepared_bytes": (_sz, [ctypes.POINTER(PreconditionItem), _i64]),
+    "kfac_precondition_grouped_f16x2_prepared": (ctypes.c_int, [ctypes.POINTER(PreconditionItem), _i64, _vp, _sz, _vp, _sz, _vp]),
+    "kfac_precondition_grouped_f16x2_prepared_workspace": (_sz, [ctypes.POINTER(PreconditionItem), _i64]),
     "kfac_invert_plan_create": (ctypes.c_int, [ctypes.POINTER(InvertItem), _i64, _f32, _vp, _sz, ctypes.POINTER(_vp)]),
     "kfac_invert_plan_steps": (_i64, [_vp]),
     "kfac_invert_plan_position": (_i64, [_vp]),
@@ -288,6 +292,35 @@ def kfac_precondition_grouped(b_invs, a_invs, grads, outs, workspace=None, strea
     ws, nbytes, keep = _workspace(need, grads[0], workspace, stream)
     _check(run(arr, len(grads), ws, nbytes, _stream(stream)))
     return outs
+
+
+class PreparedInverses:
+    """The float16 planes of the inverses of a stage, made once per refresh; `precondition` then applies them to
+    any number of gradients (kfac_precondition_f16x2_prepare / kfac_precondition_grouped_f16x2_prepared)."""
+
+    def __init__(self, b_invs, a_invs, stream=None):
+        lib = load()
+        self._invs = (list(b_invs), list(a_invs))
+        arr = (PreconditionItem * len(b_invs))()
+        for i, (b, a) in enumerate(zip(b_invs, a_invs)):
+            _need_f32_matrix(b, "b_inv")
+            _need_f32_matrix(a, "a_inv")
+            if b.shape[0] != b.shape[1] or a.shape[0] != a.shape[1]:
+                raise KfacError("the inverses must be square")
+            arr[i] = PreconditionItem(b.data_ptr(), b.shape[0], b.stride(0), a.data_ptr(), a.shape[0], a.stride(0),
+                                      0, a.shape[0], 0, a.shape[0])  # gradient and output are not looked at
+        need = lib.kfac_precondition_f16x2_prepared_bytes(arr, len(b_invs))
+        self._ptr, self._bytes, self._buf = _workspace(need, b_invs[0], None, stream)
+        _check(lib.kfac_precondition_f16x2_prepare(arr, len(b_invs), self._ptr, self._bytes, _stream(stream)))
+
+    def precondition(self, grads, outs, workspace=None, stream=None):
+        lib = load()
+        arr = _prec_items(self._invs[0], self._invs[1], grads, outs)
+        need = lib.kfac_precondition_grouped_f16x2_prepared_workspace(arr, len(grads))
+        ws, nbytes, keep = _workspace(need, grads[0], workspace, stream)
+        _check(lib.kfac_precondition_grouped_f16x2_prepared(arr, len(grads), self._ptr, self._bytes, ws, nbytes,
+                                                            _stream(stream)))
+        return outs
 
 
 class InvertPlan:

@@ -1368,30 +1368,67 @@ kfac_status kfac_precondition_grouped(const kfac_precondition_item *items, int64
     return KFAC_OK;
 }
 
-// Workspace of the two-float16-term precondition: one word per operand for its largest magnitude (four per
-// layer), T^T in float32, then the planes of G, B^-1, A^-1 and T^T of every layer.
+// The two-float16-term precondition.  Two memory regions: the *prepared inverses* (one word per inverse for its
+// largest magnitude, two per layer, then the float16 planes of B^-1 and A^-1 of every layer) and the *workspace*
+// (one word per layer for G and one for T^T, T^T in float32, then the planes of G and T^T).  The inverses only
+// change when they are refreshed, so a caller may prepare them once and precondition many gradients with them
+// (kfac_precondition_f16x2_prepare / kfac_precondition_grouped_f16x2_prepared); kfac_precondition_grouped_f16x2
+// does both in one call, with the prepared region in front of its workspace.
 namespace {
 struct PrecSplitPlan {
-    size_t amax_bytes, t_bytes, ws;
+    size_t prep_amax, prep_bytes;        // prepared inverses
+    size_t ws_amax, t_bytes, ws_bytes;   // workspace of a run on prepared inverses
 };
 inline size_t planes2_bytes(int64_t rows, int64_t cols) { return S2_PLANES * pack_bytes(rows, cols); }
+constexpr int64_t PREC_SPLIT_GROUP = PACK_MAX_ITEMS / 2;  // layers per group of launches: 80 operands per pre-pass
+static_assert(PREC_SPLIT_GROUP <= GEMM2_MAX_PROBLEMS, "a group of layers is one launch of the product kernel");
+
 bool precondition_split_plan(const kfac_precondition_item *items, int64_t count, PrecSplitPlan &pl)
 {
-    pl.amax_bytes = align_up((size_t)count * 4 * sizeof(unsigned), WS_ALIGN);
+    pl.prep_amax = pl.ws_amax = align_up((size_t)count * 2 * sizeof(unsigned), WS_ALIGN);
     pl.t_bytes = 0;
-    size_t planes = 0;
+    size_t inv_planes = 0, run_planes = 0;
     for (int64_t i = 0; i < count; ++i) {
         const int64_t dout = items[i].d_out, din = items[i].d_in;
         if (!fits_int(dout) || !fits_int(din) || dout <= 0 || din <= 0) return false;
         pl.t_bytes += align_up((size_t)din * dout * sizeof(float), WS_ALIGN);
-        planes += planes2_bytes(dout, din) + planes2_bytes(dout, dout) + planes2_bytes(din, din) + planes2_bytes(din, dout);
+        inv_planes += planes2_bytes(dout, dout) + planes2_bytes(din, din);
+        run_planes += planes2_bytes(dout, din) + planes2_bytes(din, dout);
     }
-    pl.ws = pl.amax_bytes + pl.t_bytes + planes;
+    pl.prep_bytes = pl.prep_amax + inv_planes;
+    pl.ws_bytes = pl.ws_amax + pl.t_bytes + run_planes;
     return true;
 }
-}  // namespace
 
-namespace {
+kfac_status precondition_split_check(const kfac_precondition_item *items, int64_t count, bool need_grad)
+{
+    if (items == nullptr || count < 0) return KFAC_ERR_ARG;
+    for (int64_t i = 0; i < count; ++i) {
+        const kfac_precondition_item &it = items[i];
+        if (!it.b_inv || !it.a_inv) return KFAC_ERR_ARG;
+        if (need_grad && (!it.grad || !it.out)) return KFAC_ERR_ARG;
+        if (!fits_int(it.d_out) || !fits_int(it.d_in) || it.d_out <= 0 || it.d_in <= 0) return KFAC_ERR_ARG;
+        if (it.ldb < it.d_out || it.lda < it.d_in || !fits_int(it.ldb) || !fits_int(it.lda)) return KFAC_ERR_ARG;
+        if (need_grad && (it.ldg < it.d_in || it.ldo < it.d_in || !fits_int(it.ldg) || !fits_int(it.ldo))) return KFAC_ERR_ARG;
+        if ((reinterpret_cast<uintptr_t>(it.b_inv) & 3) || (reinterpret_cast<uintptr_t>(it.a_inv) & 3)) return KFAC_ERR_ARG;
+        if (need_grad && ((reinterpret_cast<uintptr_t>(it.grad) & 3) || (reinterpret_cast<uintptr_t>(it.out) & 3)))
+            return KFAC_ERR_ARG;
+        if (it.d_out > (1 << 26) || it.d_in > (1 << 26)) return KFAC_ERR_UNSUPPORTED;  // 32-bit byte offsets in packed rows
+    }
+    return KFAC_OK;
+}
+
+inline void split2_item(Split2Item &si, const float *x, int64_t rows, int64_t cols, int64_t ld, char *dst)
+{
+    si.x = x;
+    si.dst = reinterpret_cast<unsigned short *>(dst);
+    si.n = (int)rows;
+    si.d = (int)cols;
+    si.ldx = (int)ld;
+    si.dp = pack_cols(cols);
+    si.gp = pack_groups(rows);
+}
+
 // Problems by decreasing K (stable), tile ranges renumbered: see gemm2_tile_of.
 void gemm2_order(Gemm2Launch &gl)
 {
@@ -1403,74 +1440,60 @@ void gemm2_order(Gemm2Launch &gl)
     }
     gl.total_tiles = tiles;
 }
-}  // namespace
 
-size_t kfac_precondition_grouped_f16x2_workspace(const kfac_precondition_item *items, int64_t count)
+// Largest magnitudes and planes of B^-1 (word 2 i) and A^-1 (word 2 i + 1) of every layer.
+kfac_status precondition_split_prepare(const kfac_precondition_item *items, int64_t count, const PrecSplitPlan &pl,
+                                       void *prepared, hipStream_t st)
 {
-    if (items == nullptr || count <= 0) return 0;
-    PrecSplitPlan pl;
-    if (!precondition_split_plan(items, count, pl)) return 0;
-    return pl.ws;
+    unsigned *amax = static_cast<unsigned *>(prepared);
+    char *pcur = static_cast<char *>(prepared) + pl.prep_amax;
+    for (int64_t done = 0; done < count; done += PREC_SPLIT_GROUP) {
+        const int n = (int)std::min<int64_t>(PREC_SPLIT_GROUP, count - done);
+        Split2Launch sp;
+        std::memset(&sp, 0, sizeof(sp));
+        for (int i = 0; i < n; ++i) {
+            const kfac_precondition_item &it = items[done + i];
+            split2_item(sp.it[2 * i], it.b_inv, it.d_out, it.d_out, it.ldb, pcur);
+            pcur += planes2_bytes(it.d_out, it.d_out);
+            split2_item(sp.it[2 * i + 1], it.a_inv, it.d_in, it.d_in, it.lda, pcur);
+            pcur += planes2_bytes(it.d_in, it.d_in);
+        }
+        sp.count = 2 * n;
+        sp.amax = amax + 2 * done;
+        const kfac_status pre = split2_prepass(st, sp);
+        if (pre != KFAC_OK) return pre;
+    }
+    return KFAC_OK;
 }
 
-kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items, int64_t count,
-                                            void *workspace, size_t workspace_bytes, void *stream)
+kfac_status precondition_split_run(const kfac_precondition_item *items, int64_t count, const PrecSplitPlan &pl,
+                                   const void *prepared, void *workspace, hipStream_t st)
 {
-    if (count == 0) return KFAC_OK;
-    if (items == nullptr || count < 0) return KFAC_ERR_ARG;
-    for (int64_t i = 0; i < count; ++i) {
-        const kfac_precondition_item &it = items[i];
-        if (!it.b_inv || !it.a_inv || !it.grad || !it.out) return KFAC_ERR_ARG;
-        if (!fits_int(it.d_out) || !fits_int(it.d_in) || it.d_out <= 0 || it.d_in <= 0) return KFAC_ERR_ARG;
-        if (it.ldb < it.d_out || it.lda < it.d_in || it.ldg < it.d_in || it.ldo < it.d_in) return KFAC_ERR_ARG;
-        if (!fits_int(it.ldb) || !fits_int(it.lda) || !fits_int(it.ldg) || !fits_int(it.ldo)) return KFAC_ERR_ARG;
-        if ((reinterpret_cast<uintptr_t>(it.b_inv) & 3) || (reinterpret_cast<uintptr_t>(it.a_inv) & 3) ||
-            (reinterpret_cast<uintptr_t>(it.grad) & 3) || (reinterpret_cast<uintptr_t>(it.out) & 3))
-            return KFAC_ERR_ARG;
-        if (it.d_out > (1 << 26) || it.d_in > (1 << 26)) return KFAC_ERR_UNSUPPORTED;  // 32-bit byte offsets in packed rows
-    }
-    PrecSplitPlan pl;
-    if (!precondition_split_plan(items, count, pl)) return KFAC_ERR_ARG;
-    if (!ws_ok(workspace, workspace_bytes, pl.ws)) return KFAC_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    unsigned *amax = static_cast<unsigned *>(workspace);
-    char *tcur = static_cast<char *>(workspace) + pl.amax_bytes;
+    const unsigned *amax_inv = static_cast<const unsigned *>(prepared);
+    const char *inv_cur = static_cast<const char *>(prepared) + pl.prep_amax;
+    unsigned *amax_run = static_cast<unsigned *>(workspace);  // word 2 i: G of layer i, word 2 i + 1: its T^T
+    char *tcur = static_cast<char *>(workspace) + pl.ws_amax;
     char *pcur = tcur + pl.t_bytes;
-
-    // layers in groups of 40: two operands per layer and product fill one pre-pass launch (80 items)
-    constexpr int64_t GROUP = PACK_MAX_ITEMS / 2;
-    static_assert(GROUP <= GEMM2_MAX_PROBLEMS, "a group of layers is one launch of the product kernel");
-    for (int64_t done = 0; done < count; done += GROUP) {
-        const int n = (int)std::min<int64_t>(GROUP, count - done);
-        unsigned *am = amax + 4 * done;  // per layer: G, B^-1, T^T, A^-1
-        float *tt[GROUP];
-        const char *pl_g[GROUP], *pl_b[GROUP], *pl_a[GROUP], *pl_t[GROUP];
-        auto item = [](Split2Item &si, const float *x, int64_t rows, int64_t cols, int64_t ld, char *dst) {
-            si.x = x;
-            si.dst = reinterpret_cast<unsigned short *>(dst);
-            si.n = (int)rows;
-            si.d = (int)cols;
-            si.ldx = (int)ld;
-            si.dp = pack_cols(cols);
-            si.gp = pack_groups(rows);
-        };
+    for (int64_t done = 0; done < count; done += PREC_SPLIT_GROUP) {
+        const int n = (int)std::min<int64_t>(PREC_SPLIT_GROUP, count - done);
+        float *tt[PREC_SPLIT_GROUP];
+        const char *pl_b[PREC_SPLIT_GROUP], *pl_a[PREC_SPLIT_GROUP];
+        char *pl_g[PREC_SPLIT_GROUP], *pl_t[PREC_SPLIT_GROUP];
         // T^T = G^T B^-1  (d_in x d_out): contraction over the rows of G and of B^-1
         Split2Launch sp;
         Gemm2Launch gl;
         std::memset(&sp, 0, sizeof(sp));
         std::memset(&gl, 0, sizeof(gl));
-        int tiles = 0;
         for (int i = 0; i < n; ++i) {
             const kfac_precondition_item &it = items[done + i];
             const int64_t dout = it.d_out, din = it.d_in;
             tt[i] = reinterpret_cast<float *>(tcur);
             tcur += align_up((size_t)din * dout * sizeof(float), WS_ALIGN);
+            pl_b[i] = inv_cur; inv_cur += planes2_bytes(dout, dout);
+            pl_a[i] = inv_cur; inv_cur += planes2_bytes(din, din);
             pl_g[i] = pcur; pcur += planes2_bytes(dout, din);
-            pl_b[i] = pcur; pcur += planes2_bytes(dout, dout);
-            pl_a[i] = pcur; pcur += planes2_bytes(din, din);
             pl_t[i] = pcur; pcur += planes2_bytes(din, dout);
-            item(sp.it[2 * i], it.grad, dout, din, it.ldg, const_cast<char *>(pl_g[i]));
-            item(sp.it[2 * i + 1], it.b_inv, dout, dout, it.ldb, const_cast<char *>(pl_b[i]));
+            split2_item(sp.it[i], it.grad, dout, din, it.ldg, pl_g[i]);
             Gemm2Problem &q = gl.p[i];
             q.xa = pl_g[i];
             q.xb = pl_b[i];
@@ -1481,28 +1504,27 @@ kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items,
             q.dpa = pack_cols(din);
             q.dpb = pack_cols(dout);
             q.ldc = (int)dout;
-            q.tile_begin = tiles;
-            q.amax_a = 2 * i;
-            q.amax_b = 2 * i + 1;
-            tiles += gemm2_tiles(q.m, q.n);
+            q.amax_a = i;                           // in this group's words for G
+            q.amax_b = (int)(2 * (done + i));       // B^-1 of the layer
         }
-        sp.count = 2 * n;
-        sp.amax = am;
+        // (the pre-pass numbers its items 0 .. n-1: G's words of this group are amax_run[2 done .. 2 done + n),
+        //  T^T's the n words after them)
+        sp.count = n;
+        sp.amax = amax_run + 2 * done;
         kfac_status pre = split2_prepass(st, sp);
         if (pre != KFAC_OK) return pre;
         gl.count = n;
-        gl.amax = am;
+        gl.amax_a = amax_run + 2 * done;
+        gl.amax_b = amax_inv;
         gemm2_order(gl);
         hipLaunchKernelGGL(gemm_tn_split2_256_kernel, dim3(gemm2_grid(gl)), dim3(256), 0, st, gl);
         // out = (T^T)^T A^-1  (d_out x d_in): contraction over the rows of T^T and of A^-1
         std::memset(&sp, 0, sizeof(sp));
         std::memset(&gl, 0, sizeof(gl));
-        tiles = 0;
         for (int i = 0; i < n; ++i) {
             const kfac_precondition_item &it = items[done + i];
             const int64_t dout = it.d_out, din = it.d_in;
-            item(sp.it[2 * i], tt[i], din, dout, dout, const_cast<char *>(pl_t[i]));
-            item(sp.it[2 * i + 1], it.a_inv, din, din, it.lda, const_cast<char *>(pl_a[i]));
+            split2_item(sp.it[i], tt[i], din, dout, dout, pl_t[i]);
             Gemm2Problem &q = gl.p[i];
             q.xa = pl_t[i];
             q.xb = pl_a[i];
@@ -1513,22 +1535,88 @@ kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items,
             q.dpa = pack_cols(dout);
             q.dpb = pack_cols(din);
             q.ldc = (int)it.ldo;
-            q.tile_begin = tiles;
-            q.amax_a = 2 * i;
-            q.amax_b = 2 * i + 1;
-            tiles += gemm2_tiles(q.m, q.n);
+            q.amax_a = i;
+            q.amax_b = (int)(2 * (done + i) + 1);   // A^-1 of the layer
         }
-        sp.count = 2 * n;
-        sp.amax = am + 2 * n;
+        sp.count = n;
+        sp.amax = amax_run + 2 * done + n;
         pre = split2_prepass(st, sp);
         if (pre != KFAC_OK) return pre;
         gl.count = n;
-        gl.amax = am + 2 * n;
+        gl.amax_a = amax_run + 2 * done + n;
+        gl.amax_b = amax_inv;
         gemm2_order(gl);
         hipLaunchKernelGGL(gemm_tn_split2_256_kernel, dim3(gemm2_grid(gl)), dim3(256), 0, st, gl);
         if (hipGetLastError() != hipSuccess) return KFAC_ERR_HIP;
     }
     return KFAC_OK;
+}
+}  // namespace
+
+size_t kfac_precondition_f16x2_prepared_bytes(const kfac_precondition_item *items, int64_t count)
+{
+    if (items == nullptr || count <= 0) return 0;
+    PrecSplitPlan pl;
+    if (!precondition_split_plan(items, count, pl)) return 0;
+    return pl.prep_bytes;
+}
+
+size_t kfac_precondition_grouped_f16x2_prepared_workspace(const kfac_precondition_item *items, int64_t count)
+{
+    if (items == nullptr || count <= 0) return 0;
+    PrecSplitPlan pl;
+    if (!precondition_split_plan(items, count, pl)) return 0;
+    return pl.ws_bytes;
+}
+
+size_t kfac_precondition_grouped_f16x2_workspace(const kfac_precondition_item *items, int64_t count)
+{
+    if (items == nullptr || count <= 0) return 0;
+    PrecSplitPlan pl;
+    if (!precondition_split_plan(items, count, pl)) return 0;
+    return align_up(pl.prep_bytes, WS_ALIGN) + pl.ws_bytes;
+}
+
+kfac_status kfac_precondition_f16x2_prepare(const kfac_precondition_item *items, int64_t count,
+                                            void *prepared, size_t prepared_bytes, void *stream)
+{
+    if (count == 0) return KFAC_OK;
+    const kfac_status chk = precondition_split_check(items, count, false);
+    if (chk != KFAC_OK) return chk;
+    PrecSplitPlan pl;
+    if (!precondition_split_plan(items, count, pl)) return KFAC_ERR_ARG;
+    if (!ws_ok(prepared, prepared_bytes, pl.prep_bytes)) return KFAC_ERR_WORKSPACE;
+    return precondition_split_prepare(items, count, pl, prepared, static_cast<hipStream_t>(stream));
+}
+
+kfac_status kfac_precondition_grouped_f16x2_prepared(const kfac_precondition_item *items, int64_t count,
+                                                     const void *prepared, size_t prepared_bytes,
+                                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count == 0) return KFAC_OK;
+    const kfac_status chk = precondition_split_check(items, count, true);
+    if (chk != KFAC_OK) return chk;
+    PrecSplitPlan pl;
+    if (!precondition_split_plan(items, count, pl)) return KFAC_ERR_ARG;
+    if (!ws_ok(const_cast<void *>(prepared), prepared_bytes, pl.prep_bytes)) return KFAC_ERR_WORKSPACE;
+    if (!ws_ok(workspace, workspace_bytes, pl.ws_bytes)) return KFAC_ERR_WORKSPACE;
+    return precondition_split_run(items, count, pl, prepared, workspace, static_cast<hipStream_t>(stream));
+}
+
+kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items, int64_t count,
+                                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count == 0) return KFAC_OK;
+    const kfac_status chk = precondition_split_check(items, count, true);
+    if (chk != KFAC_OK) return chk;
+    PrecSplitPlan pl;
+    if (!precondition_split_plan(items, count, pl)) return KFAC_ERR_ARG;
+    const size_t prep = align_up(pl.prep_bytes, WS_ALIGN);
+    if (!ws_ok(workspace, workspace_bytes, prep + pl.ws_bytes)) return KFAC_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const kfac_status pre = precondition_split_prepare(items, count, pl, workspace, st);
+    if (pre != KFAC_OK) return pre;
+    return precondition_split_run(items, count, pl, workspace, static_cast<char *>(workspace) + prep, st);
 }
 
 kfac_status kfac_precondition(const float *b_inv, int64_t d_out, int64_t ldb,

@@ -237,7 +237,7 @@ struct Gemm2Problem {
 constexpr int GEMM2_MAX_PROBLEMS = 48;
 struct Gemm2Launch {
     Gemm2Problem p[GEMM2_MAX_PROBLEMS];
-    const unsigned *amax;
+    const unsigned *amax_a, *amax_b;  // the words of the A operands / of the B operands
     int count, total_tiles;
 };
 
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_split2_256_kernel(const Gemm2L
     __syncthreads();
     s3_pass_planes<S3_WAVE_FULL, true>(aa, ba, rba, rbb, pr.groups, m0, n0, lds_a, lds_b, acc);
 
-    const float sa = split2_scale(lp.amax[pr.amax_a]), sb = split2_scale(lp.amax[pr.amax_b]);
+    const float sa = split2_scale(lp.amax_a[pr.amax_a]), sb = split2_scale(lp.amax_b[pr.amax_b]);
     const float inv = (1.f / sa) * (1.f / sb);  // exact: powers of two
     float *__restrict__ C = pr.c;
     const size_t ldc = (size_t)pr.ldc;

@@ -79,6 +79,10 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.kfac_precondition_grouped_f16x2(None, 1, fake, 1 << 20, None) == ERR_ARG
     assert lib.kfac_precondition_grouped_f16x2(None, 0, None, 0, None) == 0
     assert lib.kfac_precondition_grouped_f16x2_workspace(None, 0) == 0
+    assert lib.kfac_precondition_f16x2_prepare(None, 1, fake, 1 << 20, None) == ERR_ARG
+    assert lib.kfac_precondition_grouped_f16x2_prepared(None, 1, fake, 1 << 20, fake, 1 << 20, None) == ERR_ARG
+    assert lib.kfac_precondition_f16x2_prepared_bytes(None, 0) == 0
+    assert lib.kfac_precondition_grouped_f16x2_prepared_workspace(None, 0) == 0
     # empty groups are fine
     assert lib.kfac_curvature_grouped(None, 0, 0, 1.0, 0.0, None, 0, None) == 0
     assert lib.kfac_invert_batched(None, 0, 0.1, None, 0, None) == 0

@@ -1150,3 +1150,29 @@ def test_f16x2_paths_can_be_captured_in_a_graph(k):
     # cancels 10^4-fold and no fp32 product is accurate to better than 5e-3 here, on either path; the accuracy
     # of the paths is the business of the tests above, this one is about replays)
     assert bool(torch.isfinite(p).all())
+
+
+def test_precondition_f16x2_with_prepared_inverses(k, oracle):
+    """The inverses' float16 planes made once (kfac_precondition_f16x2_prepare) and applied to two different
+    gradients give, bit for bit, what the one-call form gives; 45 layers (more than one group of launches)."""
+    shapes = [(1000, 1300), (700, 2100), (384, 520)] + [(130, 257), (65, 129), (257, 130)] * 14
+    rng = np.random.default_rng(6)
+    bs, as_ = [], []
+    for do, di in shapes:
+        b = rng.standard_normal((do, do)).astype(np.float32)
+        a = rng.standard_normal((di, di)).astype(np.float32)
+        bs.append(dev((b + b.T) / 2))
+        as_.append(dev((a + a.T) / 2))
+    prepared = k.PreparedInverses(bs, as_)
+    for trial in range(2):
+        gs = [dev(rng.standard_normal((do, di)).astype(np.float32) * np.float32(10.0 ** -trial)) for do, di in shapes]
+        o1 = [torch.full((do, di), 7.0, device="cuda") for do, di in shapes]
+        o2 = [torch.full((do, di), 8.0, device="cuda") for do, di in shapes]
+        prepared.precondition(gs, o1)
+        k.kfac_precondition_grouped(bs, as_, gs, o2, f16x2=True)
+        for x, y in zip(o1, o2):
+            assert torch.equal(x, y)
+        worst = max(oracle.rel_fro(host(o), oracle.precondition(host(b), host(g), host(a)))
+                    for b, a, g, o in list(zip(bs, as_, gs, o1))[:6])
+        print("  prepared inverses, trial %d: worst rel_fro %.2e" % (trial, worst), flush=True)
+        assert worst <= 2e-6
