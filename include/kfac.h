@@ -248,7 +248,8 @@ size_t kfac_precondition_grouped_workspace(const kfac_precondition_item *items, 
  * operands (G, B^-1; then T^T, A^-1) is scaled by a power of two from its largest magnitude and taken as two
  * float16 terms, each product as three f16 MFMA products, fp32 accumulation (see KFAC_F32_F16X2).  Same
  * arguments, results to the same tolerance; the workspace is larger (T^T, and 4 bytes per element of every
- * operand).  out must not alias the inputs.  Non-finite inputs give NaN. */
+ * operand).  out must not alias the inputs.  Non-finite inputs give NaN.  Errors as for
+ * kfac_precondition_grouped; KFAC_ERR_UNSUPPORTED for d_out or d_in above 2^26. */
 kfac_status kfac_precondition_grouped_f16x2(const kfac_precondition_item *items, int64_t count,
                                             void *workspace, size_t workspace_bytes, void *stream);
 size_t kfac_precondition_grouped_f16x2_workspace(const kfac_precondition_item *items, int64_t count);
@@ -259,7 +260,8 @@ size_t kfac_precondition_grouped_f16x2_workspace(const kfac_precondition_item *i
  * fills `prepared` (device memory of the caller, kfac_precondition_f16x2_prepared_bytes, 256-byte aligned);
  * kfac_precondition_grouped_f16x2_prepared then computes what kfac_precondition_grouped_f16x2 computes, bit for
  * bit, from `prepared` (made for the same items in the same order), grad and out; its workspace is smaller
- * (kfac_precondition_grouped_f16x2_prepared_workspace).  `prepared` is only read by it. */
+ * (kfac_precondition_grouped_f16x2_prepared_workspace).  `prepared` is only read by it.  KFAC_ERR_WORKSPACE also
+ * when `prepared` is null, not 256-byte aligned or smaller than kfac_precondition_f16x2_prepared_bytes says. */
 kfac_status kfac_precondition_f16x2_prepare(const kfac_precondition_item *items, int64_t count,
                                             void *prepared, size_t prepared_bytes, void *stream);
 size_t kfac_precondition_f16x2_prepared_bytes(const kfac_precondition_item *items, int64_t count);
